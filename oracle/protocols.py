@@ -1,0 +1,242 @@
+"""Two-party simulation of the paper's protocols on top of the C oracle.
+
+TEST INFRASTRUCTURE ONLY (see ``oracle/__init__.py``).
+
+Both parties live in one process; "sending" a value is handing the array to
+the other party's step.  Parties are 0-based here: party 1 is the paper's
+P_2, the one whose share carries the extra ``E F`` term of Eq. 1.
+
+Functions
+---------
+ttp_triple        trusted third party of Sec. 3.2: shares of (A, B, C = A B)
+pi_matmul         Pi_MatMul of Sec. 2.1 / 5.1 on explicit shares
+components        connected components of the bipartite graph of Sec. 5.1
+somm_literal      Protocol 2, step by step, for an arbitrary 0/1 matrix S
+simm_literal      Protocol 3, step by step, for an arbitrary 0/1 matrix S
+block_case        Protocols 2 / 3 when S keeps the same neuron blocks for every row
+Cost              counters of the cost model in the optimality appendix
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+import oracle as co
+
+
+@dataclass
+class Cost:
+    """Cost model of the optimality appendix, accumulated over Pi_MatMul calls.
+
+    ``vectors``: row vectors of X plus column vectors of Y that are masked and
+    sent, counted for both directions: C1 = 2(|X| + |Y|).
+    ``dot_products``: local dot products, C2 = 3 |X| |Y|.
+    ``opened_elems``: ring elements each party sends (|X| k + k |Y|).
+    ``scalar_mults``: scalar ring multiplications of the three local products.
+    """
+    vectors: int = 0
+    dot_products: int = 0
+    opened_elems: int = 0
+    scalar_mults: int = 0
+    calls: int = 0
+
+    def add(self, m: int, k: int, n: int) -> None:
+        self.vectors += 2 * (m + n)
+        self.dot_products += 3 * m * n
+        self.opened_elems += m * k + k * n
+        self.scalar_mults += 3 * m * k * n
+        self.calls += 1
+
+
+@dataclass
+class Triple:
+    a: Tuple[np.ndarray, np.ndarray]
+    b: Tuple[np.ndarray, np.ndarray]
+    c: Tuple[np.ndarray, np.ndarray]
+
+
+def ttp_triple(a: np.ndarray, b: np.ndarray, a_split: np.ndarray, b_split: np.ndarray,
+               c_split: np.ndarray) -> Triple:
+    """Beaver triple for one Pi_MatMul: C = A B (mod 2^64), all three shared."""
+    c = co.ring_matmul(a, b)
+    return Triple(co.share(a, a_split), co.share(b, b_split), co.share(c, c_split))
+
+
+def pi_matmul(x: Sequence[np.ndarray], y: Sequence[np.ndarray], t: Triple,
+              cost: Optional[Cost] = None, trace: Optional[Dict[str, np.ndarray]] = None):
+    """Pi_MatMul.  ``x``, ``y``: the two parties' shares.  Returns ``(Z_0, Z_1)``.
+
+    Each party masks its shares with its triple shares, the masked values are
+    exchanged and summed (opened), then Eq. 1 is evaluated locally.
+    """
+    d = [co.mask_share(x[i], t.a[i]) for i in (0, 1)]      # [E]_i = [X]_i - [A]_i
+    g = [co.mask_share(y[i], t.b[i]) for i in (0, 1)]      # [F]_i = [Y]_i - [B]_i
+    e = co.open_(d[0], d[1])
+    f = co.open_(g[0], g[1])
+    z = tuple(co.beaver_share(i, e, f, t.a[i], t.b[i], t.c[i]) for i in (0, 1))
+    if cost is not None:
+        cost.add(x[0].shape[0], x[0].shape[1], y[0].shape[1])
+    if trace is not None:
+        trace.update(d0=d[0], d1=d[1], g0=g[0], g1=g[1], e=e, f=f)
+    return z
+
+
+# ---------------------------------------------------------------------------
+# Protocol 2 (SOMM), general form
+# ---------------------------------------------------------------------------
+
+def components(s: np.ndarray) -> List[Tuple[np.ndarray, np.ndarray]]:
+    """Connected components of the bipartite graph whose left nodes are the
+    rows of X, right nodes the columns of Y and edges the ones of ``s``
+    (``m x n``).  Isolated nodes are dropped.  Depth-first search with an
+    explicit stack.  Each component is ``(sorted rows, sorted cols)``;
+    components are ordered by their smallest row."""
+    s = np.asarray(s) != 0
+    m, n = s.shape
+    seen_r = np.zeros(m, dtype=bool)
+    seen_c = np.zeros(n, dtype=bool)
+    out = []
+    for r0 in range(m):
+        if seen_r[r0] or not s[r0].any():
+            continue
+        rows, cols = [], []
+        stack = [("r", r0)]
+        seen_r[r0] = True
+        while stack:
+            side, v = stack.pop()
+            if side == "r":
+                rows.append(v)
+                for c in np.nonzero(s[v])[0]:
+                    if not seen_c[c]:
+                        seen_c[c] = True
+                        stack.append(("c", int(c)))
+            else:
+                cols.append(v)
+                for r in np.nonzero(s[:, v])[0]:
+                    if not seen_r[r]:
+                        seen_r[r] = True
+                        stack.append(("r", int(r)))
+        out.append((np.array(sorted(rows), dtype=np.int32), np.array(sorted(cols), dtype=np.int32)))
+    return out
+
+
+def somm_literal(x, y, s, a, b, a_split, b_split, c_split, cost: Optional[Cost] = None):
+    """Protocol 2.  ``x``, ``y``: share pairs (``m x k``, ``k x n``); ``s``: 0/1
+    ``m x n``.  Triple material ``a`` (m x k), ``b`` (k x n) and the splitting
+    randomness are given at full shape; the component on rows ``I_x`` and
+    columns ``I_y`` uses their restriction to ``I_x`` / ``I_y`` with
+    ``C = A[I_x] B[:, I_y]``.  Returns full-size ``m x n`` shares that are
+    zero outside the computed blocks (Merge)."""
+    m, n = np.asarray(s).shape
+    z = [np.zeros((m, n), dtype=np.uint64) for _ in (0, 1)]
+    for i_x, i_y in components(s):                                   # DFS, then one Pi_MatMul per component
+        xt = [co.index_rows(x[i], i_x, 1) for i in (0, 1)]            # IndexRows
+        yt = [co.index_cols(y[i], i_y, 1) for i in (0, 1)]            # IndexCols
+        t = ttp_triple(co.index_rows(a, i_x, 1), co.index_cols(b, i_y, 1),
+                       co.index_rows(a_split, i_x, 1), co.index_cols(b_split, i_y, 1),
+                       co.index_cols(co.index_rows(c_split, i_x, 1), i_y, 1))
+        r = pi_matmul(xt, yt, t, cost)                                # Pi_MatMul on the sub-matrices
+        for i in (0, 1):                                              # Merge
+            z[i][np.ix_(i_x, i_y)] = r[i]
+    return tuple(z)
+
+
+# ---------------------------------------------------------------------------
+# Protocol 3 (SIMM), general form
+# ---------------------------------------------------------------------------
+
+def simm_literal(x, y, s, a, b, a_split, b_split, c_split_cols, cost: Optional[Cost] = None):
+    """Protocol 3.  ``x``: shares of the ``m x k`` sparse-input matrix, ``s``:
+    its 0/1 sparsity distribution, ``y``: shares of ``k x p``.
+    ``c_split_cols[j]`` is the ``m x p`` randomness splitting the triple of
+    column ``j`` (rows outside ``R_j`` unused).  Returns ``m x p`` shares."""
+    s = np.asarray(s) != 0
+    m, k = s.shape
+    p = y[0].shape[1]
+    z = [np.zeros((m, p), dtype=np.uint64) for _ in (0, 1)]
+    pairs = []                                                        # non-zero columns j and their row sets R_j
+    for j in range(k):
+        r_j = np.nonzero(s[:, j])[0].astype(np.int32)
+        if len(r_j):
+            pairs.append((j, r_j))
+    for j, r_j in pairs:
+        jj = np.array([j], dtype=np.int32)
+        x2 = [co.index_rows(co.index_cols(x[i], jj, 1), r_j, 1) for i in (0, 1)]   # IndexCol, IndexRows
+        yj = [co.index_rows(y[i], jj, 1) for i in (0, 1)]                          # IndexRow
+        t = ttp_triple(co.index_rows(co.index_cols(a, jj, 1), r_j, 1), co.index_rows(b, jj, 1),
+                       co.index_rows(co.index_cols(a_split, jj, 1), r_j, 1),
+                       co.index_rows(b_split, jj, 1),
+                       co.index_rows(np.ascontiguousarray(c_split_cols[j]), r_j, 1))
+        r = pi_matmul(x2, yj, t, cost)                                # Pi_MatMul: an outer product
+        for i in (0, 1):                                              # Merge&Sum
+            z[i][r_j, :] += r[i]
+    return tuple(z)
+
+
+# ---------------------------------------------------------------------------
+# The hot path: whole column blocks kept for every row
+# ---------------------------------------------------------------------------
+
+@dataclass
+class BlockCase:
+    """Everything both parties hold for one block-sparse matmul, plus results."""
+    kind: str
+    m: int
+    k: int
+    n: int
+    bs: int
+    idx: np.ndarray
+    x: Tuple[np.ndarray, np.ndarray]            # full-size shares
+    y: Tuple[np.ndarray, np.ndarray]
+    a: Tuple[np.ndarray, np.ndarray]            # full-size triple shares
+    b: Tuple[np.ndarray, np.ndarray]
+    c: Tuple[np.ndarray, np.ndarray]            # compact: C = A_sel B_sel
+    d: Tuple[np.ndarray, np.ndarray] = None     # masked X-side shares (compact for simm)
+    g: Tuple[np.ndarray, np.ndarray] = None     # masked Y-side shares (compact)
+    e: np.ndarray = None
+    f: np.ndarray = None
+    z: Tuple[np.ndarray, np.ndarray] = None
+    cost: Cost = field(default_factory=Cost)
+
+
+def _sel(kind: str, x, y, idx, bs):
+    """IndexCols / IndexRows of Protocols 2 and 3 for block-granular index sets."""
+    if kind == "somm":
+        return x, co.index_cols(y, idx, bs)
+    return co.index_cols(x, idx, bs), co.index_rows(y, idx, bs)
+
+
+def block_case(kind: str, x_sh, y_sh, mask: np.ndarray, bs: int, a: np.ndarray, b: np.ndarray,
+               a_split: np.ndarray, b_split: np.ndarray, c_split: np.ndarray,
+               with_result: bool = True) -> BlockCase:
+    """Run SOMM (``kind="somm"``) or SIMM (``kind="simm"``) when the sparsity
+    distribution keeps the same neuron blocks for every token: a single
+    Pi_MatMul on the indexed sub-matrices.
+
+    ``mask``: per-token block flags ``[n_tok, nb]``; the union over tokens is
+    kept.  Triple parts ``a``, ``b`` are full-shape draws; the TTP forms the
+    triple on their indexed restriction, ``C = A_sel B_sel``, split with
+    ``c_split`` (already of the compact output shape)."""
+    idx = co.compact_mask(mask)
+    m, k = x_sh[0].shape
+    n = y_sh[0].shape[1]
+    a_sel, b_sel = _sel(kind, a, b, idx, bs)
+    as_sel, bs_sel = _sel(kind, a_split, b_split, idx, bs)
+    a_sh = co.share(a, a_split)
+    b_sh = co.share(b, b_split)
+    case = BlockCase(kind, m, k, n, bs, idx, tuple(x_sh), tuple(y_sh), a_sh, b_sh, None)
+    c = co.ring_matmul(a_sel, b_sel)
+    case.c = co.share(c, c_split)
+    xs = [_sel(kind, x_sh[i], y_sh[i], idx, bs) for i in (0, 1)]
+    t = Triple(co.share(a_sel, as_sel), co.share(b_sel, bs_sel), case.c)
+    # the indexed restriction of a full-size share pair is the share pair of the restriction
+    assert np.array_equal(t.a[1], _sel(kind, a_sh[1], b_sh[1], idx, bs)[0])
+    if with_result:
+        trace: Dict[str, np.ndarray] = {}
+        case.z = pi_matmul([xs[0][0], xs[1][0]], [xs[0][1], xs[1][1]], t, case.cost, trace)
+        case.d = (trace["d0"], trace["d1"])
+        case.g = (trace["g0"], trace["g1"])
+        case.e, case.f = trace["e"], trace["f"]
+    return case

@@ -1,0 +1,257 @@
+"""Pins for the oracle's protocol layer (Pi_MatMul, Protocols 2 and 3).
+
+What fixes the expected values here is the mathematics of the paper, never the
+oracle itself: the reconstruction identity of Eq. 1 against a plaintext ring
+product formed from the *unshared* secrets, the all-ones mask collapsing to a
+dense product, the step-by-step protocols agreeing with the single indexed
+Pi_MatMul, the cost model of the optimality appendix, the float64 product of
+the dequantised secrets, and a communication figure printed in the paper.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import oracle as co
+from oracle import cases, protocols
+from workloads import configs, rng
+
+M64 = (1 << 64) - 1
+
+
+def u64(seed, stream, *shape):
+    return rng.uniform_u64(seed, stream, int(np.prod(shape))).reshape(shape)
+
+
+def small_q(seed, stream, *shape):
+    """Signed fixed-point-like secrets of about 20 bits, as two's complement."""
+    return co.encode(rng.gaussian_f64(seed, stream, int(np.prod(shape))).reshape(shape), 16)
+
+
+def plain_product(kind, xq, yq, idx, bs):
+    """Plaintext ring product on the kept positions, from the unshared secrets,
+    with numpy's integer matmul (wraps mod 2^64) and numpy fancy indexing."""
+    cols = (np.asarray(idx, dtype=np.int64)[:, None] * bs + np.arange(bs)[None, :]).ravel()
+    if kind == "somm":
+        return xq @ yq[:, cols]
+    return xq[:, cols] @ yq[cols, :]
+
+
+@pytest.mark.parametrize("cid", [1, 2])
+def test_reconstruction_identity_on_configs(cid):
+    cfg = configs.config(cid)
+    for mm in cfg.matmuls:
+        case, plain = cases.build(cfg, mm)
+        z = co.reconstruct(*case.z)
+        assert np.array_equal(z, plain_product(mm.kind, plain["xq"], plain["yq"], case.idx, cfg.bs))
+        # the opened values are what Eq. 1 says they are: E = X - A on the indexed operands
+        if mm.kind == "somm":
+            assert np.array_equal(case.e, case.x[0] + case.x[1] - case.a[0] - case.a[1])
+        # shares really are shares: neither equals the result on its own
+        assert not np.array_equal(case.z[0], z) and not np.array_equal(case.z[1], z)
+
+
+def test_reconstruction_tiny_bigint():
+    # bs = 1, tiny shapes, Python integers
+    m, k, n = 3, 4, 5
+    xq, yq = small_q(21, 1, m, k), small_q(21, 2, k, n)
+    mask = np.array([[1, 0, 1, 1, 0]], dtype=np.uint8)
+    case = protocols.block_case("somm", co.share(xq, u64(21, 3, m, k)), co.share(yq, u64(21, 4, k, n)),
+                                mask, 1, u64(21, 5, m, k), u64(21, 6, k, n), u64(21, 7, m, k),
+                                u64(21, 8, k, n), u64(21, 9, m, 3))
+    kept = [0, 2, 3]
+    for i in range(m):
+        for c, j in enumerate(kept):
+            want = sum(int(xq[i, l]) * int(yq[l, j]) for l in range(k)) & M64
+            assert (int(case.z[0][i, c]) + int(case.z[1][i, c])) & M64 == want
+    # SIMM: contraction over kept neurons only
+    mask = np.array([[0, 1, 1, 0]], dtype=np.uint8)
+    case = protocols.block_case("simm", co.share(xq, u64(21, 3, m, k)), co.share(yq, u64(21, 4, k, n)),
+                                mask, 1, u64(21, 5, m, k), u64(21, 6, k, n), u64(21, 7, m, k),
+                                u64(21, 8, k, n), u64(21, 9, m, n))
+    for i in range(m):
+        for j in range(n):
+            want = sum(int(xq[i, l]) * int(yq[l, j]) for l in (1, 2)) & M64
+            assert (int(case.z[0][i, j]) + int(case.z[1][i, j])) & M64 == want
+
+
+@pytest.mark.parametrize("kind", ["somm", "simm"])
+def test_all_ones_mask_is_dense_product(kind):
+    m, k, n, bs = 5, 8, 12, 4
+    xq, yq = small_q(22, 1, m, k), small_q(22, 2, k, n)
+    nb = (n if kind == "somm" else k) // bs
+    mask = np.ones((1, nb), dtype=np.uint8)
+    case = protocols.block_case(kind, co.share(xq, u64(22, 3, m, k)), co.share(yq, u64(22, 4, k, n)),
+                                mask, bs, u64(22, 5, m, k), u64(22, 6, k, n), u64(22, 7, m, k),
+                                u64(22, 8, k, n), u64(22, 9, m, n))
+    assert np.array_equal(co.reconstruct(*case.z), xq @ yq)
+    # and the triple is the dense one: C_0 + C_1 = A B
+    assert np.array_equal(co.reconstruct(*case.c),
+                          co.reconstruct(*case.a) @ co.reconstruct(*case.b))
+
+
+def test_components_against_union_find():
+    for seed in range(12):
+        m, n = 2 + seed % 5, 3 + seed % 7
+        s = (u64(seed, 30, m, n) % np.uint64(4) == 0).astype(np.uint8)
+        comps = protocols.components(s)
+        parent = list(range(m + n))
+
+        def find(v):
+            while parent[v] != v:
+                parent[v] = parent[parent[v]]
+                v = parent[v]
+            return v
+        for i in range(m):
+            for j in range(n):
+                if s[i, j]:
+                    parent[find(i)] = find(m + j)
+        groups = {}
+        for i in range(m):
+            if s[i].any():
+                groups.setdefault(find(i), (set(), set()))[0].add(i)
+        for j in range(n):
+            if s[:, j].any():
+                groups.setdefault(find(m + j), (set(), set()))[1].add(j)
+        want = sorted((sorted(r), sorted(c)) for r, c in groups.values())
+        got = sorted((r.tolist(), c.tolist()) for r, c in comps)
+        assert got == want
+    # the figure's situation: two rows sharing a column form one component
+    s = np.array([[1, 0, 0], [1, 0, 0], [0, 0, 1]], dtype=np.uint8)
+    got = [(r.tolist(), c.tolist()) for r, c in protocols.components(s)]
+    assert got == [([0, 1], [0]), ([2], [2])]
+
+
+def test_somm_literal_general_mask():
+    m, k, n = 4, 3, 6
+    xq, yq = small_q(23, 1, m, k), small_q(23, 2, k, n)
+    s = np.array([[1, 1, 0, 0, 0, 0],
+                  [0, 1, 0, 0, 0, 0],
+                  [0, 0, 0, 1, 0, 1],
+                  [0, 0, 0, 0, 0, 0]], dtype=np.uint8)
+    cost = protocols.Cost()
+    z = protocols.somm_literal(co.share(xq, u64(23, 3, m, k)), co.share(yq, u64(23, 4, k, n)), s,
+                               u64(23, 5, m, k), u64(23, 6, k, n), u64(23, 7, m, k),
+                               u64(23, 8, k, n), u64(23, 9, m, n), cost)
+    full = xq @ yq
+    rec = co.reconstruct(*z)
+    assert np.array_equal(rec[s != 0], full[s != 0])          # every wanted output is right
+    # blocks: rows {0,1} x cols {0,1}, rows {2} x cols {3,5}; nothing else is computed
+    block = np.zeros_like(s)
+    block[np.ix_([0, 1], [0, 1])] = 1
+    block[np.ix_([2], [3, 5])] = 1
+    assert np.array_equal(rec[block == 0], np.zeros(int((block == 0).sum()), np.uint64))
+    assert np.array_equal(rec[block != 0], full[block != 0])
+    # cost model: C1 = 2(|X|+|Y|) and C2 = 3|X||Y| summed over the two components
+    assert cost.calls == 2
+    assert cost.vectors == 2 * (2 + 2) + 2 * (1 + 2)
+    assert cost.dot_products == 3 * 2 * 2 + 3 * 1 * 2
+
+
+def test_somm_literal_equals_block_form_on_column_masks():
+    m, k, n, bs = 6, 5, 12, 2
+    xq, yq = small_q(24, 1, m, k), small_q(24, 2, k, n)
+    mask = np.array([[1, 0, 0, 1, 1, 0]], dtype=np.uint8)
+    args = (u64(24, 5, m, k), u64(24, 6, k, n), u64(24, 7, m, k), u64(24, 8, k, n))
+    x_sh, y_sh = co.share(xq, u64(24, 3, m, k)), co.share(yq, u64(24, 4, k, n))
+    c_split_full = u64(24, 9, m, n)
+    s = np.repeat(np.repeat(mask, bs, axis=1), m, axis=0)
+    comps = protocols.components(s)
+    assert len(comps) == 1 and comps[0][0].tolist() == list(range(m))     # a single component
+    lit = protocols.somm_literal(x_sh, y_sh, s, *args, c_split_full)
+    idx = co.compact_mask(mask)
+    case = protocols.block_case("somm", x_sh, y_sh, mask, bs, *args,
+                                co.index_cols(c_split_full, idx, bs))
+    for i in (0, 1):
+        assert np.array_equal(co.index_cols(lit[i], idx, bs), case.z[i])   # share by share
+
+
+def test_simm_literal_equals_block_form_on_column_masks():
+    m, k, p, bs = 4, 8, 5, 2
+    xq, yq = small_q(25, 1, m, k), small_q(25, 2, k, p)
+    mask = np.array([[0, 1, 1, 0]], dtype=np.uint8)
+    args = (u64(25, 5, m, k), u64(25, 6, k, p), u64(25, 7, m, k), u64(25, 8, k, p))
+    x_sh, y_sh = co.share(xq, u64(25, 3, m, k)), co.share(yq, u64(25, 4, k, p))
+    s = np.repeat(np.repeat(mask, bs, axis=1), m, axis=0)
+    c_cols = [u64(25, 100 + j, m, p) for j in range(k)]
+    cost = protocols.Cost()
+    lit = protocols.simm_literal(x_sh, y_sh, s, *args, c_cols, cost)
+    kept = [2, 3, 4, 5]
+    c0 = np.zeros((m, p), np.uint64)
+    for j in kept:
+        c0 = c0 + c_cols[j]                      # Merge&Sum of the per-column triples' shares
+    case = protocols.block_case("simm", x_sh, y_sh, mask, bs, *args, c0)
+    for i in (0, 1):
+        assert np.array_equal(lit[i], case.z[i])
+    assert np.array_equal(co.reconstruct(*lit), xq[:, kept] @ yq[kept, :])
+    # N p scalar multiplications per local product (N = non-zeros of X), three products
+    assert cost.scalar_mults == 3 * (m * len(kept)) * p
+
+
+def test_simm_literal_ragged_row_sets():
+    m, k, p = 4, 3, 2
+    xq, yq = small_q(26, 1, m, k), small_q(26, 2, k, p)
+    s = np.array([[1, 0, 0], [0, 0, 1], [1, 0, 1], [0, 0, 0]], dtype=np.uint8)
+    lit = protocols.simm_literal(co.share(xq, u64(26, 3, m, k)), co.share(yq, u64(26, 4, k, p)), s,
+                                 u64(26, 5, m, k), u64(26, 6, k, p), u64(26, 7, m, k),
+                                 u64(26, 8, k, p), [u64(26, 100 + j, m, p) for j in range(k)])
+    xs = np.where(s != 0, xq, np.uint64(0))
+    assert np.array_equal(co.reconstruct(*lit), xs @ yq)
+
+
+def test_cost_counters_on_config():
+    cfg = configs.config(1)
+    for mm in cfg.matmuls:
+        case, _ = cases.build(cfg, mm)
+        n_act = len(case.idx) * cfg.bs
+        if mm.kind == "somm":
+            assert case.cost.opened_elems == mm.m * mm.k + mm.k * n_act
+            assert case.cost.dot_products == 3 * mm.m * n_act
+            assert case.cost.scalar_mults == 3 * mm.m * mm.k * n_act
+        else:
+            assert case.cost.opened_elems == mm.m * n_act + n_act * mm.n
+            assert case.cost.scalar_mults == 3 * mm.m * n_act * mm.n
+
+
+def test_paper_communication_reduction(golden_dir):
+    vals = {}
+    with open(os.path.join(golden_dir, "comm_reduction.txt")) as fh:
+        for line in fh:
+            if not line.startswith("#") and line.strip():
+                k, v = line.split()
+                vals[k] = float(v)
+    m, k, n = int(vals["m"]), int(vals["k"]), int(vals["n"])
+    dense, sparse = protocols.Cost(), protocols.Cost()
+    dense.add(m, k, n)
+    sparse.add(m, k, int(round(vals["density"] * n)))
+    ratio = dense.opened_elems / sparse.opened_elems
+    assert abs(ratio / ((m * k + k * n) / (m * k + k * vals["density"] * n)) - 1.0) < 1e-3
+    assert abs(ratio - vals["paper_reduction_at_90pct"]) / vals["paper_reduction_at_90pct"] < 0.05
+
+
+@pytest.mark.parametrize("cid", [1, 2])
+def test_fixed_point_decode_vs_float64(cid):
+    cfg = configs.config(cid)
+    for mm in cfg.matmuls:
+        case, plain = cases.build(cfg, mm)
+        got = co.decode(co.reconstruct(*case.z), 32)
+        cols = (case.idx.astype(np.int64)[:, None] * cfg.bs + np.arange(cfg.bs)[None, :]).ravel()
+        xd, yd = co.decode(plain["xq"], 16), co.decode(plain["yq"], 16)
+        if mm.kind == "somm":
+            deq, raw = xd @ yd[:, cols], plain["x"] @ plain["y"][:, cols]
+        else:
+            deq, raw = xd[:, cols] @ yd[cols, :], plain["x"][:, cols] @ plain["y"][cols, :]
+        assert np.max(np.abs(got - deq)) < 1e-9           # exact up to float64 summation error
+        if cid == 1:
+            assert np.max(np.abs(got - raw)) < 2.0 ** -10  # quantisation error at K = 64
+
+
+def test_shares_look_uniform():
+    cfg = configs.config(2)
+    case, _ = cases.build(cfg, cfg.matmuls[0])
+    for arr in (case.d[0], case.e, case.f, case.z[0], case.z[1]):
+        top = (arr.ravel() >> np.uint64(56)).astype(np.int64)
+        counts = np.bincount(top, minlength=256)
+        expect = top.size / 256.0
+        chi2 = float(((counts - expect) ** 2 / expect).sum())
+        assert chi2 < 400.0        # 255 dof: mean 255, sd 22.6
