@@ -1,0 +1,181 @@
+/*
+ * comet_ring.h -- C ABI of the MI355X (gfx950) library for one party's local
+ * work in the sparse, secret-shared FFN matrix multiply over the ring Z_{2^64}.
+ *
+ * Notation follows the paper's Sec. 5: Z = X Y with X (m x k) the activations
+ * and Y (k x n) the weights, additively shared between two parties
+ * (Sec. 2.1).  "party" is 0-based: party 0 is the paper's P_1, party 1 is
+ * P_2, the one whose share carries the extra E F term of Eq. 1.
+ *
+ * Conventions that hold for every call unless stated otherwise
+ *   - every matrix / vector pointer is a DEVICE pointer owned by the caller,
+ *     16-byte aligned, dense row-major, elements are uint64_t taken mod 2^64;
+ *   - the library never allocates or frees device memory and never frees or
+ *     retains caller memory; scratch space comes in through (ws, ws_bytes),
+ *     sized with comet_workspace_bytes(), and may be reused between calls;
+ *   - calls enqueue work on the context's stream and return without waiting;
+ *     buffers must stay valid until that work has run;
+ *   - the predicted sparsity distribution is a plaintext list of active
+ *     blocks of `bs` consecutive neurons: blk_idx[0 .. n_blk) ascending block
+ *     ids on the device, with the count n_blk itself on the device
+ *     (n_blk_dev, one int32) so that compaction and the matmul chain without
+ *     a host round trip.  n_blk_cap is a host-side upper bound on n_blk (the
+ *     sparsity LEVEL is public in the paper's threat model, Sec. 3.2); it
+ *     fixes the leading dimension of every compact operand,
+ *     ld = n_blk_cap * bs.  n_blk_dev may be NULL, meaning n_blk = n_blk_cap.
+ *     Columns / rows of compact operands at or beyond n_blk * bs are neither
+ *     read nor written;
+ *   - return value 0 on success, a negative COMET_E* code otherwise;
+ *     comet_last_error() gives a text for the last failure on that context.
+ *     Argument errors are detected on the host before anything is enqueued.
+ *     No C++ types or exceptions cross this boundary.
+ */
+#ifndef COMET_RING_H
+#define COMET_RING_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct comet_ctx comet_ctx;
+
+enum {
+    COMET_OK = 0,
+    COMET_EINVAL = -1,     /* null pointer, negative or inconsistent size, bad enum      */
+    COMET_EALIGN = -2,     /* a pointer is not 16-byte aligned                           */
+    COMET_ECAP = -3,       /* size beyond what the kernels index (see each call)         */
+    COMET_EDEVICE = -4,    /* no such device / wrong architecture / HIP runtime failure  */
+    COMET_EWORKSPACE = -5  /* ws is NULL or smaller than comet_workspace_bytes() says    */
+};
+
+/* which axis of a full-size matrix the block list selects */
+enum { COMET_AXIS_COLS = 0, COMET_AXIS_ROWS = 1 };
+
+/* operations known to comet_workspace_bytes() */
+enum { COMET_OP_COMPACT = 0, COMET_OP_SOMM = 1, COMET_OP_SIMM = 2 };
+
+/* flags of the share calls: the named triple share is passed at FULL size and
+ * is indexed by blk_idx inside the kernel (otherwise it is already compact) */
+enum { COMET_FULL_A = 1, COMET_FULL_B = 2 };
+
+/* ---- context ---------------------------------------------------------- */
+
+/* Create a context bound to HIP device `device_id` (must be a gfx950 part).
+ * Allocates host memory only.  The context starts on the NULL stream. */
+int comet_create(comet_ctx** out, int device_id);
+int comet_destroy(comet_ctx* ctx);
+/* hip_stream: a hipStream_t (NULL = default stream).  Not owned. */
+int comet_set_stream(comet_ctx* ctx, void* hip_stream);
+const char* comet_last_error(const comet_ctx* ctx);
+/* Library version string, static storage. */
+const char* comet_version(void);
+
+/* Bytes of scratch the operation needs for the given sizes.
+ *   COMET_OP_COMPACT: m = n_tok, k unused, n = nb, bs unused
+ *   COMET_OP_SOMM   : m, k, n = n_blk_cap * bs (compact width), bs
+ *   COMET_OP_SIMM   : m, k = n_blk_cap * bs (compact contraction), n, bs
+ * Returns 0 for sizes the operation would reject. */
+size_t comet_workspace_bytes(int op, int64_t m, int64_t k, int64_t n, int bs);
+
+/* ---- (1) mask and open shares: Sec. 2.1 multiplication, Sec. 5.1 -------- */
+
+/* [D]_i = [X]_i - [A]_i, elementwise over n_elems words: the masked share a
+ * party sends to the other one.  d_i may alias x_i or a_i. */
+int comet_mask_share(comet_ctx* ctx, const uint64_t* x_i, const uint64_t* a_i,
+                     uint64_t* d_i, size_t n_elems);
+
+/* Indexed variant: masks only what the sparsity distribution keeps, which is
+ * where the protocol's communication saving comes from (Protocol 2: IndexCols
+ * before Pi_MatMul; Protocol 3: IndexCol / IndexRow before Pi_MatMul).
+ * w_i, b_i: full rows x cols.
+ *   axis = COMET_AXIS_COLS: g_i is rows x ld, g[r][c] = w[r][j] - b[r][j],
+ *                           j = blk_idx[c / bs] * bs + c % bs, c < n_blk * bs
+ *   axis = COMET_AXIS_ROWS: g_i is ld x cols, g[r][c] = w[j][c] - b[j][c],
+ *                           j = blk_idx[r / bs] * bs + r % bs, r < n_blk * bs
+ * Block ids should satisfy (blk_idx[t] + 1) * bs <= cols (resp. rows); a block
+ * whose id does not fit is skipped (its outputs are left untouched). */
+int comet_mask_share_gather(comet_ctx* ctx, const uint64_t* w_i, const uint64_t* b_i,
+                            uint64_t* g_i, int64_t rows, int64_t cols, int axis, int bs,
+                            const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap);
+
+/* E = [D]_0 + [D]_1: reconstruction of the masked value after the exchange
+ * (both parties live in one process here, so the exchange is this add).
+ * e may alias d_0 or d_1. */
+int comet_open(comet_ctx* ctx, const uint64_t* d_0, const uint64_t* d_1, uint64_t* e,
+               size_t n_elems);
+
+/* ---- (2) sparsity distribution -> ordered index list -------------------- */
+
+/* mask: n_tok x nb bytes, non-zero = block predicted active for that token
+ * (any alignment).  The masks of all tokens are OR-ed (one matmul serves the
+ * whole batch), then blk_idx[0 .. T) receives the ascending ids of the active
+ * blocks and *n_blk_dev = T.  blk_idx must hold nb int32 (4-byte aligned);
+ * entries at or beyond T are left untouched.  1 <= n_tok, 0 <= nb < 2^31 - 2^16.
+ * This is the local, communication-free step that Protocol 2 starts with (its
+ * graph search degenerates to this when every token keeps the same blocks) and
+ * the "find all non-zero columns" step of Protocol 3. */
+int comet_compact_mask(comet_ctx* ctx, const uint8_t* mask, int64_t n_tok, int64_t nb,
+                       int32_t* blk_idx, int32_t* n_blk_dev, void* ws, size_t ws_bytes);
+
+/* ---- (3) one party's output share: Eq. 1 in matrix form ----------------- */
+
+/* SOMM (Protocol 2, preceding layer: FC1 / gate / up), restricted to the kept
+ * output columns:
+ *     [Z]_i = [C]_i + E [B]_i + [A]_i F + party * E F        (mod 2^64)
+ *   E, A_i : m x k
+ *   F      : k x ld   (compact: opened masked weights of the kept columns)
+ *   B_i    : k x n_full when flags & COMET_FULL_B (kept columns are indexed in
+ *            the kernel), else k x ld
+ *   C_i,Z_i: m x ld   (compact; C = A B on the kept columns)
+ * ld = n_blk_cap * bs; column c of a compact operand is neuron
+ * blk_idx[c / bs] * bs + c % bs.  Z_i must not alias any input.
+ * Limits: 1 <= m, k, bs; m, k, ld, n_full < 2^24. */
+int comet_somm_share(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_full, int bs,
+                     const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap, int flags,
+                     const uint64_t* E, const uint64_t* F, const uint64_t* A_i,
+                     const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i,
+                     void* ws, size_t ws_bytes);
+
+/* SIMM (Protocol 3, subsequent layer: FC2 / down), contraction restricted to
+ * the kept neurons (the sum of the per-neuron outer products of Protocol 3):
+ *     [Z]_i = [C]_i + E [B]_i + [A]_i F + party * E F        (mod 2^64)
+ *   E      : m x ld   (compact: opened masked activations of the kept neurons)
+ *   A_i    : m x k_full when flags & COMET_FULL_A, else m x ld
+ *   F      : ld x n   (compact: opened masked weight rows of the kept neurons)
+ *   B_i    : k_full x n when flags & COMET_FULL_B, else ld x n
+ *   C_i,Z_i: m x n    (C = A_sel B_sel)
+ * ld = n_blk_cap * bs; only the first n_blk * bs columns of E / rows of F are
+ * contracted.  Z_i must not alias any input.
+ * Limits: 1 <= m, n, bs; m, n, ld, k_full < 2^24. */
+int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64_t n, int bs,
+                     const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap, int flags,
+                     const uint64_t* E, const uint64_t* F, const uint64_t* A_i,
+                     const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i,
+                     void* ws, size_t ws_bytes);
+
+/* ---- measurement aids (roofline probes; not part of the protocol) ------- */
+
+/* Launch-shape overrides for sweeps and for tests that must reach a particular
+ * code path.  Results never depend on them.  value 0 restores the default.
+ *   COMET_TUNE_GEMM_GRID: number of workgroups the share calls launch
+ *                         (default: one per compute unit, fewer for tiny work) */
+enum { COMET_TUNE_GEMM_GRID = 0 };
+int comet_set_tuning(comet_ctx* ctx, int key, int value);
+
+/* Register-resident issue loop of the int8 matrix instruction the ring GEMM
+ * uses: launches `blocks` x 256 threads, `iters` dependent-free MFMA groups
+ * each.  out (device, blocks*256 int32) keeps the results alive.  Returns the
+ * number of int8 multiply-accumulates issued through *macs (host). */
+int comet_probe_mfma_i8(comet_ctx* ctx, int blocks, int iters, int32_t* out, double* macs);
+/* Same for the plain 64-bit vector multiply-add: *macs = ring MACs issued. */
+int comet_probe_valu_mac64(comet_ctx* ctx, int blocks, int iters, uint64_t* out, double* macs);
+/* Plain device copy of n_elems words (bandwidth yardstick, 16 B per element). */
+int comet_probe_copy(comet_ctx* ctx, const uint64_t* src, uint64_t* dst, size_t n_elems);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMET_RING_H */

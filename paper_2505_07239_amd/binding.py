@@ -1,0 +1,231 @@
+"""Thin ctypes binding of ``libcomet_ring.so`` (see ``include/comet_ring.h``).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  Tensors are ``torch.int64`` CUDA(-HIP) tensors whose bits are the
+ring elements mod 2^64; torch is used for device memory and streams, nothing
+else.  There is no CPU fallback: if the library is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcomet_ring.so")
+
+AXIS_COLS, AXIS_ROWS = 0, 1
+OP_COMPACT, OP_SOMM, OP_SIMM = 0, 1, 2
+FULL_A, FULL_B = 1, 2
+TUNE_GEMM_GRID = 0
+
+EXPORTS = [
+    "comet_create", "comet_destroy", "comet_set_stream", "comet_last_error", "comet_version",
+    "comet_workspace_bytes", "comet_mask_share", "comet_mask_share_gather", "comet_open",
+    "comet_compact_mask", "comet_somm_share", "comet_simm_share",
+    "comet_set_tuning", "comet_probe_mfma_i8", "comet_probe_valu_mac64", "comet_probe_copy",
+]
+
+_lib = None
+
+
+class CometError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("comet_ring error %d: %s" % (code, msg))
+        self.code = code
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen the in-tree library (build it first with ``paper_2505_07239_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s not found: run `python -m paper_2505_07239_amd.build` (needs hipcc)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+    lib.comet_create.argtypes = [ctypes.POINTER(vp), i32]
+    lib.comet_destroy.argtypes = [vp]
+    lib.comet_set_stream.argtypes = [vp, vp]
+    lib.comet_last_error.argtypes = [vp]
+    lib.comet_last_error.restype = ctypes.c_char_p
+    lib.comet_version.restype = ctypes.c_char_p
+    lib.comet_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
+    lib.comet_workspace_bytes.restype = sz
+    lib.comet_mask_share.argtypes = [vp, vp, vp, vp, sz]
+    lib.comet_open.argtypes = [vp, vp, vp, vp, sz]
+    lib.comet_mask_share_gather.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, i32]
+    lib.comet_compact_mask.argtypes = [vp, vp, i64, i64, vp, vp, vp, sz]
+    share = [vp, i32, i64, i64, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz]
+    lib.comet_somm_share.argtypes = share
+    lib.comet_simm_share.argtypes = share
+    lib.comet_probe_mfma_i8.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.comet_probe_valu_mac64.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.comet_probe_copy.argtypes = [vp, vp, vp, sz]
+    lib.comet_set_tuning.argtypes = [vp, i32, i32]
+    _lib = lib
+    return lib
+
+
+def workspace_bytes(op: int, m: int, k: int, n: int, bs: int) -> int:
+    return int(load_library().comet_workspace_bytes(op, m, k, n, bs))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _words(t: torch.Tensor, what: str) -> torch.Tensor:
+    if t.dtype != torch.int64 or not t.is_cuda or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous int64 tensor on the GPU" % what)
+    return t
+
+
+class Context:
+    """One library context on one device; calls run on torch's current stream."""
+
+    def __init__(self, device: int = 0):
+        self.lib = load_library()
+        self.device = device
+        h = ctypes.c_void_p()
+        rc = self.lib.comet_create(ctypes.byref(h), device)
+        if rc != 0:
+            raise CometError(rc, "comet_create failed (is device %d an MI355X?)" % device)
+        self.h = h
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.comet_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != 0:
+            raise CometError(rc, self.lib.comet_last_error(self.h).decode())
+
+    def _sync_stream(self):
+        s = torch.cuda.current_stream(self.device).cuda_stream
+        self._check(self.lib.comet_set_stream(self.h, ctypes.c_void_p(s)))
+
+    def workspace(self, nbytes: int) -> Optional[torch.Tensor]:
+        """A cached device buffer of at least ``nbytes`` (torch allocation, 256-byte aligned)."""
+        if nbytes == 0:
+            return None
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda:%d" % self.device)
+        return self._ws
+
+    # ---- (1) mask / open ----
+    def mask_share(self, x_i, a_i, out=None):
+        _words(x_i, "x_i"), _words(a_i, "a_i")
+        out = torch.empty_like(x_i) if out is None else _words(out, "out")
+        self._sync_stream()
+        self._check(self.lib.comet_mask_share(self.h, _ptr(x_i), _ptr(a_i), _ptr(out), x_i.numel()))
+        return out
+
+    def open(self, d_0, d_1, out=None):
+        _words(d_0, "d_0"), _words(d_1, "d_1")
+        out = torch.empty_like(d_0) if out is None else _words(out, "out")
+        self._sync_stream()
+        self._check(self.lib.comet_open(self.h, _ptr(d_0), _ptr(d_1), _ptr(out), d_0.numel()))
+        return out
+
+    def mask_share_gather(self, w_i, b_i, axis, bs, blk_idx, n_blk_dev, n_blk_cap, out=None):
+        _words(w_i, "w_i"), _words(b_i, "b_i")
+        rows, cols = w_i.shape
+        ld = n_blk_cap * bs
+        shape = (rows, ld) if axis == AXIS_COLS else (ld, cols)
+        out = torch.empty(shape, dtype=torch.int64, device=w_i.device) if out is None else _words(out, "out")
+        self._sync_stream()
+        self._check(self.lib.comet_mask_share_gather(self.h, _ptr(w_i), _ptr(b_i), _ptr(out), rows,
+                                                     cols, axis, bs, _ptr(blk_idx), _ptr(n_blk_dev),
+                                                     n_blk_cap))
+        return out
+
+    # ---- (2) compact ----
+    def compact_mask(self, mask, blk_idx=None, n_blk_dev=None):
+        if mask.dtype != torch.uint8 or not mask.is_cuda or not mask.is_contiguous():
+            raise TypeError("mask must be a contiguous uint8 tensor on the GPU")
+        if mask.dim() == 1:
+            mask = mask[None, :]
+        n_tok, nb = mask.shape
+        if blk_idx is None:
+            blk_idx = torch.empty(max(nb, 1), dtype=torch.int32, device=mask.device)
+        if n_blk_dev is None:
+            n_blk_dev = torch.empty(1, dtype=torch.int32, device=mask.device)
+        need = workspace_bytes(OP_COMPACT, n_tok, 0, nb, 0)
+        ws = self.workspace(need)
+        self._sync_stream()
+        self._check(self.lib.comet_compact_mask(self.h, _ptr(mask), n_tok, nb, _ptr(blk_idx),
+                                                _ptr(n_blk_dev), _ptr(ws), need))
+        return blk_idx, n_blk_dev
+
+    # ---- (3) output share ----
+    def somm_share(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, e, f, a_i, b_i, c_i,
+                   b_full=True, out=None):
+        for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
+            _words(t, nm)
+        m, k = e.shape
+        n_full = b_i.shape[1] if b_full else 0
+        ld = n_blk_cap * bs
+        out = torch.empty((m, ld), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        need = workspace_bytes(OP_SOMM, m, k, ld, bs)
+        ws = self.workspace(need)
+        self._sync_stream()
+        self._check(self.lib.comet_somm_share(self.h, party, m, k, n_full, bs, _ptr(blk_idx),
+                                              _ptr(n_blk_dev), n_blk_cap, FULL_B if b_full else 0,
+                                              _ptr(e), _ptr(f), _ptr(a_i), _ptr(b_i), _ptr(c_i),
+                                              _ptr(out), _ptr(ws), need))
+        return out
+
+    def simm_share(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, e, f, a_i, b_i, c_i,
+                   a_full=True, b_full=True, out=None):
+        for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
+            _words(t, nm)
+        m = e.shape[0]
+        n = f.shape[1]
+        ld = n_blk_cap * bs
+        k_full = a_i.shape[1] if a_full else (b_i.shape[0] if b_full else 0)
+        out = torch.empty((m, n), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        need = workspace_bytes(OP_SIMM, m, ld, n, bs)
+        ws = self.workspace(need)
+        flags = (FULL_A if a_full else 0) | (FULL_B if b_full else 0)
+        self._sync_stream()
+        self._check(self.lib.comet_simm_share(self.h, party, m, k_full, n, bs, _ptr(blk_idx),
+                                              _ptr(n_blk_dev), n_blk_cap, flags, _ptr(e), _ptr(f),
+                                              _ptr(a_i), _ptr(b_i), _ptr(c_i), _ptr(out), _ptr(ws),
+                                              need))
+        return out
+
+    # ---- probes ----
+    def set_tuning(self, key: int, value: int):
+        self._check(self.lib.comet_set_tuning(self.h, key, value))
+
+    def probe_mfma_i8(self, blocks: int, iters: int) -> float:
+        out = torch.empty(blocks * 256, dtype=torch.int32, device="cuda:%d" % self.device)
+        macs = ctypes.c_double()
+        self._sync_stream()
+        self._check(self.lib.comet_probe_mfma_i8(self.h, blocks, iters, _ptr(out), ctypes.byref(macs)))
+        return macs.value
+
+    def probe_valu_mac64(self, blocks: int, iters: int) -> float:
+        out = torch.empty(blocks * 256, dtype=torch.int64, device="cuda:%d" % self.device)
+        macs = ctypes.c_double()
+        self._sync_stream()
+        self._check(self.lib.comet_probe_valu_mac64(self.h, blocks, iters, _ptr(out), ctypes.byref(macs)))
+        return macs.value
+
+    def probe_copy(self, src, dst):
+        self._sync_stream()
+        self._check(self.lib.comet_probe_copy(self.h, _ptr(src), _ptr(dst), src.numel()))
+        return dst

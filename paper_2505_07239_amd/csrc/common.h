@@ -1,0 +1,65 @@
+// Shared host-side declarations of the comet_ring library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "comet_ring.h"
+
+typedef unsigned long long u64;
+typedef unsigned int u32;
+
+struct comet_ctx {
+    int device;
+    int num_cu;
+    hipStream_t stream;
+    int gemm_grid;   // 0 = automatic
+    char err[512];
+};
+
+static inline int comet_fail(comet_ctx* ctx, int code, const char* fmt, ...) {
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+static inline bool comet_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Makes the context's device current for the duration of a call.
+struct comet_device_guard {
+    int prev;
+    bool ok;
+    explicit comet_device_guard(const comet_ctx* ctx) : prev(-1), ok(true) {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+        if (prev != ctx->device && hipSetDevice(ctx->device) != hipSuccess) ok = false;
+    }
+    ~comet_device_guard() {
+        int cur = -1;
+        if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+    }
+};
+
+#define COMET_CHECK_CTX(ctx)                                             \
+    do {                                                                 \
+        if (!(ctx)) return COMET_EINVAL;                                 \
+    } while (0)
+
+#define COMET_LAUNCH_CHECK(ctx, what)                                                            \
+    do {                                                                                         \
+        hipError_t e_ = hipGetLastError();                                                       \
+        if (e_ != hipSuccess)                                                                    \
+            return comet_fail((ctx), COMET_EDEVICE, "%s: launch failed: %s", (what),             \
+                              hipGetErrorString(e_));                                            \
+    } while (0)
+
+// Limits shared by the host checks and the kernels' 32-bit index arithmetic.
+static const int64_t COMET_DIM_MAX = (1ll << 24) - 1;

@@ -1,0 +1,221 @@
+// Plaintext sparsity distribution -> ordered list of active neuron blocks.
+//
+// The predictor's mask is plaintext on each server (paper Sec. 4.2), so the
+// local first step of Protocols 2 and 3 -- find the columns that are kept -- is
+// an ordered stream compaction.  The per-token masks of a batch are OR-ed first
+// because one matmul serves the whole batch.
+//
+// Two paths:
+//   small (nb <= 4096): one 256-thread workgroup does everything in one launch;
+//     this is every real FFN mask (a few hundred blocks) and is latency-bound.
+//   large: three wait-free launches.  (1) each lane ORs 16 adjacent flags over
+//     all tokens into a 16-bit word and each workgroup stores its popcount;
+//     (2) one workgroup scans the workgroup counts; (3) each workgroup scans its
+//     own 16-bit words with wavefront prefix sums and writes the indices.
+//     The mask bytes are read exactly once; passes 2 and 3 touch only the
+//     bit-packed words (1/8 of a byte per flag) and the outputs.
+#include "common.h"
+
+namespace {
+
+constexpr int CT = 256;             // threads per workgroup
+constexpr int FL = 16;              // flags per lane
+constexpr int ITEMS = 4;            // 16-flag groups per lane in the large path
+constexpr int CHUNK = CT * FL * ITEMS;   // flags per workgroup in the large path
+
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u32 nz_bits4(u32 w, int shift) {
+    // one bit per non-zero byte of w, placed at bit positions shift .. shift+3
+    u32 r = 0;
+    r |= ((w & 0x000000ffu) ? 1u : 0u);
+    r |= ((w & 0x0000ff00u) ? 2u : 0u);
+    r |= ((w & 0x00ff0000u) ? 4u : 0u);
+    r |= ((w & 0xff000000u) ? 8u : 0u);
+    return r << shift;
+}
+
+// OR over tokens of flags [c0, c0+16) -> 16-bit word.  Flags at or beyond nb read as 0.
+__device__ __forceinline__ u32 or_flags16(const uint8_t* __restrict__ mask, long n_tok, long nb,
+                                          long c0, bool rows_aligned) {
+    if (c0 >= nb) return 0;
+    if (rows_aligned && c0 + FL <= nb) {
+        u32x4 acc = {0, 0, 0, 0};
+        for (long t = 0; t < n_tok; ++t)
+            acc |= __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(mask + t * nb + c0));
+        return nz_bits4(acc.x, 0) | nz_bits4(acc.y, 4) | nz_bits4(acc.z, 8) | nz_bits4(acc.w, 12);
+    }
+    u32 bits = 0;
+    const int lim = (int)((nb - c0) < FL ? (nb - c0) : FL);
+    for (int j = 0; j < lim; ++j) {
+        u32 any = 0;
+        for (long t = 0; t < n_tok; ++t) any |= mask[t * nb + c0 + j];
+        bits |= (any ? 1u : 0u) << j;
+    }
+    return bits;
+}
+
+// Exclusive prefix sum of one value per lane over the 64-lane wavefront.
+__device__ __forceinline__ int wave_excl_scan(int v, int lane, int* total) {
+    int inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += o;
+    }
+    *total = __shfl(inc, 63, 64);
+    return inc - v;
+}
+
+// Exclusive prefix over the workgroup (CT threads).  sm: CT/64 + 1 ints.
+__device__ __forceinline__ int block_excl_scan(int v, int* sm, int* block_total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int wtot;
+    const int ex = wave_excl_scan(v, lane, &wtot);
+    if (lane == 0) sm[wave] = wtot;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < CT / 64; ++w) {
+        const int x = sm[w];
+        if (w < wave) base += x;
+        tot += x;
+    }
+    __syncthreads();
+    *block_total = tot;
+    return base + ex;
+}
+
+__device__ __forceinline__ void emit_bits(u32 bits, int first_block, int* __restrict__ out) {
+    while (bits) {
+        const int j = __builtin_ctz(bits);
+        *out++ = first_block + j;
+        bits &= bits - 1;
+    }
+}
+
+__global__ __launch_bounds__(CT) void compact_small_kernel(const uint8_t* __restrict__ mask,
+                                                           long n_tok, long nb, bool rows_aligned,
+                                                           int* __restrict__ blk_idx,
+                                                           int* __restrict__ n_blk_dev) {
+    __shared__ int sm[CT / 64 + 1];
+    const long c0 = (long)threadIdx.x * FL;
+    const u32 bits = or_flags16(mask, n_tok, nb, c0, rows_aligned);
+    int total;
+    const int off = block_excl_scan(__builtin_popcount(bits), sm, &total);
+    emit_bits(bits, (int)c0, blk_idx + off);
+    if (threadIdx.x == 0) *n_blk_dev = total;
+}
+
+// pass 1: bit-pack and count
+__global__ __launch_bounds__(CT) void compact_pack_kernel(const uint8_t* __restrict__ mask,
+                                                          long n_tok, long nb, bool rows_aligned,
+                                                          unsigned short* __restrict__ words,
+                                                          int* __restrict__ counts) {
+    __shared__ int sm[CT / 64 + 1];
+    const long base = (long)blockIdx.x * CHUNK;
+    u32 bits[ITEMS];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j)
+        bits[j] = or_flags16(mask, n_tok, nb, base + ((long)j * CT + threadIdx.x) * FL, rows_aligned);
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        cnt += __builtin_popcount(bits[j]);
+        const long w = (base / FL) + (long)j * CT + threadIdx.x;
+        if (w * FL < nb) words[w] = (unsigned short)bits[j];
+    }
+    int total;
+    (void)block_excl_scan(cnt, sm, &total);
+    if (threadIdx.x == 0) counts[blockIdx.x] = total;
+}
+
+// pass 2: exclusive scan of the workgroup counts, in place; writes the grand total
+__global__ __launch_bounds__(CT) void compact_scan_kernel(int* __restrict__ counts, int n,
+                                                          int* __restrict__ n_blk_dev) {
+    __shared__ int sm[CT / 64 + 1];
+    int carry = 0;
+    for (int base = 0; base < n; base += CT) {
+        const int i = base + threadIdx.x;
+        const int v = i < n ? counts[i] : 0;
+        int total;
+        const int ex = block_excl_scan(v, sm, &total);
+        if (i < n) counts[i] = carry + ex;
+        carry += total;
+    }
+    if (threadIdx.x == 0) *n_blk_dev = carry;
+}
+
+// pass 3: positions inside the workgroup, then write the indices
+__global__ __launch_bounds__(CT) void compact_emit_kernel(const unsigned short* __restrict__ words,
+                                                          const int* __restrict__ offsets, long nb,
+                                                          int* __restrict__ blk_idx) {
+    __shared__ int sm[CT / 64 + 1];
+    const long base = (long)blockIdx.x * CHUNK;
+    int carry = offsets[blockIdx.x];
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const long w = (base / FL) + (long)j * CT + threadIdx.x;
+        const u32 bits = (w * FL < nb) ? words[w] : 0u;
+        int total;
+        const int ex = block_excl_scan(__builtin_popcount(bits), sm, &total);
+        emit_bits(bits, (int)(w * FL), blk_idx + carry + ex);
+        carry += total;
+    }
+}
+
+inline size_t compact_ws_bytes(int64_t nb) {
+    if (nb <= (int64_t)CT * FL) return 0;
+    const int64_t groups = (nb + CHUNK - 1) / CHUNK;
+    const size_t words = ((size_t)groups * CT * ITEMS * sizeof(unsigned short) + 255) & ~(size_t)255;
+    return words + (size_t)groups * sizeof(int);
+}
+
+}  // namespace
+
+size_t comet_compact_workspace_bytes(int64_t n_tok, int64_t nb) {
+    if (n_tok < 1 || nb < 0 || nb >= (1ll << 31) - (1ll << 16)) return 0;
+    return compact_ws_bytes(nb);
+}
+
+extern "C" int comet_compact_mask(comet_ctx* ctx, const uint8_t* mask, int64_t n_tok, int64_t nb,
+                                  int32_t* blk_idx, int32_t* n_blk_dev, void* ws, size_t ws_bytes) {
+    const char* what = "comet_compact_mask";
+    COMET_CHECK_CTX(ctx);
+    if (!mask || !blk_idx || !n_blk_dev) return comet_fail(ctx, COMET_EINVAL, "%s: null pointer", what);
+    if (n_tok < 1 || nb < 0) return comet_fail(ctx, COMET_EINVAL, "%s: need n_tok >= 1, nb >= 0", what);
+    if (nb >= (1ll << 31) - (1ll << 16) || n_tok > (1ll << 40) / (nb > 0 ? nb : 1))
+        return comet_fail(ctx, COMET_ECAP, "%s: mask too large", what);
+    if ((reinterpret_cast<uintptr_t>(blk_idx) & 3u) || (reinterpret_cast<uintptr_t>(n_blk_dev) & 3u))
+        return comet_fail(ctx, COMET_EALIGN, "%s: int32 outputs must be 4-byte aligned", what);
+    const size_t need = compact_ws_bytes(nb);
+    if (need && (!ws || ws_bytes < need))
+        return comet_fail(ctx, COMET_EWORKSPACE, "%s: workspace of %zu bytes required", what, need);
+    if (need && (reinterpret_cast<uintptr_t>(ws) & 255u))
+        return comet_fail(ctx, COMET_EALIGN, "%s: workspace must be 256-byte aligned", what);
+    comet_device_guard guard(ctx);
+    if (!guard.ok) return comet_fail(ctx, COMET_EDEVICE, "%s: cannot select device", what);
+    // 16-byte loads need every token row to start on a 16-byte boundary
+    const bool rows_aligned =
+        (reinterpret_cast<uintptr_t>(mask) & 15u) == 0 && (n_tok == 1 || (nb & 15) == 0);
+    if (!need) {
+        hipLaunchKernelGGL(compact_small_kernel, dim3(1), dim3(CT), 0, ctx->stream, mask,
+                           (long)n_tok, (long)nb, rows_aligned, blk_idx, n_blk_dev);
+        COMET_LAUNCH_CHECK(ctx, what);
+        return COMET_OK;
+    }
+    const int groups = (int)((nb + CHUNK - 1) / CHUNK);
+    unsigned short* words = static_cast<unsigned short*>(ws);
+    const size_t words_bytes = ((size_t)groups * CT * ITEMS * sizeof(unsigned short) + 255) & ~(size_t)255;
+    int* counts = reinterpret_cast<int*>(static_cast<char*>(ws) + words_bytes);
+    hipLaunchKernelGGL(compact_pack_kernel, dim3(groups), dim3(CT), 0, ctx->stream, mask, (long)n_tok,
+                       (long)nb, rows_aligned, words, counts);
+    COMET_LAUNCH_CHECK(ctx, what);
+    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(CT), 0, ctx->stream, counts, groups,
+                       n_blk_dev);
+    COMET_LAUNCH_CHECK(ctx, what);
+    hipLaunchKernelGGL(compact_emit_kernel, dim3(groups), dim3(CT), 0, ctx->stream, words, counts,
+                       (long)nb, blk_idx);
+    COMET_LAUNCH_CHECK(ctx, what);
+    return COMET_OK;
+}

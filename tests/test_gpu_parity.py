@@ -1,0 +1,334 @@
+"""GPU parity: every HIP entry point against the CPU oracle, bit for bit.
+
+All calls go through the C ABI (ctypes binding).  Inputs are the seeded
+synthetic workloads; expected values come from ``oracle/`` only.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle as co                                   # noqa: E402
+from oracle import cases, protocols                   # noqa: E402
+from workloads import configs, masks, rng             # noqa: E402
+
+
+def say(msg):
+    print("[gpu-parity] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2505_07239_amd as comet
+    c = comet.Context(0)
+    yield c
+    c.close()
+
+
+def up(a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int64)).cuda()
+
+
+def down(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+def u64(seed, stream, *shape):
+    return rng.uniform_u64(seed, stream, int(np.prod(shape))).reshape(shape)
+
+
+# ---------------------------------------------------------------------------
+# (1) mask / open
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n", [0, 1, 2, 3, 1023, 2048, (1 << 20) + 3, 5_000_001])
+def test_mask_share_and_open(ctx, n):
+    say("mask_share/open n=%d" % n)
+    x, a = u64(31, 1, n), u64(31, 2, n)
+    gx, ga = up(x), up(a)
+    d = ctx.mask_share(gx, ga)
+    e = ctx.open(gx, ga)
+    torch.cuda.synchronize()
+    assert np.array_equal(down(d), co.mask_share(x, a))
+    assert np.array_equal(down(e), co.open_(x, a))
+
+
+def test_mask_share_rejects_bad_arguments(ctx):
+    import paper_2505_07239_amd as comet
+    x = up(u64(32, 1, 16))
+    with pytest.raises(comet.CometError) as ei:
+        ctx.mask_share(x[1:9], x[1:9])          # 8-byte aligned only
+    assert ei.value.code == -2
+
+
+@pytest.mark.parametrize("rows,cols,bs,nb_keep,axis", [
+    (5, 48, 4, 3, 0), (7, 33, 3, 4, 0), (48, 10, 4, 5, 1), (33, 7, 3, 2, 1),
+    (128, 3072, 32, 10, 0), (3072, 768, 32, 10, 1)])
+def test_mask_share_gather(ctx, rows, cols, bs, nb_keep, axis):
+    import paper_2505_07239_amd as comet
+    say("mask_share_gather %dx%d bs=%d axis=%d" % (rows, cols, bs, axis))
+    extent = cols if axis == comet.AXIS_COLS else rows
+    nb = extent // bs
+    mask = masks.uniform_block_mask(33, rows + cols, nb, nb_keep / nb)
+    idx = co.compact_mask(mask)
+    w, b = u64(33, 1, rows, cols), u64(33, 2, rows, cols)
+    cap = len(idx) + 2 if len(idx) + 2 <= nb else len(idx)
+    gi = torch.zeros(nb, dtype=torch.int32, device="cuda")
+    gi[:len(idx)] = torch.from_numpy(idx).cuda()
+    n_dev = torch.tensor([len(idx)], dtype=torch.int32, device="cuda")
+    shape = (rows, cap * bs) if axis == comet.AXIS_COLS else (cap * bs, cols)
+    out = torch.full(shape, -1, dtype=torch.int64, device="cuda")
+    ctx.mask_share_gather(up(w), up(b), axis, bs, gi, n_dev, cap, out=out)
+    torch.cuda.synchronize()
+    got = down(out)
+    if axis == comet.AXIS_COLS:
+        want = co.mask_share(co.index_cols(w, idx, bs), co.index_cols(b, idx, bs))
+        assert np.array_equal(got[:, :len(idx) * bs], want)
+        assert np.all(got[:, len(idx) * bs:] == np.uint64(2 ** 64 - 1))     # beyond n_blk: untouched
+    else:
+        want = co.mask_share(co.index_rows(w, idx, bs), co.index_rows(b, idx, bs))
+        assert np.array_equal(got[:len(idx) * bs], want)
+        assert np.all(got[len(idx) * bs:] == np.uint64(2 ** 64 - 1))
+
+
+# ---------------------------------------------------------------------------
+# (2) compaction
+# ---------------------------------------------------------------------------
+
+def _check_compact(ctx, mask_np):
+    m = torch.from_numpy(mask_np).cuda()
+    idx, n_dev = ctx.compact_mask(m)
+    torch.cuda.synchronize()
+    want = co.compact_mask(mask_np)
+    t = int(n_dev.item())
+    assert t == len(want)
+    assert np.array_equal(idx[:t].cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+def test_compact_mask_configs(ctx, cid):
+    cfg = configs.config(cid, 0.25 if cid == 5 else None)
+    say("compact config %d" % cid)
+    _check_compact(ctx, configs.token_masks(cfg))
+
+
+@pytest.mark.parametrize("n_tok,nb", [(1, 1), (1, 15), (1, 16), (1, 17), (3, 100), (8, 216), (5, 4096),
+                                      (1, 4097), (1, 16384), (1, 16385), (3, 50_000), (4, 65536),
+                                      (1, 1_000_003), (2, 3_000_000)])
+def test_compact_mask_shapes(ctx, n_tok, nb):
+    say("compact n_tok=%d nb=%d" % (n_tok, nb))
+    m = np.stack([masks.stress_mask(34, 10 * t + nb % 7, nb, 0.15) for t in range(n_tok)])
+    # any non-zero byte is an active flag
+    m = (m * (1 + (rng.uniform_u64(34, 99, n_tok * nb) % np.uint64(255)).astype(np.uint8).reshape(n_tok, nb)))
+    _check_compact(ctx, np.ascontiguousarray(m.astype(np.uint8)))
+
+
+def test_compact_mask_degenerate(ctx):
+    say("compact degenerate")
+    for nb in (7, 5000, 70_000):
+        _check_compact(ctx, np.zeros((2, nb), np.uint8))
+        _check_compact(ctx, np.ones((1, nb), np.uint8))
+    # unaligned mask pointer
+    base = torch.from_numpy(masks.stress_mask(35, 1, 20_001, 0.3)).cuda()
+    idx, n_dev = ctx.compact_mask(base[1:])
+    torch.cuda.synchronize()
+    want = co.compact_mask(base[1:].cpu().numpy())
+    assert int(n_dev.item()) == len(want) and np.array_equal(idx[:len(want)].cpu().numpy(), want)
+
+
+# ---------------------------------------------------------------------------
+# (3) output shares
+# ---------------------------------------------------------------------------
+
+def _run_share(ctx, kind, party, bs, idx_np, cap, e, f, a_i, b_i, c_i, a_full=True, b_full=True,
+               n_blk_on_device=True):
+    gi = torch.zeros(max(cap, 1), dtype=torch.int32, device="cuda")
+    gi[:len(idx_np)] = torch.from_numpy(idx_np).cuda()
+    n_dev = torch.tensor([len(idx_np)], dtype=torch.int32, device="cuda") if n_blk_on_device else None
+    if kind == "somm":
+        return ctx.somm_share(party, bs, gi, n_dev, cap, up(e), up(f), up(a_i), up(b_i), up(c_i),
+                              b_full=b_full)
+    return ctx.simm_share(party, bs, gi, n_dev, cap, up(e), up(f), up(a_i), up(b_i), up(c_i),
+                          a_full=a_full, b_full=b_full)
+
+
+def _pad_cols(a, ld):
+    out = np.zeros((a.shape[0], ld), np.uint64)
+    out[:, :a.shape[1]] = a
+    return out
+
+
+def _pad_rows(a, ld):
+    out = np.zeros((ld, a.shape[1]), np.uint64)
+    out[:a.shape[0]] = a
+    return out
+
+
+def _random_case(kind, m, k, n, bs, keep, seed):
+    """Uniformly random ring elements everywhere (shares are uniform anyway)."""
+    nb = (n if kind == "somm" else k) // bs
+    mask = masks.uniform_block_mask(seed, 7, nb, keep / nb)[None, :]
+    nk = int(mask.sum()) * bs
+    shape_c = (m, nk) if kind == "somm" else (m, n)
+    x_sh = (u64(seed, 1, m, k), u64(seed, 2, m, k))
+    y_sh = (u64(seed, 3, k, n), u64(seed, 4, k, n))
+    return protocols.block_case(kind, x_sh, y_sh, mask, bs, u64(seed, 5, m, k), u64(seed, 6, k, n),
+                                u64(seed, 8, m, k), u64(seed, 9, k, n), u64(seed, 10, *shape_c))
+
+
+@pytest.mark.parametrize("cid", [1, 2])
+def test_share_configs_full(ctx, cid):
+    cfg = configs.config(cid)
+    for mm in cfg.matmuls:
+        case, _ = cases.build(cfg, mm)
+        for party in (0, 1):
+            say("config %d %s party %d" % (cid, mm.name, party))
+            z = _run_share(ctx, mm.kind, party, cfg.bs, case.idx, len(case.idx), case.e, case.f,
+                           case.a[party], case.b[party], case.c[party])
+            torch.cuda.synchronize()
+            assert np.array_equal(down(z), case.z[party])
+
+
+@pytest.mark.parametrize("kind,m,k,n,bs,keep", [
+    ("somm", 1, 1, 4, 4, 1), ("somm", 37, 70, 96, 3, 5), ("somm", 130, 45, 200, 8, 9),
+    ("somm", 65, 33, 64, 32, 1), ("somm", 200, 300, 512, 16, 20), ("somm", 9, 520, 600, 20, 17),
+    ("simm", 1, 4, 1, 4, 1), ("simm", 37, 96, 70, 3, 5), ("simm", 130, 200, 45, 8, 9),
+    ("simm", 65, 64, 33, 32, 1), ("simm", 200, 512, 300, 16, 20), ("simm", 9, 600, 520, 20, 17)])
+def test_share_ragged_shapes(ctx, kind, m, k, n, bs, keep):
+    case = _random_case(kind, m, k, n, bs, keep, 40 + m)
+    t = len(case.idx)
+    for party in (0, 1):
+        say("ragged %s m=%d k=%d n=%d bs=%d party %d" % (kind, m, k, n, bs, party))
+        z = _run_share(ctx, kind, party, bs, case.idx, t, case.e, case.f, case.a[party],
+                       case.b[party], case.c[party])
+        torch.cuda.synchronize()
+        assert np.array_equal(down(z), case.z[party])
+
+
+@pytest.mark.parametrize("kind", ["somm", "simm"])
+def test_share_compact_triples_and_spare_capacity(ctx, kind):
+    """Triple shares passed already indexed; n_blk on the device below n_blk_cap."""
+    m, k, n, bs, keep = 70, 96, 128, 8, 5
+    case = _random_case(kind, m, k, n, bs, keep, 51)
+    t, cap = len(case.idx), len(case.idx) + 3
+    ld = cap * bs
+    for party in (0, 1):
+        say("compact triples %s party %d" % (kind, party))
+        if kind == "somm":
+            b_sel = co.index_cols(case.b[party], case.idx, bs)
+            args = (case.e, _pad_cols(case.f, ld), case.a[party], _pad_cols(b_sel, ld),
+                    _pad_cols(case.c[party], ld))
+            z = _run_share(ctx, kind, party, bs, case.idx, cap, *args, b_full=False)
+            torch.cuda.synchronize()
+            got = down(z)
+            assert np.array_equal(got[:, :t * bs], case.z[party])
+        else:
+            a_sel = co.index_cols(case.a[party], case.idx, bs)
+            b_sel = co.index_rows(case.b[party], case.idx, bs)
+            args = (_pad_cols(case.e, ld), _pad_rows(case.f, ld), _pad_cols(a_sel, ld),
+                    _pad_rows(b_sel, ld), case.c[party])
+            z = _run_share(ctx, kind, party, bs, case.idx, cap, *args, a_full=False, b_full=False)
+            torch.cuda.synchronize()
+            assert np.array_equal(down(z), case.z[party])
+
+
+def test_share_without_device_count(ctx):
+    case = _random_case("somm", 40, 64, 96, 8, 4, 52)
+    z = _run_share(ctx, "somm", 1, 8, case.idx, len(case.idx), case.e, case.f, case.a[1], case.b[1],
+                   case.c[1], n_blk_on_device=False)
+    torch.cuda.synchronize()
+    assert np.array_equal(down(z), case.z[1])
+
+
+def test_share_empty_mask(ctx):
+    """No active block: SOMM has nothing to write, SIMM returns C_i."""
+    m, k, n, bs = 16, 32, 24, 8
+    e, a, c = u64(53, 1, m, bs), u64(53, 2, m, k), u64(53, 3, m, n)
+    f, b = u64(53, 4, bs, n), u64(53, 5, k, n)
+    gi = torch.zeros(1, dtype=torch.int32, device="cuda")
+    n_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
+    z = ctx.simm_share(1, bs, gi, n_dev, 1, up(e), up(f), up(a), up(b), up(c))
+    torch.cuda.synchronize()
+    assert np.array_equal(down(z), c)
+
+
+@pytest.mark.parametrize("grid", [0, 1, 8])
+def test_share_extreme_digits_long_contraction(ctx, grid):
+    """All-0x80 bytes make every signed digit -128, the worst case for the
+    int32 digit-product planes; a contraction of 2 x 8224 words forces more
+    than one accumulation segment when few workgroups share it."""
+    import paper_2505_07239_amd as comet
+    m, k, n, bs = 33, 8224, 32, 32
+    worst = np.uint64(0x8080808080808080)
+    e, a = np.full((m, k), worst), np.full((m, k), worst)
+    f, b = np.full((k, n), worst), np.full((k, n), worst)
+    c = u64(54, 1, m, n)
+    e[::3, ::5] = u64(54, 2, m, k)[::3, ::5]
+    f[::7, ::2] = u64(54, 3, k, n)[::7, ::2]
+    idx = np.array([0], dtype=np.int32)
+    ctx.set_tuning(comet.TUNE_GEMM_GRID, grid)
+    try:
+        for party in (0, 1):
+            say("extreme digits grid=%d party %d" % (grid, party))
+            z = _run_share(ctx, "somm", party, bs, idx, 1, e, f, a, b, c)
+            torch.cuda.synchronize()
+            assert np.array_equal(down(z), co.beaver_share(party, e, f, a, b, c))
+    finally:
+        ctx.set_tuning(comet.TUNE_GEMM_GRID, 0)
+
+
+def test_share_is_deterministic(ctx):
+    """Integer ring: two runs must agree bit for bit (any difference is a race)."""
+    case = _random_case("simm", 150, 256, 200, 16, 9, 55)
+    runs = []
+    for _ in range(2):
+        z = _run_share(ctx, "simm", 1, 16, case.idx, len(case.idx), case.e, case.f, case.a[1],
+                       case.b[1], case.c[1])
+        torch.cuda.synchronize()
+        runs.append(down(z).copy())
+    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], case.z[1])
+
+
+def test_end_to_end_pipeline_config2(ctx):
+    """compact -> mask (indexed) -> open -> share, chained on the device with
+    n_blk never leaving it; then reconstruction against the plaintext product."""
+    import paper_2505_07239_amd as comet
+    cfg = configs.config(2)
+    for mm in cfg.matmuls:
+        say("pipeline config 2 %s" % mm.name)
+        case, plain = cases.build(cfg, mm)
+        idx, n_dev = ctx.compact_mask(torch.from_numpy(plain["mask"]).cuda())
+        cap = configs.masks.kept_blocks(cfg.density, cfg.nb)
+        d, g = [], []
+        for i in (0, 1):
+            if mm.kind == "somm":
+                d.append(ctx.mask_share(up(case.x[i]), up(case.a[i])))
+                g.append(ctx.mask_share_gather(up(case.y[i]), up(case.b[i]), comet.AXIS_COLS, cfg.bs,
+                                               idx, n_dev, cap))
+            else:
+                d.append(ctx.mask_share_gather(up(case.x[i]), up(case.a[i]), comet.AXIS_COLS, cfg.bs,
+                                               idx, n_dev, cap))
+                g.append(ctx.mask_share_gather(up(case.y[i]), up(case.b[i]), comet.AXIS_ROWS, cfg.bs,
+                                               idx, n_dev, cap))
+        e, f = ctx.open(d[0], d[1]), ctx.open(g[0], g[1])
+        z = []
+        for i in (0, 1):
+            fn = ctx.somm_share if mm.kind == "somm" else ctx.simm_share
+            z.append(fn(i, cfg.bs, idx, n_dev, cap, e, f, up(case.a[i]), up(case.b[i]), up(case.c[i])))
+        torch.cuda.synchronize()
+        assert np.array_equal(down(e), case.e) and np.array_equal(down(f), case.f)
+        for i in (0, 1):
+            assert np.array_equal(down(z[i]), case.z[i])
+        cols = (case.idx.astype(np.int64)[:, None] * cfg.bs + np.arange(cfg.bs)[None, :]).ravel()
+        rec = down(z[0]) + down(z[1])
+        want = plain["xq"] @ plain["yq"][:, cols] if mm.kind == "somm" else \
+            plain["xq"][:, cols] @ plain["yq"][cols, :]
+        assert np.array_equal(rec, want)
