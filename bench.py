@@ -1,0 +1,306 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+One *step* is one pass of the whole local path of a sparse FFN layer over one
+batch of synthetic input: compact the predicted block mask, then for every
+projection of the layer (gate / up: SOMM, down: SIMM) mask both parties'
+shares, open them, and compute both parties' output shares.  All inputs are
+resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  ``value`` is ring-GEMM throughput: algorithmic ring
+operations (1 multiply-accumulate mod 2^64 = 2 ops, two products per party per
+projection -- the minimum for Eq. 1) of one step divided by the step time.
+Both simulated parties run on the same GPU one after the other, so this is the
+rate one party's GPU sustains.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "sparse secret-shared FFN ring-GEMM Gop/s (mod 2^64) per party; % of roofline"
+PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
+INT8_OPS_PER_RING_MAC = 72   # 36 digit products, 2 ops each
+
+# HBM bytes per ring-GEMM launch from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by
+# the same counters on a plain copy); see profiles/.  None until measured for that workload.
+GEMM_TRAFFIC_BYTES = {}
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def parse_workload(name):
+    from workloads import configs
+    name = name.lower()
+    if name.startswith("c5"):
+        dens = 1.0
+        if "_d" in name:
+            dens = int(name.split("_d")[1]) / 100.0
+        return configs.config(5, dens), "c5_d%03d" % round(dens * 100)
+    cid = int(name[1:])
+    return configs.config(cid), "c%d" % cid
+
+
+class Layer:
+    """Device buffers of one sparse FFN layer and the step that runs the path."""
+
+    def __init__(self, ctx, cfg, seed):
+        import numpy as np
+        import torch
+        from workloads import configs
+        self.ctx, self.cfg = ctx, cfg
+        dev = torch.device("cuda:0")
+        self.mask_np = configs.token_masks(cfg, seed)
+        self.mask = torch.from_numpy(self.mask_np).to(dev)
+        self.n_blk = int(np.count_nonzero(self.mask_np.max(axis=0)))     # public sparsity level
+        self.n_act = self.n_blk * cfg.bs
+        self.idx = torch.zeros(cfg.nb, dtype=torch.int32, device=dev)
+        self.n_dev = torch.zeros(1, dtype=torch.int32, device=dev)
+        gen = torch.Generator(device=dev)
+
+        def words(stream, *shape):
+            # additive shares and triple parts are uniform over Z_{2^64} whatever the secrets are
+            gen.manual_seed(seed * 1000003 + stream)
+            return torch.randint(-(2 ** 63), 2 ** 63 - 1, shape, dtype=torch.int64, device=dev,
+                                 generator=gen)
+
+        self.mm = []
+        for mm in cfg.matmuls:
+            sid = lambda role, party=0: configs.stream_id(cfg, mm.index, role) * 2 + party
+            b = dict(mm=mm)
+            b["x"] = [words(sid(0, i), mm.m, mm.k) for i in (0, 1)]
+            b["y"] = [words(sid(1, i), mm.k, mm.n) for i in (0, 1)]
+            b["a"] = [words(sid(4, i), mm.m, mm.k) for i in (0, 1)]
+            b["b"] = [words(sid(5, i), mm.k, mm.n) for i in (0, 1)]
+            if mm.kind == "somm":
+                dshape, gshape, zshape = (mm.m, mm.k), (mm.k, self.n_act), (mm.m, self.n_act)
+            else:
+                dshape, gshape, zshape = (mm.m, self.n_act), (self.n_act, mm.n), (mm.m, mm.n)
+            b["c"] = [words(sid(8, i), *zshape) for i in (0, 1)]
+            b["d"] = [torch.empty(dshape, dtype=torch.int64, device=dev) for _ in (0, 1)]
+            b["g"] = [torch.empty(gshape, dtype=torch.int64, device=dev) for _ in (0, 1)]
+            b["e"] = torch.empty(dshape, dtype=torch.int64, device=dev)
+            b["f"] = torch.empty(gshape, dtype=torch.int64, device=dev)
+            b["z"] = [torch.empty(zshape, dtype=torch.int64, device=dev) for _ in (0, 1)]
+            b["macs_per_launch"] = 2 * mm.m * (mm.k if mm.kind == "somm" else self.n_act) * \
+                (self.n_act if mm.kind == "somm" else mm.n)
+            self.mm.append(b)
+        self.ring_ops_per_step = sum(2 * 2 * b["macs_per_launch"] for b in self.mm)   # 2 parties, 2 ops/MAC
+
+    def step(self):
+        import paper_2505_07239_amd as comet
+        ctx, cfg = self.ctx, self.cfg
+        ctx.compact_mask(self.mask, self.idx, self.n_dev)
+        for b in self.mm:
+            mm = b["mm"]
+            for i in (0, 1):
+                if mm.kind == "somm":
+                    ctx.mask_share(b["x"][i], b["a"][i], out=b["d"][i])
+                    ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_COLS, cfg.bs, self.idx,
+                                          self.n_dev, self.n_blk, out=b["g"][i])
+                else:
+                    ctx.mask_share_gather(b["x"][i], b["a"][i], comet.AXIS_COLS, cfg.bs, self.idx,
+                                          self.n_dev, self.n_blk, out=b["d"][i])
+                    ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_ROWS, cfg.bs, self.idx,
+                                          self.n_dev, self.n_blk, out=b["g"][i])
+            ctx.open(b["d"][0], b["d"][1], out=b["e"])
+            ctx.open(b["g"][0], b["g"][1], out=b["f"])
+            for i in (0, 1):
+                if mm.kind == "somm":
+                    ctx.somm_share(i, cfg.bs, self.idx, self.n_dev, self.n_blk, b["e"], b["f"],
+                                   b["a"][i], b["b"][i], b["c"][i], out=b["z"][i])
+                else:
+                    ctx.simm_share(i, cfg.bs, self.idx, self.n_dev, self.n_blk, b["e"], b["f"],
+                                   b["a"][i], b["b"][i], b["c"][i], out=b["z"][i])
+
+
+def cpu_baseline(layer, budget_s=15.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload:
+    both parties' output shares of the first projection for a block of output
+    rows (all rows when that fits the budget).  Also checks the GPU's rows."""
+    import numpy as np
+    import oracle as co
+    b = layer.mm[0]
+    mm, cfg = b["mm"], layer.cfg
+    host = lambda t: t.cpu().numpy().view(np.uint64)
+    idx = layer.idx[:layer.n_blk].cpu().numpy()
+    e, f = host(b["e"]), host(b["f"])
+    k_eff = e.shape[1]
+    n_eff = f.shape[1]
+    cores = co.num_threads()
+    est_rate = 0.6e9 * cores                     # ring MAC/s, rough; only sizes the sample
+    rows = int(max(1, min(mm.m, budget_s * est_rate / (6.0 * k_eff * n_eff))))
+    r0, r1 = 0, rows
+    a_sel, b_sel = [], []
+    for i in (0, 1):
+        a_i, b_i = host(b["a"][i]), host(b["b"][i])
+        if mm.kind == "somm":
+            a_sel.append(a_i)
+            b_sel.append(co.index_cols(b_i, idx, cfg.bs))
+        else:
+            a_sel.append(co.index_cols(a_i, idx, cfg.bs))
+            b_sel.append(co.index_rows(b_i, idx, cfg.bs))
+    c = [host(b["c"][i]) for i in (0, 1)]
+    t0 = time.perf_counter()
+    z = [co.beaver_share_rows(i, e, f, a_sel[i], b_sel[i], c[i], r0, r1) for i in (0, 1)]
+    dt = time.perf_counter() - t0
+    ok = all(np.array_equal(z[i], host(b["z"][i])[r0:r1]) for i in (0, 1))
+    ring_ops = 2 * 2 * (2 * rows * k_eff * n_eff)            # 2 parties, 2 ops/MAC, 2 products
+    return {"value": ring_ops / dt / 1e9, "unit": "Gop/s", "cores": cores, "kind": "oracle",
+            "sample": "%s projection, output rows %d..%d of %d, both parties, oracle's 3-product "
+                      "Eq. 1 loops (counted as the 2-product minimum), %.1f s" %
+                      (mm.name, r0, r1, mm.m, dt),
+            "matches_gpu": bool(ok)}
+
+
+def micro(ctx, layer):
+    """Per-kernel yardsticks on the same device (stderr + returned dict)."""
+    import torch
+    from workloads import masks
+    out = {}
+
+    def timed(fn, reps=20):
+        fn()
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(reps):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) / reps * 1e-3
+
+    n = 11008 * 4096                                  # weight side of the dense down projection
+    a = torch.randint(-(2 ** 63), 2 ** 63 - 1, (n,), dtype=torch.int64, device="cuda")
+    b = torch.randint(-(2 ** 63), 2 ** 63 - 1, (n,), dtype=torch.int64, device="cuda")
+    o = torch.empty_like(a)
+    t = timed(lambda: ctx.open(a, b, out=o))
+    out["open_GBs"] = 24.0 * n / t / 1e9
+    t = timed(lambda: ctx.mask_share(a, b, out=o))
+    out["mask_share_GBs"] = 24.0 * n / t / 1e9
+    t = timed(lambda: ctx.probe_copy(a, o))
+    out["copy_GBs"] = 16.0 * n / t / 1e9
+    del a, b, o
+    flags = 1 << 28
+    m = masks.stress_mask_device(7, flags, torch.device("cuda:0"), 0.15)
+    idx = torch.empty(flags, dtype=torch.int32, device="cuda")
+    nd = torch.empty(1, dtype=torch.int32, device="cuda")
+    t = timed(lambda: ctx.compact_mask(m, idx, nd), reps=10)
+    kept = int(nd.item())
+    out["compact_stress_GBs"] = (flags + 4.0 * kept) / t / 1e9
+    out["compact_stress_kept"] = kept
+    del m, idx
+    t = timed(lambda: ctx.compact_mask(layer.mask, layer.idx, layer.n_dev), reps=50)
+    out["compact_layer_mask_us"] = t * 1e6
+    macs = ctx.probe_mfma_i8(1024, 2000)
+    t = timed(lambda: ctx.probe_mfma_i8(1024, 2000), reps=5)
+    out["mfma_i8_issue_TOPs"] = 2.0 * macs / t / 1e12
+    macs = ctx.probe_valu_mac64(2048, 2000)
+    t = timed(lambda: ctx.probe_valu_mac64(2048, 2000), reps=5)
+    out["valu_mac64_Gops"] = 2.0 * macs / t / 1e9
+    out["integer_roofline_Gops"] = max(out["valu_mac64_Gops"],
+                                       out["mfma_i8_issue_TOPs"] * 1e3 / 36.0)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3",
+                    help="c1..c4, c5_d100 / c5_d050 / c5_d025 / c5_d010 / c5_d005")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-micro", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (both parties are simulated on it); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_2505_07239_amd as comet
+    from workloads import rng
+    if not os.path.exists(comet.binding.LIB_PATH):
+        from paper_2505_07239_amd import build
+        build.build()
+
+    cfg, wname = parse_workload(args.workload)
+    ctx = comet.Context(0)
+    layer = Layer(ctx, cfg, rng.BASE_SEED)
+    log("workload %s: %s, m=%d d=%d f=%d bs=%d kept blocks %d/%d (n_act=%d), %.2f G ring ops/step" %
+        (wname, cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs, layer.n_blk, cfg.nb,
+         layer.n_act, layer.ring_ops_per_step / 1e9))
+
+    for _ in range(args.warmup):
+        layer.step()
+    torch.cuda.synchronize()
+    launches = 2 * len(layer.mm) * args.steps
+    ctx.timing_begin(launches)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        layer.step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    gemm_ms, n_timed = ctx.timing_end()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = layer.ring_ops_per_step / (ms_per_step * 1e-3) / 1e9
+    macs_per_launch = sum(b["macs_per_launch"] for b in layer.mm) / len(layer.mm)
+    gemm_ms_avg = gemm_ms / max(n_timed, 1)
+    achieved = INT8_OPS_PER_RING_MAC * macs_per_launch / (gemm_ms_avg * 1e-3) / 1e12
+    result = {
+        "metric": METRIC, "value": value, "unit": "Gop/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "%s: %s FFN, %d tokens, d_model %d, d_ff %d, block %d, %d of %d blocks "
+                               "kept (%s mask); projections %s; both parties" %
+                               (wname, cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs,
+                                layer.n_blk, cfg.nb, cfg.mask_kind,
+                                "+".join(m.name for m in cfg.matmuls)),
+                   "ring_ops_per_step": layer.ring_ops_per_step,
+                   "launches_per_step": 2 * len(layer.mm)},
+        "roofline": {"bound": "mfma", "kernel": "ring_gemm_kernel",
+                     "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                     "frac": achieved / PEAK_INT8_TOPS,
+                     "traffic": GEMM_TRAFFIC_BYTES.get(wname),
+                     "avg_launch_ms": gemm_ms_avg, "launches_timed": n_timed,
+                     "ring_macs_per_launch": macs_per_launch,
+                     "gemm_share_of_step": gemm_ms / ((t1 - t0) * 1e3),
+                     "note": "algorithmic int8 ops: 36 digit products x 2 ops per ring MAC, two "
+                             "products per party (2*m*k*n_act ring MACs per launch)"},
+    }
+    if not args.no_micro:
+        result["kernels"] = micro(ctx, layer)
+        for k, v in result["kernels"].items():
+            log("%s = %.4g" % (k, v))
+        result["roofline"]["frac_of_measured_mfma_issue"] = achieved / result["kernels"]["mfma_i8_issue_TOPs"]
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(layer)
+        log("cpu oracle: %.2f Gop/s on %d threads; rows match GPU: %s" %
+            (result["cpu_baseline"]["value"], result["cpu_baseline"]["cores"],
+             result["cpu_baseline"]["matches_gpu"]))
+        if not result["cpu_baseline"]["matches_gpu"]:
+            log("ERROR: GPU result differs from the oracle on the sampled rows")
+            print(json.dumps(result))
+            sys.exit(3)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

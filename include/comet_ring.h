@@ -165,6 +165,15 @@ int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64
 enum { COMET_TUNE_GEMM_GRID = 0 };
 int comet_set_tuning(comet_ctx* ctx, int key, int value);
 
+/* Device-side timing of the ring-GEMM kernel alone (the share calls also run a
+ * small operand-packing kernel, which this excludes).  comet_timing_begin
+ * creates up to max_launches HIP event pairs; while timing is on, every share
+ * call records one pair around its GEMM kernel on the context's stream.
+ * comet_timing_end waits for the last recorded event, returns the summed
+ * kernel time and the number of launches timed, and destroys the events. */
+int comet_timing_begin(comet_ctx* ctx, int max_launches);
+int comet_timing_end(comet_ctx* ctx, double* total_ms, int* launches);
+
 /* Register-resident issue loop of the int8 matrix instruction the ring GEMM
  * uses: launches `blocks` x 256 threads, `iters` dependent-free MFMA groups
  * each.  out (device, blocks*256 int32) keeps the results alive.  Returns the

@@ -26,7 +26,7 @@ EXPORTS = [
     "comet_create", "comet_destroy", "comet_set_stream", "comet_last_error", "comet_version",
     "comet_workspace_bytes", "comet_mask_share", "comet_mask_share_gather", "comet_open",
     "comet_compact_mask", "comet_somm_share", "comet_simm_share",
-    "comet_set_tuning", "comet_probe_mfma_i8", "comet_probe_valu_mac64", "comet_probe_copy",
+    "comet_set_tuning", "comet_timing_begin", "comet_timing_end", "comet_probe_mfma_i8", "comet_probe_valu_mac64", "comet_probe_copy",
 ]
 
 _lib = None
@@ -67,6 +67,8 @@ def load_library() -> ctypes.CDLL:
     lib.comet_probe_valu_mac64.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
     lib.comet_probe_copy.argtypes = [vp, vp, vp, sz]
     lib.comet_set_tuning.argtypes = [vp, i32, i32]
+    lib.comet_timing_begin.argtypes = [vp, i32]
+    lib.comet_timing_end.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
     _lib = lib
     return lib
 
@@ -210,6 +212,14 @@ class Context:
     # ---- probes ----
     def set_tuning(self, key: int, value: int):
         self._check(self.lib.comet_set_tuning(self.h, key, value))
+
+    def timing_begin(self, max_launches: int):
+        self._check(self.lib.comet_timing_begin(self.h, max_launches))
+
+    def timing_end(self):
+        ms, n = ctypes.c_double(), ctypes.c_int()
+        self._check(self.lib.comet_timing_end(self.h, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
 
     def probe_mfma_i8(self, blocks: int, iters: int) -> float:
         out = torch.empty(blocks * 256, dtype=torch.int32, device="cuda:%d" % self.device)

@@ -22,13 +22,27 @@ int comet_create(comet_ctx** out, int device_id) {
     ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     ctx->stream = nullptr;
     ctx->gemm_grid = 0;
+    ctx->ev = nullptr;
+    ctx->ev_cap = ctx->ev_used = 0;
     ctx->err[0] = '\0';
     *out = ctx;
     return COMET_OK;
 }
 
+static void drop_events(comet_ctx* ctx) {
+    if (!ctx->ev) return;
+    for (int i = 0; i < ctx->ev_cap; ++i) (void)hipEventDestroy(ctx->ev[i]);
+    delete[] ctx->ev;
+    ctx->ev = nullptr;
+    ctx->ev_cap = ctx->ev_used = 0;
+}
+
 int comet_destroy(comet_ctx* ctx) {
     COMET_CHECK_CTX(ctx);
+    {
+        comet_device_guard guard(ctx);
+        drop_events(ctx);
+    }
     delete ctx;
     return COMET_OK;
 }
@@ -44,6 +58,50 @@ int comet_set_tuning(comet_ctx* ctx, int key, int value) {
     if (key != COMET_TUNE_GEMM_GRID || value < 0 || value > (1 << 16))
         return comet_fail(ctx, COMET_EINVAL, "comet_set_tuning: unknown key or bad value");
     ctx->gemm_grid = value;
+    return COMET_OK;
+}
+
+int comet_timing_begin(comet_ctx* ctx, int max_launches) {
+    COMET_CHECK_CTX(ctx);
+    if (max_launches < 1 || max_launches > (1 << 20))
+        return comet_fail(ctx, COMET_EINVAL, "comet_timing_begin: bad max_launches");
+    comet_device_guard guard(ctx);
+    if (!guard.ok) return comet_fail(ctx, COMET_EDEVICE, "comet_timing_begin: cannot select device");
+    drop_events(ctx);
+    ctx->ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_launches];
+    if (!ctx->ev) return comet_fail(ctx, COMET_EINVAL, "comet_timing_begin: out of host memory");
+    for (int i = 0; i < 2 * max_launches; ++i) {
+        if (hipEventCreate(&ctx->ev[i]) != hipSuccess) {
+            ctx->ev_cap = i;
+            drop_events(ctx);
+            return comet_fail(ctx, COMET_EDEVICE, "comet_timing_begin: hipEventCreate failed");
+        }
+    }
+    ctx->ev_cap = 2 * max_launches;
+    ctx->ev_used = 0;
+    return COMET_OK;
+}
+
+int comet_timing_end(comet_ctx* ctx, double* total_ms, int* launches) {
+    COMET_CHECK_CTX(ctx);
+    if (!total_ms || !launches) return comet_fail(ctx, COMET_EINVAL, "comet_timing_end: null pointer");
+    comet_device_guard guard(ctx);
+    if (!guard.ok) return comet_fail(ctx, COMET_EDEVICE, "comet_timing_end: cannot select device");
+    double sum = 0.0;
+    int n = 0;
+    if (ctx->ev && ctx->ev_used >= 2) {
+        if (hipEventSynchronize(ctx->ev[ctx->ev_used - 1]) != hipSuccess) {
+            drop_events(ctx);
+            return comet_fail(ctx, COMET_EDEVICE, "comet_timing_end: hipEventSynchronize failed");
+        }
+        for (int i = 0; i + 1 < ctx->ev_used; i += 2) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1]) == hipSuccess) { sum += ms; ++n; }
+        }
+    }
+    drop_events(ctx);
+    *total_ms = sum;
+    *launches = n;
     return COMET_OK;
 }
 

@@ -200,73 +200,98 @@ struct Tile {
     static_assert(XVEC >= 1 && WTASK >= 1, "tile too small for the loader");
 };
 
+// Weight-side and activation-side loads of one contraction step, staged in
+// registers.  Every load is unconditional: out-of-range rows and columns are
+// clamped to a valid address instead of being predicated off.  That is exact
+// because (a) a weight column only feeds its own output column, and columns at
+// or beyond the kept width are never written back, and (b) the packed
+// activation planes hold zeros beyond the contraction length, so whatever the
+// weight side reads there is multiplied by zero.
 template <class T, int KIND>
 struct Loader {
-    // per-thread constants of the weight-side tasks
-    int col[T::WTASK];        // output column inside the problem (compact numbering)
-    long bcol[T::WTASK];      // SOMM: column offset into B (gathered); SIMM: column
-    bool col_ok[T::WTASK];
-    int oct[T::WTASK];
-    // staged registers
+    const u64* wb[T::WTASK];   // B_i at (row 0, this task's column), gather applied (SOMM)
+    const u64* wf[T::WTASK];   // F   at (row 0, this task's column)
+    bool bzero[T::WTASK];      // SOMM: the column's block id does not fit B_i -> contributes zeros
+    const unsigned char* xsrc; // this thread's first 16-byte unit of step (h = 0, s = 0)
     u32x4 xr[T::XVEC];
     u64 wr[T::WTASK][8];
 
-    __device__ __forceinline__ void setup(const GemmParams& p, int tn, int n_eff) {
+    static constexpr int XROWS2 = T::BM / 2;                 // 16-byte units per group
+    static constexpr int XGRP_PER_PASS = GT / XROWS2;        // groups covered by one pass of the block
+
+    __device__ __forceinline__ void setup(const GemmParams& p, int tm, int tn, int n_eff) {
 #pragma unroll
         for (int j = 0; j < T::WTASK; ++j) {
             const int id = threadIdx.x + GT * j;
-            const int c = id % T::BN;
-            oct[j] = id / T::BN;
-            col[j] = tn * T::BN + c;
-            col_ok[j] = col[j] < n_eff;
-            bcol[j] = col[j];
-            if (KIND == KIND_SOMM && p.b_full && col_ok[j]) {
-                const int blk = col[j] / p.bs;
+            int col = tn * T::BN + id % T::BN;
+            col = col < n_eff ? col : n_eff - 1;
+            long bcol = col;
+            bzero[j] = false;
+            if (KIND == KIND_SOMM && p.b_full) {
+                const int blk = col / p.bs;
                 const long st = block_start(p, blk);
-                bcol[j] = st < 0 ? -1 : st + (col[j] - blk * p.bs);
+                bzero[j] = st < 0;
+                bcol = st < 0 ? 0 : st + (col - blk * p.bs);
             }
+            wb[j] = p.B + bcol;
+            wf[j] = p.F + col;
         }
+        const int grp = threadIdx.x / XROWS2, within = threadIdx.x % XROWS2;
+        xsrc = p.xp + ((size_t)grp * p.mpad + (size_t)tm * T::BM) * 8 + within * 16;
     }
 
-    // issue the global loads of stacked step ks (0 .. 2 KS) into registers
-    __device__ __forceinline__ void load(const GemmParams& p, int tm, int ks, int KS, int kc) {
+    __device__ __forceinline__ void load(const GemmParams& p, int ks, int KS, int kc) {
         const int h = ks >= KS ? 1 : 0;
         const int s = ks - h * KS;
-        // activation side: linear copy of 32 groups of BM rows x 8 bytes
-        const unsigned char* xbase = p.xp + (xp_group(h, s, 0, 0, p.ks_cap) * p.mpad) * 8;
+        const unsigned char* xs = xsrc + (size_t)(h * p.ks_cap + s) * 32 * p.mpad * 8;
+        const size_t xstride = (size_t)XGRP_PER_PASS * p.mpad * 8;
 #pragma unroll
-        for (int j = 0; j < T::XVEC; ++j) {
-            const int id = threadIdx.x + GT * j;              // 16-byte unit inside the stage
-            const int grp = id / (T::BM / 2);
-            const int within = id - grp * (T::BM / 2);
-            const unsigned char* src = xbase + ((size_t)grp * p.mpad + (size_t)tm * T::BM) * 8 + within * 16;
-            xr[j] = *reinterpret_cast<const u32x4*>(src);
-        }
-        // weight side: eight consecutive-k words of one column per task
-        const u64* wsrc = h ? p.F : p.B;
-        const long ld = h ? p.ldf : p.ldb;
-        const bool gather_rows = (KIND == KIND_SIMM) && !h && p.b_full;
+        for (int j = 0; j < T::XVEC; ++j)
+            xr[j] = *reinterpret_cast<const u32x4*>(xs + j * xstride);
+
 #pragma unroll
         for (int j = 0; j < T::WTASK; ++j) {
-            const int k0 = s * KSTEP + oct[j] * 8;
-            const long cofs = (KIND == KIND_SOMM && !h) ? bcol[j] : (long)col[j];
-            int blk = 0, off = 0;
-            if (gather_rows) { blk = k0 / p.bs; off = k0 - blk * p.bs; }
+            // octet index is the same for all lanes of a wavefront
+            const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * j) / T::BN));
+            const int k0 = s * KSTEP + oct * 8;
+            const u64* src = h ? wf[j] : wb[j];
+            const long ld = h ? p.ldf : p.ldb;
+            if (KIND == KIND_SIMM && !h && p.b_full) {
+                // B_i rows are the kept neurons: compact row -> row of the full matrix
+                if ((p.bs & 7) == 0) {
+                    int kk = k0 <= kc - 8 ? k0 : kc - 8;          // kc is a positive multiple of 8 here
+                    const int blk = kk / p.bs;
+                    const long st = block_start(p, blk);
+                    const long row0 = st < 0 ? 0 : st + (kk - blk * p.bs);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int k = k0 + e;
-                u64 v = 0;
-                if (col_ok[j] && k < kc && cofs >= 0) {
-                    long row = k;
-                    if (gather_rows) {
-                        while (off >= p.bs) { off -= p.bs; ++blk; }
-                        const long st = block_start(p, blk);
-                        row = st < 0 ? -1 : st + off;
-                        ++off;
+                    for (int e = 0; e < 8; ++e) {
+                        const u64 v = src[(row0 + e) * ld];
+                        wr[j][e] = st < 0 ? 0ull : v;
                     }
-                    if (row >= 0) v = wsrc[row * ld + cofs];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int kk = (k0 + e) < kc ? (k0 + e) : kc - 1;
+                        const int blk = kk / p.bs;
+                        const long st = block_start(p, blk);
+                        const long row = st < 0 ? 0 : st + (kk - blk * p.bs);
+                        const u64 v = src[row * ld];
+                        wr[j][e] = st < 0 ? 0ull : v;
+                    }
                 }
-                wr[j][e] = v;
+            } else if (k0 + 8 <= kc) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) wr[j][e] = src[(long)(k0 + e) * ld];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int kk = (k0 + e) < kc ? (k0 + e) : kc - 1;
+                    wr[j][e] = src[(long)kk * ld];
+                }
+            }
+            if (KIND == KIND_SOMM && !h && bzero[j]) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) wr[j][e] = 0;
             }
         }
     }
@@ -274,10 +299,8 @@ struct Loader {
     // digits, byte transpose, and store of the staged registers into an LDS stage
     __device__ __forceinline__ void store(unsigned char* stage) {
 #pragma unroll
-        for (int j = 0; j < T::XVEC; ++j) {
-            const int id = threadIdx.x + GT * j;
-            *reinterpret_cast<u32x4*>(stage + id * 16) = xr[j];
-        }
+        for (int j = 0; j < T::XVEC; ++j)
+            *reinterpret_cast<u32x4*>(stage + (threadIdx.x + GT * j) * 16) = xr[j];
         unsigned char* ws = stage + T::XBYTES;
 #pragma unroll
         for (int j = 0; j < T::WTASK; ++j) {
@@ -285,13 +308,20 @@ struct Loader {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = to_digits(wr[j][e]);
             digits_to_planes(v, plane);
-            const int c = (threadIdx.x + GT * j) % T::BN;
+            const int id = threadIdx.x + GT * j;
+            const int c = id % T::BN, oct = id / T::BN;
 #pragma unroll
             for (int t = 0; t < 8; ++t)
-                *reinterpret_cast<u64*>(ws + ((size_t)(t * 4 + oct[j]) * T::BN + c) * 8) = plane[t];
+                *reinterpret_cast<u64*>(ws + ((size_t)(t * 4 + oct) * T::BN + c) * 8) = plane[t];
         }
     }
 };
+
+__device__ __forceinline__ v4i lds_frag(const unsigned char* base, int stride_bytes) {
+    const u64 x0 = *reinterpret_cast<const u64*>(base);
+    const u64 x1 = *reinterpret_cast<const u64*>(base + stride_bytes);
+    return v4i{(int)(u32)x0, (int)(u32)(x0 >> 32), (int)(u32)x1, (int)(u32)(x1 >> 32)};
+}
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND>
 __global__ __launch_bounds__(GT) void ring_gemm_kernel(GemmParams p) {
@@ -320,6 +350,9 @@ __global__ __launch_bounds__(GT) void ring_gemm_kernel(GemmParams p) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
     const int g = lane >> 5, r = lane & 31;
+    // this lane's fragment offsets inside a stage (digit 0)
+    const int a_off = ((2 * g) * T::BM + wm * WM * 32 + r) * 8;
+    const int b_off = T::XBYTES + ((2 * g) * T::BN + wn * WN * 32 + r) * 8;
 
     Loader<T, KIND> ld;
 
@@ -332,7 +365,7 @@ __global__ __launch_bounds__(GT) void ring_gemm_kernel(GemmParams p) {
         const int ks1 = ks0 + (int)len;
         const int tm = tile % tiles_m, tn = tile / tiles_m;
 
-        ld.setup(p, tn, n_eff);
+        ld.setup(p, tm, tn, n_eff);
         v16i acc[WM][WN][8];
 #pragma unroll
         for (int i = 0; i < WM; ++i)
@@ -343,39 +376,27 @@ __global__ __launch_bounds__(GT) void ring_gemm_kernel(GemmParams p) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[i][j][s][e] = 0;
 
-        ld.load(p, tm, ks0, KS, kc);
+        ld.load(p, ks0, KS, kc);
         ld.store(smem);
         __syncthreads();
         int cur = 0;
         for (int ks = ks0; ks < ks1; ++ks) {
             const bool more = ks + 1 < ks1;
-            if (more) ld.load(p, tm, ks + 1, KS, kc);
+            if (more) ld.load(p, ks + 1, KS, kc);
 
-            const unsigned char* xs = smem + cur * T::STAGE;
-            const unsigned char* ws = xs + T::XBYTES;
-            v4i a[WM][8], bf[WN][8];
+            const unsigned char* st = smem + cur * T::STAGE;
+            v4i bf[WN][8];
 #pragma unroll
-            for (int i = 0; i < WM; ++i) {
-                const int row = (wm * WM + i) * 32 + r;
+            for (int j = 0; j < WN; ++j)
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const u64 x0 = *reinterpret_cast<const u64*>(xs + ((size_t)(t * 4 + 2 * g) * T::BM + row) * 8);
-                    const u64 x1 = *reinterpret_cast<const u64*>(xs + ((size_t)(t * 4 + 2 * g + 1) * T::BM + row) * 8);
-                    a[i][t] = v4i{(int)(u32)x0, (int)(u32)(x0 >> 32), (int)(u32)x1, (int)(u32)(x1 >> 32)};
-                }
-            }
+                for (int t = 0; t < 8; ++t)
+                    bf[j][t] = lds_frag(st + b_off + (t * 4 * T::BN + j * 32) * 8, T::BN * 8);
 #pragma unroll
-            for (int j = 0; j < WN; ++j) {
-                const int colw = (wn * WN + j) * 32 + r;
+            for (int t = 0; t < 8; ++t) {
+                v4i a[WM];
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const u64 x0 = *reinterpret_cast<const u64*>(ws + ((size_t)(t * 4 + 2 * g) * T::BN + colw) * 8);
-                    const u64 x1 = *reinterpret_cast<const u64*>(ws + ((size_t)(t * 4 + 2 * g + 1) * T::BN + colw) * 8);
-                    bf[j][t] = v4i{(int)(u32)x0, (int)(u32)(x0 >> 32), (int)(u32)x1, (int)(u32)(x1 >> 32)};
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
+                for (int i = 0; i < WM; ++i)
+                    a[i] = lds_frag(st + a_off + (t * 4 * T::BM + i * 32) * 8, T::BM * 8);
 #pragma unroll
                 for (int uu = 0; uu < 8 - t; ++uu)
 #pragma unroll
@@ -383,9 +404,10 @@ __global__ __launch_bounds__(GT) void ring_gemm_kernel(GemmParams p) {
 #pragma unroll
                         for (int j = 0; j < WN; ++j)
                             acc[i][j][t + uu] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                                a[i][t], bf[j][uu], acc[i][j][t + uu], 0, 0, 0);
-
-            if (more) ld.store(smem + (cur ^ 1) * T::STAGE);
+                                a[i], bf[j][uu], acc[i][j][t + uu], 0, 0, 0);
+                // the next stage is written while the matrix cores work through the queue
+                if (t == 2 && more) ld.store(smem + (cur ^ 1) * T::STAGE);
+            }
             __syncthreads();
             cur ^= 1;
         }
@@ -428,7 +450,13 @@ int launch_gemm(comet_ctx* ctx, const char* what, const GemmParams& p, long unit
     const long want = (units_cap + 3) / 4;
     if (want < grid) grid = want < 8 ? (want < 1 ? 1 : want) : (want / 8) * 8;
     if (ctx->gemm_grid > 0) grid = ctx->gemm_grid;
+    const bool timed = ctx->ev && ctx->ev_used + 2 <= ctx->ev_cap;
+    if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], ctx->stream);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), T::SMEM, ctx->stream, p);
+    if (timed) {
+        (void)hipEventRecord(ctx->ev[ctx->ev_used + 1], ctx->stream);
+        ctx->ev_used += 2;
+    }
     COMET_LAUNCH_CHECK(ctx, what);
     return COMET_OK;
 }

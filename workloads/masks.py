@@ -94,3 +94,23 @@ def stress_mask(seed: int, stream_id: int, n_flags: int, density: float = 0.15,
         np.add.at(out, starts + s, 1)
         np.add.at(out, ends, -1)
     return (np.cumsum(out[:n_flags]) > 0).astype(np.uint8)
+
+
+def stress_mask_device(seed: int, n_flags: int, device, density: float = 0.15,
+                       mean_run: float = 4.0):
+    """The recipe of :func:`stress_mask`, drawn with torch's seeded generator on
+    ``device`` (host generation of 2^28 flags would take most of a minute).
+    Returns a uint8 tensor of 0/1 flags."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    p_start = density / mean_run
+    starts = (torch.rand(n_flags, device=device, generator=gen) < p_start).nonzero().squeeze(1)
+    v = torch.rand(starts.numel(), device=device, generator=gen).clamp_(min=1e-12)
+    runs = 1 + torch.floor(torch.log(v) / math.log1p(-1.0 / mean_run)).to(torch.int64)
+    ends = torch.clamp(starts + runs, max=n_flags)
+    delta = torch.zeros(n_flags + 1, dtype=torch.int32, device=device)
+    one = torch.ones(starts.numel(), dtype=torch.int32, device=device)
+    delta.index_add_(0, starts, one)
+    delta.index_add_(0, ends, -one)
+    return (torch.cumsum(delta[:n_flags], 0, dtype=torch.int32) > 0).to(torch.uint8)
