@@ -224,6 +224,9 @@ def main():
                     help="c1..c4, c5_d100 / c5_d050 / c5_d025 / c5_d010 / c5_d005")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true")
+    ap.add_argument("--gemm-chunk", type=int, default=0, help="tuning sweep: scheduling slice length")
+    ap.add_argument("--gemm-grid", type=int, default=0, help="tuning sweep: workgroups per launch")
+    ap.add_argument("--gemm-tile", type=int, default=0, help="tuning sweep: 2 = 64x64 tile")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (both parties are simulated on it); "
@@ -242,6 +245,9 @@ def main():
 
     cfg, wname = parse_workload(args.workload)
     ctx = comet.Context(0)
+    ctx.set_tuning(comet.TUNE_GEMM_CHUNK, args.gemm_chunk)
+    ctx.set_tuning(comet.TUNE_GEMM_GRID, args.gemm_grid)
+    ctx.set_tuning(comet.TUNE_GEMM_TILE, args.gemm_tile)
     layer = Layer(ctx, cfg, rng.BASE_SEED)
     log("workload %s: %s, m=%d d=%d f=%d bs=%d kept blocks %d/%d (n_act=%d), %.2f G ring ops/step" %
         (wname, cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs, layer.n_blk, cfg.nb,

@@ -161,8 +161,12 @@ int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64
 /* Launch-shape overrides for sweeps and for tests that must reach a particular
  * code path.  Results never depend on them.  value 0 restores the default.
  *   COMET_TUNE_GEMM_GRID: number of workgroups the share calls launch
- *                         (default: one per compute unit, fewer for tiny work) */
-enum { COMET_TUNE_GEMM_GRID = 0 };
+ *                         (default: one per compute unit, fewer for tiny work)
+ *   COMET_TUNE_GEMM_CHUNK: contraction steps (of 32 words) per scheduling slice,
+ *                         clamped to 256
+ *   COMET_TUNE_GEMM_TILE: 2 forces the 64 x 64 output tile (two workgroups per
+ *                         compute unit) whatever m is */
+enum { COMET_TUNE_GEMM_GRID = 0, COMET_TUNE_GEMM_CHUNK = 1, COMET_TUNE_GEMM_TILE = 2 };
 int comet_set_tuning(comet_ctx* ctx, int key, int value);
 
 /* Device-side timing of the ring-GEMM kernel alone (the share calls also run a

@@ -19,6 +19,8 @@ struct comet_ctx {
     int num_cu;
     hipStream_t stream;
     int gemm_grid;   // 0 = automatic
+    int gemm_chunk;  // 0 = default
+    int gemm_tile;   // 0 = automatic
     hipEvent_t* ev;  // timing event pairs, or null
     int ev_cap, ev_used;
     char err[512];

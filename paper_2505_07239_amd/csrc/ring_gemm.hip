@@ -21,12 +21,14 @@
 //     eight accumulator planes per output element, recombined at the end as
 //     sum_s sext64(S_s) << 8s.  |d e| <= 2^14 and a plane receives at most
 //     8 * 32 products per contraction step, so a plane cannot overflow within
-//     MAX_SEG = 256 steps; longer contractions are cut into segments.
+//     MAX_SEG = 256 steps; the schedule below never accumulates more than that
+//     before it flushes.
 //   * Addition mod 2^64 is associative and commutative, so partial sums may be
-//     formed in any order and by any number of workgroups: segments of the
-//     stacked contraction are dealt out evenly over a fixed, chip-sized grid
-//     (a stream-K split) and every segment ends with 64-bit atomic adds onto
-//     Z, which starts out as [C]_i.  The result is bit-exact whatever the split.
+//     formed in any order and by any number of workgroups: the (tile, slice of
+//     the stacked contraction) work units are dealt out evenly over a fixed,
+//     chip-sized grid (a stream-K split) and every run of units inside one
+//     tile ends with 64-bit atomic adds onto Z, which starts out as [C]_i.
+//     The result is bit-exact whatever the split.
 //
 // Data flow
 //   xpack kernel : E, A_i  -> digit planes of [E | A'] in the workspace, laid
@@ -37,6 +39,12 @@
 //                  to v_mfma_i32_32x32x32_i8.  The weight matrices are the
 //                  large operands; they are never re-written to memory.
 #include "common.h"
+
+#include <type_traits>
+
+#ifndef EXP_VALU_PER_MFMA
+#define EXP_VALU_PER_MFMA 3
+#endif
 
 namespace {
 
@@ -52,12 +60,18 @@ constexpr u64 DIGIT_BIAS = 0x0080808080808080ull;
 constexpr int KIND_SOMM = 0;
 constexpr int KIND_SIMM = 1;
 
+// how the weight-side rows of B_i are addressed (SIMM with a full-size B_i only)
+constexpr int GATHER_NONE = 0;   // rows are the compact contraction index
+constexpr int GATHER_POW2 = 1;   // block gather, bs a power of two >= 8
+constexpr int GATHER_ANY = 2;    // block gather, any bs
+
 struct GemmParams {
     int kind, party;
     int m;          // rows of X / Z
     int kc_cap;     // contraction length bound: SOMM k, SIMM n_blk_cap * bs
     int n_cap;      // output width bound: SOMM n_blk_cap * bs, SIMM n
     int bs, n_blk_cap;
+    int bs_shift;   // log2(bs) when bs is a power of two, else -1
     int full_extent; // length of the axis blk_idx refers to (neurons)
     const int* blk_idx;
     const int* n_blk_dev;
@@ -72,6 +86,7 @@ struct GemmParams {
     // packed digit planes of [E | A']
     unsigned char* xp;
     int mpad;       // rows of xp, multiple of 128
+    int chunk;      // contraction steps per scheduling slice, 1 .. MAX_SEG
     int ks_cap;     // contraction steps per half, ceil(kc_cap / 32)
 };
 
@@ -121,11 +136,12 @@ __device__ __forceinline__ void digits_to_planes(const u64 (&v)[8], u64 (&plane)
     for (int t = 0; t < 8; ++t) plane[t] = (u64)a[t] | ((u64)b[t] << 32);
 }
 
-// Packed layout of [E | A'] (bytes): group (half h, step s, digit t, octet q)
-// is a run of mpad rows x 8 bytes; the 8 bytes are digit t of words
-// k = 32 s + 8 q + 0..7 of that row.  Groups are ordered (h, s, t, q).
-__device__ __host__ __forceinline__ size_t xp_group(int h, int s, int t, int q, int ks_cap) {
-    return ((((size_t)h * ks_cap + s) * 8 + t) * 4 + q);
+// Packed layout of [E | A'] in 16-byte units: group (half h, step s, digit t,
+// k-half g) is a run of mpad units, one per row; the 16 bytes of a unit are
+// digit t of words k = 32 s + 16 g + 0..15 of that row, which is exactly what
+// one lane feeds to v_mfma_i32_32x32x32_i8.  Groups are ordered (h, s, t, g).
+__device__ __host__ __forceinline__ size_t xp_group(int h, int s, int t, int g, int ks_cap) {
+    return ((((size_t)h * ks_cap + s) * 8 + t) * 2 + g);
 }
 
 // ---------------------------------------------------------------------------
@@ -135,43 +151,48 @@ __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
     const int nblk = n_blocks(p);
     const int kc = p.kind == KIND_SOMM ? p.kc_cap : nblk * p.bs;
     const int row = blockIdx.y * 128 + threadIdx.x;    // < mpad by construction (128 threads)
-    const int oct = blockIdx.x;                        // octet index over the half: 0 .. ks_cap*4
+    const int half16 = blockIdx.x;                     // 16-word group over the half: 0 .. ks_cap*2
     const int h = blockIdx.z;                          // 0: E, 1: A'
-    const int k0 = oct * 8;
-    u64 v[8];
+    const int k0 = half16 * 16;
+    u64 plane[2][8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = 0;
-    if (row < p.m && k0 < kc) {
-        int blk = 0, off = 0;
-        if (h == 1 && p.a_full) { blk = k0 / p.bs; off = k0 - blk * p.bs; }
+    for (int o = 0; o < 2; ++o) {
+        u64 v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int k = k0 + j;
-            if (k < kc) {
-                const u64 e = p.E[(size_t)row * p.lde + k];
-                u64 x = e;
-                if (h == 1) {
-                    long col = k;
-                    if (p.a_full) {
-                        while (off >= p.bs) { off -= p.bs; ++blk; }
-                        const long st = block_start(p, blk);
-                        col = st < 0 ? -1 : st + off;
-                        ++off;
+        for (int j = 0; j < 8; ++j) v[j] = 0;
+        const int kb = k0 + 8 * o;
+        if (row < p.m && kb < kc) {
+            int blk = 0, off = 0;
+            if (h == 1 && p.a_full) { blk = kb / p.bs; off = kb - blk * p.bs; }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int k = kb + j;
+                if (k < kc) {
+                    const u64 e = p.E[(size_t)row * p.lde + k];
+                    u64 x = e;
+                    if (h == 1) {
+                        long col = k;
+                        if (p.a_full) {
+                            while (off >= p.bs) { off -= p.bs; ++blk; }
+                            const long st = block_start(p, blk);
+                            col = st < 0 ? -1 : st + off;
+                            ++off;
+                        }
+                        const u64 a = col < 0 ? 0ull : p.A[(size_t)row * p.lda + col];
+                        x = a + (p.party ? e : 0ull);
                     }
-                    const u64 a = col < 0 ? 0ull : p.A[(size_t)row * p.lda + col];
-                    x = a + (p.party ? e : 0ull);
+                    v[j] = to_digits(x);
                 }
-                v[j] = to_digits(x);
             }
         }
+        digits_to_planes(v, plane[o]);
     }
-    u64 plane[8];
-    digits_to_planes(v, plane);
-    const int s = oct >> 2, q = oct & 3;
+    const int s = half16 >> 1, g = half16 & 1;
+    typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-        u64* dst = reinterpret_cast<u64*>(p.xp) + xp_group(h, s, t, q, p.ks_cap) * p.mpad + row;
-        *dst = plane[t];
+        u64x2* dst = reinterpret_cast<u64x2*>(p.xp) + xp_group(h, s, t, g, p.ks_cap) * p.mpad + row;
+        *dst = u64x2{plane[0][t], plane[1][t]};
     }
 }
 
@@ -190,34 +211,57 @@ template <int WAVES_M, int WAVES_N, int WM, int WN>
 struct Tile {
     static constexpr int BM = 32 * WM * WAVES_M;
     static constexpr int BN = 32 * WN * WAVES_N;
-    static constexpr int XBYTES = BM * 256;          // 8 digits x 4 octets x BM rows x 8 bytes
+    static constexpr int XBYTES = BM * 256;          // 8 digits x 2 k-halves x BM rows x 16 bytes
     static constexpr int WBYTES = BN * 256;
-    static constexpr int STAGE = XBYTES + WBYTES;
-    static constexpr int SMEM = 2 * STAGE;
-    static constexpr int XVEC = XBYTES / 16 / GT;    // 16-byte vectors per thread per stage
+    static constexpr int XSTAGES = 3;                // written by LDS-DMA two steps ahead
+    static constexpr int WSTAGES = 2;                // written from registers one step ahead
+    static constexpr int WBASE = XSTAGES * XBYTES;
+    static constexpr int SMEM = XSTAGES * XBYTES + WSTAGES * WBYTES;
+    static constexpr int XVEC = XBYTES / 16 / GT;    // 16-byte units per thread per stage
     static constexpr int WTASK = BN * 4 / GT;        // (column, octet) tasks per thread per stage
+    static constexpr int VM_PER_STEP = XVEC + 8 * WTASK;   // vector-memory loads a thread issues per step
     static_assert(WAVES_M * WAVES_N * 64 == GT, "four wavefronts per workgroup");
     static_assert(XVEC >= 1 && WTASK >= 1, "tile too small for the loader");
+    static_assert(VM_PER_STEP < 63, "outstanding-load counter has 6 bits");
+    static_assert(SMEM <= 160 * 1024, "LDS of one CDNA4 compute unit");
 };
 
-// Weight-side and activation-side loads of one contraction step, staged in
-// registers.  Every load is unconditional: out-of-range rows and columns are
-// clamped to a valid address instead of being predicated off.  That is exact
-// because (a) a weight column only feeds its own output column, and columns at
-// or beyond the kept width are never written back, and (b) the packed
-// activation planes hold zeros beyond the contraction length, so whatever the
-// weight side reads there is multiplied by zero.
-template <class T, int KIND>
+// Workgroup barrier of the main loop.  Waits until at most N of this
+// wavefront's vector-memory loads are still in flight (loads return in order,
+// so everything older than the N youngest has landed, including LDS-DMA
+// writes) and until all of its LDS accesses are done, then meets the other
+// wavefronts.  Written out by hand because the generic barrier would also
+// wait for the LDS-DMA loads that were only just issued for a later step.
+template <int N>
+__device__ __forceinline__ void wait_and_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// Loads of one contraction step.
+//
+// Activation side: the packed digit planes go from global memory straight into
+// LDS (global_load_lds_dwordx4: every lane supplies its own global address, the
+// wavefront's 64 x 16 bytes land contiguously at a wave-uniform LDS address),
+// so they occupy no registers and need no LDS store.
+//
+// Weight side: raw uint64 words into registers; digits, byte transpose and the
+// LDS store happen one step later (store()).  Every load is unconditional:
+// out-of-range rows and columns are clamped to a valid address instead of being
+// predicated off.  That is exact because (a) a weight column only feeds its own
+// output column, and columns at or beyond the kept width are never written
+// back, and (b) the packed activation planes hold zeros beyond the contraction
+// length, so whatever the weight side reads there is multiplied by zero.
+template <class T, int KIND, int GMODE>
 struct Loader {
     const u64* wb[T::WTASK];   // B_i at (row 0, this task's column), gather applied (SOMM)
     const u64* wf[T::WTASK];   // F   at (row 0, this task's column)
     bool bzero[T::WTASK];      // SOMM: the column's block id does not fit B_i -> contributes zeros
+    unsigned wzero[T::WTASK];  // bit e set: word e in flight is replaced by zero when staged
     const unsigned char* xsrc; // this thread's first 16-byte unit of step (h = 0, s = 0)
-    u32x4 xr[T::XVEC];
-    u64 wr[T::WTASK][8];
+    u64 wr[T::WTASK][8];       // weight words in flight (staged into LDS one step later)
 
-    static constexpr int XROWS2 = T::BM / 2;                 // 16-byte units per group
-    static constexpr int XGRP_PER_PASS = GT / XROWS2;        // groups covered by one pass of the block
+    static constexpr int XGRP_PER_PASS = GT / T::BM;         // groups covered by one pass of the block
+    static_assert(GT % T::BM == 0, "tile rows must divide the block");
 
     __device__ __forceinline__ void setup(const GemmParams& p, int tm, int tn, int n_eff) {
 #pragma unroll
@@ -236,97 +280,170 @@ struct Loader {
             wb[j] = p.B + bcol;
             wf[j] = p.F + col;
         }
-        const int grp = threadIdx.x / XROWS2, within = threadIdx.x % XROWS2;
-        xsrc = p.xp + ((size_t)grp * p.mpad + (size_t)tm * T::BM) * 8 + within * 16;
+        const int grp = threadIdx.x / T::BM, within = threadIdx.x % T::BM;
+        xsrc = p.xp + ((size_t)grp * p.mpad + (size_t)tm * T::BM + within) * 16;
     }
 
-    __device__ __forceinline__ void load(const GemmParams& p, int ks, int KS, int kc) {
+    // activation planes of stacked step ks -> LDS stage at xstage (asynchronous)
+    __device__ __forceinline__ void load_x(const GemmParams& p, int ks, int KS, unsigned char* xstage) {
         const int h = ks >= KS ? 1 : 0;
         const int s = ks - h * KS;
-        const unsigned char* xs = xsrc + (size_t)(h * p.ks_cap + s) * 32 * p.mpad * 8;
-        const size_t xstride = (size_t)XGRP_PER_PASS * p.mpad * 8;
+        const unsigned char* xs = xsrc + (size_t)(h * p.ks_cap + s) * 16 * p.mpad * 16;
+        const size_t xstride = (size_t)XGRP_PER_PASS * p.mpad * 16;
+        const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+        const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)xstage;
 #pragma unroll
-        for (int j = 0; j < T::XVEC; ++j)
-            xr[j] = *reinterpret_cast<const u32x4*>(xs + j * xstride);
+        for (int j = 0; j < T::XVEC; ++j) {
+            // Issued as plain text so that the compiler's own wait-count bookkeeping does not
+            // treat every later LDS read as dependent on this transfer; the waits that order it
+            // are the explicit ones in wait_and_barrier().  M0 carries the wave's LDS address.
+            const unsigned lds = __builtin_amdgcn_readfirstlane(lds0 + (wave * 64 + GT * j) * 16);
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :
+                         : "s"(lds), "v"(xs + j * xstride)
+                         : "memory", "m0");
+        }
+    }
 
+    // weight words of stacked step ks -> registers.  Straight-line code: the
+    // choice between the two halves of the stacked contraction and the row
+    // gather are selects on wave-uniform values, not branches.
+    __device__ __forceinline__ void load_w(const GemmParams& p, int ks, int KS, int kc) {
+        const int h = ks >= KS ? 1 : 0;
+        const int s = ks - h * KS;
+        const long ld = h ? p.ldf : p.ldb;
 #pragma unroll
         for (int j = 0; j < T::WTASK; ++j) {
             // octet index is the same for all lanes of a wavefront
             const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * j) / T::BN));
             const int k0 = s * KSTEP + oct * 8;
             const u64* src = h ? wf[j] : wb[j];
-            const long ld = h ? p.ldf : p.ldb;
-            if (KIND == KIND_SIMM && !h && p.b_full) {
-                // B_i rows are the kept neurons: compact row -> row of the full matrix
-                if ((p.bs & 7) == 0) {
-                    int kk = k0 <= kc - 8 ? k0 : kc - 8;          // kc is a positive multiple of 8 here
-                    const int blk = kk / p.bs;
-                    const long st = block_start(p, blk);
-                    const long row0 = st < 0 ? 0 : st + (kk - blk * p.bs);
+            unsigned zero = (KIND == KIND_SOMM && !h && bzero[j]) ? 0xffu : 0u;
+            long row[8];
+            if (GMODE == GATHER_NONE) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const u64 v = src[(row0 + e) * ld];
-                        wr[j][e] = st < 0 ? 0ull : v;
-                    }
-                } else {
+                for (int e = 0; e < 8; ++e) row[e] = (k0 + e) < kc ? (k0 + e) : kc - 1;
+            } else if (GMODE == GATHER_POW2) {
+                // B_i rows are the kept neurons; bs is a power of two >= 8, so an octet of
+                // compact rows lies inside one block and kc is a positive multiple of 8
+                const int kk = k0 <= kc - 8 ? k0 : kc - 8;
+                const int blk = kk >> p.bs_shift;
+                const long st = block_start(p, blk);
+                const long g0 = (st < 0 ? 0 : st) + (kk & (p.bs - 1));
+                if (!h && st < 0) zero = 0xffu;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int kk = (k0 + e) < kc ? (k0 + e) : kc - 1;
-                        const int blk = kk / p.bs;
-                        const long st = block_start(p, blk);
-                        const long row = st < 0 ? 0 : st + (kk - blk * p.bs);
-                        const u64 v = src[row * ld];
-                        wr[j][e] = st < 0 ? 0ull : v;
-                    }
+                for (int e = 0; e < 8; ++e) {
+                    const long plain = (k0 + e) < kc ? (k0 + e) : kc - 1;
+                    row[e] = h ? plain : g0 + e;
                 }
-            } else if (k0 + 8 <= kc) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) wr[j][e] = src[(long)(k0 + e) * ld];
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int kk = (k0 + e) < kc ? (k0 + e) : kc - 1;
-                    wr[j][e] = src[(long)kk * ld];
+                    const int blk = kk / p.bs;
+                    const long st = block_start(p, blk);
+                    if (!h && st < 0) zero |= 1u << e;
+                    row[e] = h ? (long)kk : (st < 0 ? 0 : st) + (kk - blk * p.bs);
                 }
             }
-            if (KIND == KIND_SOMM && !h && bzero[j]) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) wr[j][e] = 0;
-            }
+            for (int e = 0; e < 8; ++e) wr[j][e] = src[row[e] * ld];
+            wzero[j] = zero;
         }
     }
 
-    // digits, byte transpose, and store of the staged registers into an LDS stage
-    __device__ __forceinline__ void store(unsigned char* stage) {
-#pragma unroll
-        for (int j = 0; j < T::XVEC; ++j)
-            *reinterpret_cast<u32x4*>(stage + (threadIdx.x + GT * j) * 16) = xr[j];
-        unsigned char* ws = stage + T::XBYTES;
+    // digits, byte transpose, and LDS store of the staged registers
+    __device__ __forceinline__ void store_w(unsigned char* wstage) {
 #pragma unroll
         for (int j = 0; j < T::WTASK; ++j) {
             u64 v[8], plane[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = to_digits(wr[j][e]);
+            for (int e = 0; e < 8; ++e) v[e] = ((wzero[j] >> e) & 1u) ? 0ull : to_digits(wr[j][e]);
             digits_to_planes(v, plane);
             const int id = threadIdx.x + GT * j;
             const int c = id % T::BN, oct = id / T::BN;
 #pragma unroll
             for (int t = 0; t < 8; ++t)
-                *reinterpret_cast<u64*>(ws + ((size_t)(t * 4 + oct) * T::BN + c) * 8) = plane[t];
+                *reinterpret_cast<u64*>(wstage + ((size_t)(t * 2 + (oct >> 1)) * T::BN + c) * 16 + (oct & 1) * 8) = plane[t];
         }
     }
 };
 
-__device__ __forceinline__ v4i lds_frag(const unsigned char* base, int stride_bytes) {
-    const u64 x0 = *reinterpret_cast<const u64*>(base);
-    const u64 x1 = *reinterpret_cast<const u64*>(base + stride_bytes);
-    return v4i{(int)(u32)x0, (int)(u32)(x0 >> 32), (int)(u32)x1, (int)(u32)(x1 >> 32)};
+__device__ __forceinline__ v4i lds_frag(const unsigned char* p) {
+    return *reinterpret_cast<const v4i*>(p);
 }
 
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND>
-__global__ __launch_bounds__(GT) void ring_gemm_kernel(GemmParams p) {
+// One contraction step of a workgroup: 36 * WM * WN matrix instructions on the
+// fragments of activation stage xs and weight stage ws.  The same straight-line
+// block also stages the weight words of the next step (requested one step ago),
+// reuses their registers for the step after it and starts that step's activation
+// planes on their way; it has no branches so that the instruction scheduler can
+// weave that work between the matrix instructions (the sched_group_barrier
+// pattern at the end).  ks_next2 is clamped by the caller: past the end of a
+// segment the look-ahead work is redundant but harmless.
+template <class T, int KIND, int GMODE, int WM, int WN>
+__device__ __forceinline__ void gemm_step(const GemmParams& p, Loader<T, KIND, GMODE>& ld,
+                                          v16i (&acc)[WM][WN][8], const unsigned char* xs,
+                                          const unsigned char* ws, unsigned char* ws_next,
+                                          unsigned char* xs_next2, int a_off, int b_off,
+                                          int ks_next2, int KS, int kc) {
+    v4i bf[WN][8];
+    v4i a[8][WM];
+#pragma unroll
+    for (int ii = 0; ii < WM; ++ii) a[0][ii] = lds_frag(xs + a_off + (ii * 32) * 16);
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) bf[j][t] = lds_frag(ws + b_off + (t * 2 * T::BN + j * 32) * 16);
+#pragma unroll
+    for (int t = 1; t < 8; ++t)
+#pragma unroll
+        for (int ii = 0; ii < WM; ++ii)
+            a[t][ii] = lds_frag(xs + a_off + (t * 2 * T::BM + ii * 32) * 16);
+
+    ld.store_w(ws_next);
+    ld.load_w(p, ks_next2, KS, kc);
+    ld.load_x(p, ks_next2, KS, xs_next2);
+
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int uu = 0; uu < 8 - t; ++uu)
+#pragma unroll
+            for (int ii = 0; ii < WM; ++ii)
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    acc[ii][j][t + uu] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                        a[t][ii], bf[j][uu], acc[ii][j][t + uu], 0, 0, 0);
+
+    // Issue order asked of the scheduler: after each matrix instruction one LDS access, a few
+    // vector ALU instructions and one global load, for as long as there are any left.
+#ifndef EXP_NOSGB
+    __builtin_amdgcn_sched_group_barrier(0x100, WM + 1, 0);       // first fragments
+#pragma unroll
+    for (int m = 0; m < 36 * WM * WN; ++m) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // matrix instruction
+        if (m < 8 * (WM + WN) - (WM + 1)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+        __builtin_amdgcn_sched_group_barrier(0x002, EXP_VALU_PER_MFMA, 0);                     // vector ALU
+        if (m >= 12 && m < 12 + 8 * T::WTASK) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // LDS write
+        if (m >= 24 && m < 24 + 8 * T::WTASK) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // global load
+    }
+#endif
+    // The activation planes of the next step were requested one step ago; only the loads
+    // issued during this step may still be in flight past this point.
+    wait_and_barrier<T::VM_PER_STEP>();
+}
+
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE>
+__global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
-    extern __shared__ __align__(16) unsigned char smem[];
+    // Three activation stages filled by LDS-DMA two steps ahead, as separate
+    // arrays so that the compiler can tell a stage being filled from the one
+    // being read; two weight stages written from registers one step ahead.
+    __shared__ __align__(16) unsigned char xs0[T::XBYTES];
+    __shared__ __align__(16) unsigned char xs1[T::XBYTES];
+    __shared__ __align__(16) unsigned char xs2[T::XBYTES];
+    __shared__ __align__(16) unsigned char wsm[T::WSTAGES * T::WBYTES];
 
     const int nblk = n_blocks(p);
     const int n_eff = KIND == KIND_SOMM ? nblk * p.bs : p.n_cap;
@@ -339,8 +456,7 @@ __global__ __launch_bounds__(GT) void ring_gemm_kernel(GemmParams p) {
     if (units == 0) return;
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one
-    // contiguous range of work so that tiles sharing weight columns meet in
-    // the same L2.
+    // contiguous range of work units.
     const int G = gridDim.x;
     int b = blockIdx.x;
     if ((G & 7) == 0) b = (b & 7) * (G >> 3) + (b >> 3);
@@ -351,18 +467,30 @@ __global__ __launch_bounds__(GT) void ring_gemm_kernel(GemmParams p) {
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
     const int g = lane >> 5, r = lane & 31;
     // this lane's fragment offsets inside a stage (digit 0)
-    const int a_off = ((2 * g) * T::BM + wm * WM * 32 + r) * 8;
-    const int b_off = T::XBYTES + ((2 * g) * T::BN + wn * WN * 32 + r) * 8;
+    const int a_off = (g * T::BM + wm * WM * 32 + r) * 16;
+    const int b_off = (g * T::BN + wn * WN * 32 + r) * 16;
 
-    Loader<T, KIND> ld;
+    Loader<T, KIND, GMODE> ld;
 
+    // Work units are ordered chunk-major: all tiles for contraction steps
+    // [0, CH), then all tiles for [CH, 2 CH), ...  Workgroups that run side by
+    // side therefore sweep the same slice of the contraction at the same time
+    // (the activation planes of that slice stay hot in L2) and each XCD ends up
+    // with whole slices, so a weight word is fetched from HBM by one XCD only.
+    const int CH = p.chunk;
+    const int tiles = tiles_m * tiles_n;
+    const long full_chunk_units = (long)tiles * CH;
+    const int n_chunks = (KT + CH - 1) / CH;
     while (u < u_end) {
-        const int tile = (int)(u / KT);
-        const int ks0 = (int)(u - (long)tile * KT);
-        long len = KT - ks0;
+        int c = (int)(u / full_chunk_units);
+        if (c > n_chunks - 1) c = n_chunks - 1;
+        const long rem = u - (long)c * full_chunk_units;
+        const int clen = (c == n_chunks - 1) ? KT - c * CH : CH;
+        const int tile = (int)(rem / clen);
+        const int ks0 = c * CH + (int)(rem - (long)tile * clen);
+        long len = c * CH + clen - ks0;
         if (len > u_end - u) len = u_end - u;
-        if (len > MAX_SEG) len = MAX_SEG;
-        const int ks1 = ks0 + (int)len;
+        const int L = (int)len;
         const int tm = tile % tiles_m, tn = tile / tiles_m;
 
         ld.setup(p, tm, tn, n_eff);
@@ -376,41 +504,35 @@ __global__ __launch_bounds__(GT) void ring_gemm_kernel(GemmParams p) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[i][j][s][e] = 0;
 
-        ld.load(p, ks0, KS, kc);
-        ld.store(smem);
-        __syncthreads();
-        int cur = 0;
-        for (int ks = ks0; ks < ks1; ++ks) {
-            const bool more = ks + 1 < ks1;
-            if (more) ld.load(p, ks + 1, KS, kc);
-
-            const unsigned char* st = smem + cur * T::STAGE;
-            v4i bf[WN][8];
-#pragma unroll
-            for (int j = 0; j < WN; ++j)
-#pragma unroll
-                for (int t = 0; t < 8; ++t)
-                    bf[j][t] = lds_frag(st + b_off + (t * 4 * T::BN + j * 32) * 8, T::BN * 8);
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                v4i a[WM];
-#pragma unroll
-                for (int i = 0; i < WM; ++i)
-                    a[i] = lds_frag(st + a_off + (t * 4 * T::BM + i * 32) * 8, T::BM * 8);
-#pragma unroll
-                for (int uu = 0; uu < 8 - t; ++uu)
-#pragma unroll
-                    for (int i = 0; i < WM; ++i)
-#pragma unroll
-                        for (int j = 0; j < WN; ++j)
-                            acc[i][j][t + uu] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                                a[i], bf[j][uu], acc[i][j][t + uu], 0, 0, 0);
-                // the next stage is written while the matrix cores work through the queue
-                if (t == 2 && more) ld.store(smem + (cur ^ 1) * T::STAGE);
-            }
-            __syncthreads();
-            cur ^= 1;
+        // prologue: step ks0 staged, step ks0+1 on its way
+        ld.load_x(p, ks0, KS, xs0);
+        ld.load_w(p, ks0, KS, kc);
+        ld.store_w(wsm);
+        {
+            const int ksn = ks0 + 1 < KT ? ks0 + 1 : KT - 1;
+            ld.load_w(p, ksn, KS, kc);
+            ld.load_x(p, ksn, KS, xs1);
         }
+        wait_and_barrier<T::VM_PER_STEP>();
+
+        const int ks_last = ks0 + L - 1;
+        for (int i = 0; i < L; i += 3) {
+            const int k2 = ks0 + i + 2;
+            gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs0, wsm + (i & 1) * T::WBYTES,
+                                       wsm + ((i + 1) & 1) * T::WBYTES, xs2, a_off, b_off,
+                                       k2 < ks_last ? k2 : ks_last, KS, kc);
+            if (i + 1 < L)
+                gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs1, wsm + ((i + 1) & 1) * T::WBYTES,
+                                           wsm + (i & 1) * T::WBYTES, xs0, a_off, b_off,
+                                           k2 + 1 < ks_last ? k2 + 1 : ks_last, KS, kc);
+            if (i + 2 < L)
+                gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs2, wsm + (i & 1) * T::WBYTES,
+                                           wsm + ((i + 1) & 1) * T::WBYTES, xs1, a_off, b_off,
+                                           k2 + 2 < ks_last ? k2 + 2 : ks_last, KS, kc);
+        }
+        // the look-ahead transfers of the last steps are redundant; let them land before the
+        // stages are reused
+        wait_and_barrier<0>();
 
         // recombine the eight planes and add the partial sum onto Z
 #pragma unroll
@@ -434,25 +556,24 @@ __global__ __launch_bounds__(GT) void ring_gemm_kernel(GemmParams p) {
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 int launch_gemm(comet_ctx* ctx, const char* what, const GemmParams& p, long units_cap) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
-    auto kern = p.kind == KIND_SOMM ? ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM>
-                                    : ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM>;
-    static bool lds_reserved[2][64] = {};
-    const int dev_slot = ctx->device & 63;
-    if (!lds_reserved[p.kind][dev_slot]) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, T::SMEM) != hipSuccess)
-            return comet_fail(ctx, COMET_EDEVICE, "%s: cannot reserve %d bytes of LDS", what, T::SMEM);
-        lds_reserved[p.kind][dev_slot] = true;
+    void (*kern)(GemmParams) = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, GATHER_NONE>;
+    if (p.kind == KIND_SIMM) {
+        if (!p.b_full)
+            kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_NONE>;
+        else if (p.bs_shift >= 3)
+            kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_POW2>;
+        else
+            kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_ANY>;
     }
     // a chip-sized grid, shrunk when there is too little work to share out
-    long grid = (ctx->num_cu / 8) * 8;
+    long grid = (ctx->num_cu / 8) * 8 * (WM * WN == 1 ? 2 : 1);
     if (grid < 8) grid = 8;
     const long want = (units_cap + 3) / 4;
     if (want < grid) grid = want < 8 ? (want < 1 ? 1 : want) : (want / 8) * 8;
     if (ctx->gemm_grid > 0) grid = ctx->gemm_grid;
     const bool timed = ctx->ev && ctx->ev_used + 2 <= ctx->ev_cap;
     if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], ctx->stream);
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), T::SMEM, ctx->stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), 0, ctx->stream, p);
     if (timed) {
         (void)hipEventRecord(ctx->ev[ctx->ev_used + 1], ctx->stream);
         ctx->ev_used += 2;
@@ -483,6 +604,10 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     p.xp = static_cast<unsigned char*>(ws);
     p.mpad = round_up(p.m, 128);
     p.ks_cap = (p.kc_cap + KSTEP - 1) / KSTEP;
+    p.bs_shift = -1;
+    for (int sh = 0; sh < 30; ++sh)
+        if (p.bs == (1 << sh)) p.bs_shift = sh;
+    p.chunk = ctx->gemm_chunk > 0 ? (ctx->gemm_chunk < MAX_SEG ? ctx->gemm_chunk : MAX_SEG) : 16;
 
     if (p.n_cap == 0) return COMET_OK;
     // Z := C on the kept region
@@ -499,11 +624,15 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         }
     }
     if (p.ks_cap == 0) return COMET_OK;
-    hipLaunchKernelGGL(xpack_kernel, dim3((unsigned)(p.ks_cap * 4), (unsigned)(p.mpad / 128), 2),
+    hipLaunchKernelGGL(xpack_kernel, dim3((unsigned)(p.ks_cap * 2), (unsigned)(p.mpad / 128), 2),
                        dim3(128), 0, ctx->stream, p);
     COMET_LAUNCH_CHECK(ctx, what);
 
     const long kt = 2l * p.ks_cap;
+    if (ctx->gemm_tile == 2) {
+        const long units = (long)((p.m + 63) / 64) * ((p.n_cap + 63) / 64) * kt;
+        return launch_gemm<2, 2, 1, 1>(ctx, what, p, units);
+    }
     if (p.m <= 32) {
         const long units = (long)((p.m + 31) / 32) * ((p.n_cap + 255) / 256) * kt;
         return launch_gemm<1, 4, 1, 2>(ctx, what, p, units);
