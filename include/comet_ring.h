@@ -131,8 +131,11 @@ int comet_compact_mask(comet_ctx* ctx, const uint8_t* mask, int64_t n_tok, int64
  *            the kernel), else k x ld
  *   C_i,Z_i: m x ld   (compact; C = A B on the kept columns)
  * ld = n_blk_cap * bs; column c of a compact operand is neuron
- * blk_idx[c / bs] * bs + c % bs.  Z_i must not alias any input.
- * Limits: 1 <= m, k, bs; m, k, ld, n_full < 2^24. */
+ * blk_idx[c / bs] * bs + c % bs.  Z_i must not alias any input.  A block id
+ * that does not fit n_full is read as block 0 (the outputs it feeds are then
+ * meaningless; no access ever leaves the operands).
+ * Limits: 1 <= m, k, bs; m < 2^23; k, ld, n_full < 2^24; F and B_i hold fewer
+ * than 2^31 words each. */
 int comet_somm_share(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_full, int bs,
                      const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap, int flags,
                      const uint64_t* E, const uint64_t* F, const uint64_t* A_i,
@@ -148,8 +151,10 @@ int comet_somm_share(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_
  *   B_i    : k_full x n when flags & COMET_FULL_B, else ld x n
  *   C_i,Z_i: m x n    (C = A_sel B_sel)
  * ld = n_blk_cap * bs; only the first n_blk * bs columns of E / rows of F are
- * contracted.  Z_i must not alias any input.
- * Limits: 1 <= m, n, bs; m, n, ld, k_full < 2^24. */
+ * contracted.  Z_i must not alias any input.  A block id that does not fit
+ * k_full is read as block 0 (see comet_somm_share).
+ * Limits: 1 <= m, n, bs; m < 2^23; n, ld, k_full < 2^24; F and B_i hold fewer
+ * than 2^31 words each. */
 int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64_t n, int bs,
                      const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap, int flags,
                      const uint64_t* E, const uint64_t* F, const uint64_t* A_i,

@@ -11,6 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcomet_ring.so")
 SOURCES = ["ctx.hip", "elementwise.hip", "compact.hip", "ring_gemm.hip", "probe.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=default",
+         # the LDS-DMA helper names M0 as clobbered, which clang flags as a reserved register
+         "-Wno-inline-asm",
          # packed-FP32 instruction selection is switched off for every device pass
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -41,10 +41,8 @@
 #include "common.h"
 
 #include <type_traits>
+#include <utility>
 
-#ifndef EXP_VALU_PER_MFMA
-#define EXP_VALU_PER_MFMA 3
-#endif
 
 namespace {
 
@@ -100,7 +98,8 @@ __device__ __forceinline__ int n_blocks(const GemmParams& p) {
 }
 
 // Start of block `blk` on the indexed axis, or -1 when the id does not fit the
-// axis (such ids contribute zeros instead of faulting).
+// axis.  Callers clamp such a block to the start of the axis: a bad id can make
+// the outputs it feeds meaningless, but it can never make an access fault.
 __device__ __forceinline__ long block_start(const GemmParams& p, int blk) {
     const long s = (long)p.blk_idx[blk] * p.bs;
     return (s < 0 || s + p.bs > p.full_extent) ? -1 : s;
@@ -237,44 +236,66 @@ __device__ __forceinline__ void wait_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-// Loads of one contraction step.
+// Loads and staging of the operands, cut into small pieces.
+//
+// A contraction step issues 36 * WM * WN matrix instructions.  Everything else
+// a step has to do -- start the LDS-DMA of the activation planes two steps
+// ahead, load the weight words two steps ahead, turn the weight words of the
+// next step into digit planes and store them to LDS -- is cut into pieces of a
+// handful of instructions, and gemm_step() places one or two pieces behind
+// each matrix instruction so that they execute in its shadow.
 //
 // Activation side: the packed digit planes go from global memory straight into
 // LDS (global_load_lds_dwordx4: every lane supplies its own global address, the
 // wavefront's 64 x 16 bytes land contiguously at a wave-uniform LDS address),
 // so they occupy no registers and need no LDS store.
 //
-// Weight side: raw uint64 words into registers; digits, byte transpose and the
-// LDS store happen one step later (store()).  Every load is unconditional:
-// out-of-range rows and columns are clamped to a valid address instead of being
-// predicated off.  That is exact because (a) a weight column only feeds its own
-// output column, and columns at or beyond the kept width are never written
-// back, and (b) the packed activation planes hold zeros beyond the contraction
-// length, so whatever the weight side reads there is multiplied by zero.
+// Weight side: raw uint64 words into registers ("next" set), moved to the
+// "staged" set at the end of the step, and converted during the following
+// step.  Every load is unconditional: out-of-range rows and columns are clamped
+// to a valid address instead of being predicated off.  That is exact because
+// (a) a weight column only feeds its own output column, and columns at or
+// beyond the kept width are never written back, and (b) the packed activation
+// planes hold zeros beyond the contraction length, so whatever the weight side
+// reads there is multiplied by zero.
 template <class T, int KIND, int GMODE>
 struct Loader {
-    const u64* wb[T::WTASK];   // B_i at (row 0, this task's column), gather applied (SOMM)
-    const u64* wf[T::WTASK];   // F   at (row 0, this task's column)
-    bool bzero[T::WTASK];      // SOMM: the column's block id does not fit B_i -> contributes zeros
-    unsigned wzero[T::WTASK];  // bit e set: word e in flight is replaced by zero when staged
+    static constexpr int W = T::WTASK;
+    const u64* wb[W];          // B_i at (row 0, this task's column), gather applied (SOMM)
+    const u64* wf[W];          // F   at (row 0, this task's column)
     const unsigned char* xsrc; // this thread's first 16-byte unit of step (h = 0, s = 0)
-    u64 wr[T::WTASK][8];       // weight words in flight (staged into LDS one step later)
+    u64 wn[W][8];              // weight words in flight (two steps ahead)
+    u64 wa[W][8];              // weight words being staged (one step ahead), then their digits
+    u32 pl[W][16];             // transposed digits: [t] = words 0..3, [8 + t] = words 4..7
+    // wave-uniform state of the look-ahead step, set by begin()
+    int h2, s2;
+    int ld2;                   // row pitch of the weight-side source in words
+    const unsigned char* xs2;
+    size_t xstride;            // bytes between the 16-byte units one thread moves per step
+    int g0[W];                 // GATHER_POW2: first gathered row of this task's octet
 
     static constexpr int XGRP_PER_PASS = GT / T::BM;         // groups covered by one pass of the block
     static_assert(GT % T::BM == 0, "tile rows must divide the block");
 
+    // piece list of one step, in execution order
+    static constexpr int P_DMA = 0;
+    static constexpr int P_LOAD = P_DMA + T::XVEC;
+    static constexpr int P_DIGIT = P_LOAD + 8 * W;
+    static constexpr int P_TRANS = P_DIGIT + 8 * W;
+    static constexpr int P_WRITE = P_TRANS + 4 * W;
+    static constexpr int P_MOVE = P_WRITE + 8 * W;
+    static constexpr int P_END = P_MOVE + 8 * W;
+
     __device__ __forceinline__ void setup(const GemmParams& p, int tm, int tn, int n_eff) {
 #pragma unroll
-        for (int j = 0; j < T::WTASK; ++j) {
+        for (int j = 0; j < W; ++j) {
             const int id = threadIdx.x + GT * j;
             int col = tn * T::BN + id % T::BN;
             col = col < n_eff ? col : n_eff - 1;
             long bcol = col;
-            bzero[j] = false;
             if (KIND == KIND_SOMM && p.b_full) {
                 const int blk = col / p.bs;
                 const long st = block_start(p, blk);
-                bzero[j] = st < 0;
                 bcol = st < 0 ? 0 : st + (col - blk * p.bs);
             }
             wb[j] = p.B + bcol;
@@ -282,156 +303,196 @@ struct Loader {
         }
         const int grp = threadIdx.x / T::BM, within = threadIdx.x % T::BM;
         xsrc = p.xp + ((size_t)grp * p.mpad + (size_t)tm * T::BM + within) * 16;
+        xstride = (size_t)XGRP_PER_PASS * p.mpad * 16;
     }
 
-    // activation planes of stacked step ks -> LDS stage at xstage (asynchronous)
-    __device__ __forceinline__ void load_x(const GemmParams& p, int ks, int KS, unsigned char* xstage) {
-        const int h = ks >= KS ? 1 : 0;
-        const int s = ks - h * KS;
-        const unsigned char* xs = xsrc + (size_t)(h * p.ks_cap + s) * 16 * p.mpad * 16;
-        const size_t xstride = (size_t)XGRP_PER_PASS * p.mpad * 16;
+    // fix the step the following dma / load pieces work on
+    __device__ __forceinline__ void begin(const GemmParams& p, int ks, int KS) {
+        h2 = ks >= KS ? 1 : 0;
+        s2 = ks - h2 * KS;
+        ld2 = (int)(h2 ? p.ldf : p.ldb);
+        xs2 = xsrc + (size_t)(h2 * p.ks_cap + s2) * 16 * p.mpad * 16;
+    }
+
+    // one 16-byte unit per lane of the activation planes -> LDS stage (asynchronous)
+    template <int J>
+    __device__ __forceinline__ void dma_piece(const GemmParams& p, unsigned char* xstage) {
         const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
         const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)xstage;
-#pragma unroll
-        for (int j = 0; j < T::XVEC; ++j) {
-            // Issued as plain text so that the compiler's own wait-count bookkeeping does not
-            // treat every later LDS read as dependent on this transfer; the waits that order it
-            // are the explicit ones in wait_and_barrier().  M0 carries the wave's LDS address.
-            const unsigned lds = __builtin_amdgcn_readfirstlane(lds0 + (wave * 64 + GT * j) * 16);
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :
-                         : "s"(lds), "v"(xs + j * xstride)
-                         : "memory", "m0");
-        }
+        // Issued as plain text so that the compiler's own wait-count bookkeeping does not treat
+        // every later LDS read as dependent on this transfer; the waits that order it are the
+        // explicit ones in wait_and_barrier().  M0 carries the wave's LDS address.
+        const unsigned lds = __builtin_amdgcn_readfirstlane(lds0 + (wave * 64 + GT * J) * 16);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :
+                     : "s"(lds), "v"(xs2 + J * xstride)
+                     : "memory", "m0");
     }
 
-    // weight words of stacked step ks -> registers.  Straight-line code: the
-    // choice between the two halves of the stacked contraction and the row
-    // gather are selects on wave-uniform values, not branches.
-    __device__ __forceinline__ void load_w(const GemmParams& p, int ks, int KS, int kc) {
-        const int h = ks >= KS ? 1 : 0;
-        const int s = ks - h * KS;
-        const long ld = h ? p.ldf : p.ldb;
-#pragma unroll
-        for (int j = 0; j < T::WTASK; ++j) {
-            // octet index is the same for all lanes of a wavefront
-            const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * j) / T::BN));
-            const int k0 = s * KSTEP + oct * 8;
-            const u64* src = h ? wf[j] : wb[j];
-            unsigned zero = (KIND == KIND_SOMM && !h && bzero[j]) ? 0xffu : 0u;
-            long row[8];
-            if (GMODE == GATHER_NONE) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) row[e] = (k0 + e) < kc ? (k0 + e) : kc - 1;
-            } else if (GMODE == GATHER_POW2) {
-                // B_i rows are the kept neurons; bs is a power of two >= 8, so an octet of
-                // compact rows lies inside one block and kc is a positive multiple of 8
-                const int kk = k0 <= kc - 8 ? k0 : kc - 8;
-                const int blk = kk >> p.bs_shift;
-                const long st = block_start(p, blk);
-                const long g0 = (st < 0 ? 0 : st) + (kk & (p.bs - 1));
-                if (!h && st < 0) zero = 0xffu;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const long plain = (k0 + e) < kc ? (k0 + e) : kc - 1;
-                    row[e] = h ? plain : g0 + e;
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int kk = (k0 + e) < kc ? (k0 + e) : kc - 1;
-                    const int blk = kk / p.bs;
-                    const long st = block_start(p, blk);
-                    if (!h && st < 0) zero |= 1u << e;
-                    row[e] = h ? (long)kk : (st < 0 ? 0 : st) + (kk - blk * p.bs);
-                }
+    // word E of task J -> wn.  The choice between the two halves of the stacked
+    // contraction and the row gather are selects on wave-uniform values.
+    template <int J, int E>
+    __device__ __forceinline__ void load_piece(const GemmParams& p, int kc) {
+        // octet index is the same for all lanes of a wavefront
+        const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * J) / T::BN));
+        const int k0 = s2 * KSTEP + oct * 8;
+        const u64* src = h2 ? wf[J] : wb[J];
+        const int kk = (k0 + E) < kc ? (k0 + E) : kc - 1;
+        int row = kk;
+        if (GMODE == GATHER_POW2) {
+            // B_i rows are the kept neurons; bs is a power of two >= 8, so an octet of
+            // compact rows lies inside one block and kc is a positive multiple of 8
+            if (E == 0) {
+                const int kb = k0 <= kc - 8 ? k0 : kc - 8;
+                const long st = block_start(p, kb >> p.bs_shift);
+                g0[J] = (int)(st < 0 ? 0 : st) + (kb & (p.bs - 1));
             }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) wr[j][e] = src[row[e] * ld];
-            wzero[j] = zero;
+            row = h2 ? kk : g0[J] + E;
+        } else if (GMODE == GATHER_ANY) {
+            const int blk = kk / p.bs;
+            const long st = block_start(p, blk);
+            row = h2 ? kk : (int)(st < 0 ? 0 : st) + (kk - blk * p.bs);
         }
+        // every operand holds fewer than 2^31 words (host check), so the word offset fits 32 bits
+        const unsigned off = (unsigned)row * (unsigned)ld2;
+        wn[J][E] = src[off];
     }
 
-    // digits, byte transpose, and LDS store of the staged registers
-    __device__ __forceinline__ void store_w(unsigned char* wstage) {
-#pragma unroll
-        for (int j = 0; j < T::WTASK; ++j) {
-            u64 v[8], plane[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = ((wzero[j] >> e) & 1u) ? 0ull : to_digits(wr[j][e]);
-            digits_to_planes(v, plane);
-            const int id = threadIdx.x + GT * j;
-            const int c = id % T::BN, oct = id / T::BN;
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-                *reinterpret_cast<u64*>(wstage + ((size_t)(t * 2 + (oct >> 1)) * T::BN + c) * 16 + (oct & 1) * 8) = plane[t];
-        }
+    // word E of task J of the staged set -> signed digits
+    template <int J, int E>
+    __device__ __forceinline__ void digit_piece() {
+        wa[J][E] = to_digits(wa[J][E]);
     }
+
+    // quarter Q of the byte transpose of task J: Q = 0: low digits of words 0..3,
+    // 1: high digits of words 0..3, 2: low digits of words 4..7, 3: high digits of words 4..7
+    template <int J, int Q>
+    __device__ __forceinline__ void transpose_piece() {
+        constexpr int e0 = (Q >> 1) * 4, d0 = (Q & 1) * 4, o = (Q >> 1) * 8 + d0;
+        u32 x[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = (Q & 1) ? (u32)(wa[J][e0 + i] >> 32) : (u32)wa[J][e0 + i];
+        transpose4(x[0], x[1], x[2], x[3], pl[J][o], pl[J][o + 1], pl[J][o + 2], pl[J][o + 3]);
+    }
+
+    // digit plane Tt of task J -> LDS
+    template <int J, int Tt>
+    __device__ __forceinline__ void write_piece(unsigned char* wstage) {
+        const int id = threadIdx.x + GT * J;
+        const int c = id % T::BN, oct = id / T::BN;
+        const u64 v = (u64)pl[J][Tt] | ((u64)pl[J][8 + Tt] << 32);
+        // weight stage layout: 8-byte units ordered (digit, k-half, octet-in-half, column), so
+        // that the 64 lanes of a store hit 64 consecutive units
+        *reinterpret_cast<u64*>(wstage + ((size_t)(Tt * 4 + oct) * T::BN + c) * 8) = v;
+    }
+
+    // the words that were in flight become the staged set of the next step
+    template <int J, int E>
+    __device__ __forceinline__ void move_piece() {
+        wa[J][E] = wn[J][E];
+    }
+
+    template <int P>
+    __device__ __forceinline__ void piece(const GemmParams& p, int kc, unsigned char* xstage,
+                                          unsigned char* wstage) {
+        if constexpr (P < P_LOAD) dma_piece<P - P_DMA>(p, xstage);
+        else if constexpr (P < P_DIGIT) load_piece<(P - P_LOAD) / 8, (P - P_LOAD) % 8>(p, kc);
+        else if constexpr (P < P_TRANS) digit_piece<(P - P_DIGIT) / 8, (P - P_DIGIT) % 8>();
+        else if constexpr (P < P_WRITE) transpose_piece<(P - P_TRANS) / 4, (P - P_TRANS) % 4>();
+        else if constexpr (P < P_MOVE) write_piece<(P - P_WRITE) / 8, (P - P_WRITE) % 8>(wstage);
+        else if constexpr (P < P_END) move_piece<(P - P_MOVE) / 8, (P - P_MOVE) % 8>();
+    }
+
+    template <int P0, int... Ps>
+    __device__ __forceinline__ void pieces(std::integer_sequence<int, Ps...>, const GemmParams& p,
+                                           int kc, unsigned char* xstage, unsigned char* wstage) {
+        (piece<P0 + Ps>(p, kc, xstage, wstage), ...);
+    }
+
 };
 
 __device__ __forceinline__ v4i lds_frag(const unsigned char* p) {
     return *reinterpret_cast<const v4i*>(p);
 }
 
+// weight-side fragment: the two octets of a k-half sit stride_bytes apart
+__device__ __forceinline__ v4i lds_frag2(const unsigned char* p, int stride_bytes) {
+    const u64 x0 = *reinterpret_cast<const u64*>(p);
+    const u64 x1 = *reinterpret_cast<const u64*>(p + stride_bytes);
+    return v4i{(int)(u32)x0, (int)(u32)(x0 >> 32), (int)(u32)x1, (int)(u32)(x1 >> 32)};
+}
+
+// position of matrix instruction M inside a step: digit plane t of the activation side,
+// weight digit uu, wave sub-tiles (ii, j)
+template <int WM, int WN>
+struct SlotMap {
+    static constexpr int per_t(int t) { return (8 - t) * WM * WN; }
+    static constexpr int t_of(int m) {
+        int t = 0;
+        while (m >= per_t(t)) { m -= per_t(t); ++t; }
+        return t;
+    }
+    static constexpr int in_t(int m) {
+        int t = 0;
+        while (m >= per_t(t)) { m -= per_t(t); ++t; }
+        return m;
+    }
+};
+
 // One contraction step of a workgroup: 36 * WM * WN matrix instructions on the
-// fragments of activation stage xs and weight stage ws.  The same straight-line
-// block also stages the weight words of the next step (requested one step ago),
-// reuses their registers for the step after it and starts that step's activation
-// planes on their way; it has no branches so that the instruction scheduler can
-// weave that work between the matrix instructions (the sched_group_barrier
-// pattern at the end).  ks_next2 is clamped by the caller: past the end of a
-// segment the look-ahead work is redundant but harmless.
+// fragments of activation stage xs and weight stage ws, each followed by its
+// share of the look-ahead pieces (see Loader).  The scheduling fences keep the
+// compiler from regrouping them.  ks_next2 is clamped by the caller: past the
+// end of a segment the look-ahead work is redundant but harmless.
+template <class T, int KIND, int GMODE, int WM, int WN, int... Ms>
+__device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>, const GemmParams& p,
+                                               Loader<T, KIND, GMODE>& ld, v16i (&acc)[WM][WN][8],
+                                               const unsigned char* xs, const unsigned char* ws,
+                                               unsigned char* ws_next, unsigned char* xs_next2,
+                                               int a_off, int b_off, int ks_next2, int KS, int kc) {
+    using L = Loader<T, KIND, GMODE>;
+    using SM = SlotMap<WM, WN>;
+    constexpr int NM = 36 * WM * WN;
+    v4i bf[WN][8];
+    v4i a[8][WM];
+    ld.begin(p, ks_next2, KS);
+    // all fragment reads of the step, in the order the matrix instructions consume them
+#pragma unroll
+    for (int ii = 0; ii < WM; ++ii) a[0][ii] = lds_frag(xs + a_off + (ii * 32) * 16);
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) bf[j][t] = lds_frag2(ws + b_off + (t * 4 * T::BN + j * 32) * 8, T::BN * 8);
+#pragma unroll
+    for (int t = 1; t < 8; ++t)
+#pragma unroll
+        for (int ii = 0; ii < WM; ++ii) a[t][ii] = lds_frag(xs + a_off + (t * 2 * T::BM + ii * 32) * 16);
+    __builtin_amdgcn_sched_barrier(0);
+    (
+        [&] {
+            constexpr int M = Ms;
+            constexpr int t = SM::t_of(M), r = SM::in_t(M);
+            constexpr int uu = r / (WM * WN), ii = (r / WN) % WM, j = r % WN;
+            acc[ii][j][t + uu] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t][ii], bf[j][uu],
+                                                                        acc[ii][j][t + uu], 0, 0, 0);
+            constexpr int p0 = (int)((long)M * L::P_END / NM), p1 = (int)((long)(M + 1) * L::P_END / NM);
+            ld.template pieces<p0>(std::make_integer_sequence<int, p1 - p0>{}, p, kc, xs_next2, ws_next);
+            __builtin_amdgcn_sched_barrier(0);
+        }(),
+        ...);
+    // The activation planes of the next step were requested one step ago; only the loads
+    // issued during this step may still be in flight past this point.
+    wait_and_barrier<T::VM_PER_STEP>();
+}
+
 template <class T, int KIND, int GMODE, int WM, int WN>
 __device__ __forceinline__ void gemm_step(const GemmParams& p, Loader<T, KIND, GMODE>& ld,
                                           v16i (&acc)[WM][WN][8], const unsigned char* xs,
                                           const unsigned char* ws, unsigned char* ws_next,
                                           unsigned char* xs_next2, int a_off, int b_off,
                                           int ks_next2, int KS, int kc) {
-    v4i bf[WN][8];
-    v4i a[8][WM];
-#pragma unroll
-    for (int ii = 0; ii < WM; ++ii) a[0][ii] = lds_frag(xs + a_off + (ii * 32) * 16);
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-#pragma unroll
-        for (int j = 0; j < WN; ++j) bf[j][t] = lds_frag(ws + b_off + (t * 2 * T::BN + j * 32) * 16);
-#pragma unroll
-    for (int t = 1; t < 8; ++t)
-#pragma unroll
-        for (int ii = 0; ii < WM; ++ii)
-            a[t][ii] = lds_frag(xs + a_off + (t * 2 * T::BM + ii * 32) * 16);
-
-    ld.store_w(ws_next);
-    ld.load_w(p, ks_next2, KS, kc);
-    ld.load_x(p, ks_next2, KS, xs_next2);
-
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-#pragma unroll
-        for (int uu = 0; uu < 8 - t; ++uu)
-#pragma unroll
-            for (int ii = 0; ii < WM; ++ii)
-#pragma unroll
-                for (int j = 0; j < WN; ++j)
-                    acc[ii][j][t + uu] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                        a[t][ii], bf[j][uu], acc[ii][j][t + uu], 0, 0, 0);
-
-    // Issue order asked of the scheduler: after each matrix instruction one LDS access, a few
-    // vector ALU instructions and one global load, for as long as there are any left.
-#ifndef EXP_NOSGB
-    __builtin_amdgcn_sched_group_barrier(0x100, WM + 1, 0);       // first fragments
-#pragma unroll
-    for (int m = 0; m < 36 * WM * WN; ++m) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // matrix instruction
-        if (m < 8 * (WM + WN) - (WM + 1)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
-        __builtin_amdgcn_sched_group_barrier(0x002, EXP_VALU_PER_MFMA, 0);                     // vector ALU
-        if (m >= 12 && m < 12 + 8 * T::WTASK) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // LDS write
-        if (m >= 24 && m < 24 + 8 * T::WTASK) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // global load
-    }
-#endif
-    // The activation planes of the next step were requested one step ago; only the loads
-    // issued during this step may still be in flight past this point.
-    wait_and_barrier<T::VM_PER_STEP>();
+    gemm_step_impl<T, KIND, GMODE, WM, WN>(std::make_integer_sequence<int, 36 * WM * WN>{}, p, ld, acc,
+                                           xs, ws, ws_next, xs_next2, a_off, b_off, ks_next2, KS, kc);
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE>
@@ -468,7 +529,7 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
     const int g = lane >> 5, r = lane & 31;
     // this lane's fragment offsets inside a stage (digit 0)
     const int a_off = (g * T::BM + wm * WM * 32 + r) * 16;
-    const int b_off = (g * T::BN + wn * WN * 32 + r) * 16;
+    const int b_off = (2 * g * T::BN + wn * WN * 32 + r) * 8;
 
     Loader<T, KIND, GMODE> ld;
 
@@ -504,16 +565,19 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[i][j][s][e] = 0;
 
-        // prologue: step ks0 staged, step ks0+1 on its way
-        ld.load_x(p, ks0, KS, xs0);
-        ld.load_w(p, ks0, KS, kc);
-        ld.store_w(wsm);
+        // prologue: step ks0 staged, step ks0+1 in flight
         {
+            using LD = Loader<T, KIND, GMODE>;
+            ld.begin(p, ks0, KS);
+            ld.template pieces<LD::P_DMA>(std::make_integer_sequence<int, LD::P_DIGIT - LD::P_DMA>{}, p, kc, xs0, wsm);
+            ld.template pieces<LD::P_MOVE>(std::make_integer_sequence<int, LD::P_END - LD::P_MOVE>{}, p, kc, xs0, wsm);
+            ld.template pieces<LD::P_DIGIT>(std::make_integer_sequence<int, LD::P_MOVE - LD::P_DIGIT>{}, p, kc, xs0, wsm);
             const int ksn = ks0 + 1 < KT ? ks0 + 1 : KT - 1;
-            ld.load_w(p, ksn, KS, kc);
-            ld.load_x(p, ksn, KS, xs1);
+            ld.begin(p, ksn, KS);
+            ld.template pieces<LD::P_DMA>(std::make_integer_sequence<int, LD::P_DIGIT - LD::P_DMA>{}, p, kc, xs1, wsm);
+            ld.template pieces<LD::P_MOVE>(std::make_integer_sequence<int, LD::P_END - LD::P_MOVE>{}, p, kc, xs1, wsm);
         }
-        wait_and_barrier<T::VM_PER_STEP>();
+        wait_and_barrier<0>();
 
         const int ks_last = ks0 + L - 1;
         for (int i = 0; i < L; i += 3) {
@@ -607,7 +671,7 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     p.bs_shift = -1;
     for (int sh = 0; sh < 30; ++sh)
         if (p.bs == (1 << sh)) p.bs_shift = sh;
-    p.chunk = ctx->gemm_chunk > 0 ? (ctx->gemm_chunk < MAX_SEG ? ctx->gemm_chunk : MAX_SEG) : 16;
+    p.chunk = ctx->gemm_chunk > 0 ? (ctx->gemm_chunk < MAX_SEG ? ctx->gemm_chunk : MAX_SEG) : 128;
 
     if (p.n_cap == 0) return COMET_OK;
     // Z := C on the kept region
@@ -684,6 +748,8 @@ int comet_somm_share(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_
     const int64_t ld = (int64_t)n_blk_cap * bs;
     if ((flags & COMET_FULL_B) && ld > n_full)
         return comet_fail(ctx, COMET_EINVAL, "%s: n_blk_cap * bs exceeds n_full", what);
+    if (k * ((flags & COMET_FULL_B) ? n_full : ld) >= (1ll << 31) || k * ld >= (1ll << 31))
+        return comet_fail(ctx, COMET_ECAP, "%s: a weight-side operand holds 2^31 words or more", what);
     GemmParams p = {};
     p.kind = KIND_SOMM; p.party = party; p.m = (int)m; p.kc_cap = (int)k; p.n_cap = (int)ld;
     p.bs = bs; p.n_blk_cap = n_blk_cap; p.blk_idx = blk_idx; p.n_blk_dev = n_blk_dev;
@@ -711,6 +777,8 @@ int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64
     const int64_t ld = (int64_t)n_blk_cap * bs;
     if ((flags & (COMET_FULL_A | COMET_FULL_B)) && ld > k_full)
         return comet_fail(ctx, COMET_EINVAL, "%s: n_blk_cap * bs exceeds k_full", what);
+    if (((flags & COMET_FULL_B) ? k_full : ld) * n >= (1ll << 31))
+        return comet_fail(ctx, COMET_ECAP, "%s: a weight-side operand holds 2^31 words or more", what);
     GemmParams p = {};
     p.kind = KIND_SIMM; p.party = party; p.m = (int)m; p.kc_cap = (int)ld; p.n_cap = (int)n;
     p.bs = bs; p.n_blk_cap = n_blk_cap; p.blk_idx = blk_idx; p.n_blk_dev = n_blk_dev;
