@@ -250,9 +250,8 @@ __device__ __forceinline__ void wait_and_barrier() {
 // wavefront's 64 x 16 bytes land contiguously at a wave-uniform LDS address),
 // so they occupy no registers and need no LDS store.
 //
-// Weight side: raw uint64 words into registers ("next" set), moved to the
-// "staged" set at the end of the step, and converted during the following
-// step.  Every load is unconditional: out-of-range rows and columns are clamped
+// Weight side: raw uint64 words into registers; one step later each word is
+// split into digits and its register immediately reused for the next request.  Every load is unconditional: out-of-range rows and columns are clamped
 // to a valid address instead of being predicated off.  That is exact because
 // (a) a weight column only feeds its own output column, and columns at or
 // beyond the kept width are never written back, and (b) the packed activation
@@ -264,8 +263,8 @@ struct Loader {
     const u64* wb[W];          // B_i at (row 0, this task's column), gather applied (SOMM)
     const u64* wf[W];          // F   at (row 0, this task's column)
     const unsigned char* xsrc; // this thread's first 16-byte unit of step (h = 0, s = 0)
-    u64 wn[W][8];              // weight words in flight (two steps ahead)
-    u64 wa[W][8];              // weight words being staged (one step ahead), then their digits
+    u64 wn[W][8];              // weight words in flight (requested one step before they are split)
+    u64 wa[W][8];              // digits of the weight words being staged for the next step
     u32 pl[W][16];             // transposed digits: [t] = words 0..3, [8 + t] = words 4..7
     // wave-uniform state of the look-ahead step, set by begin()
     int h2, s2;
@@ -273,18 +272,17 @@ struct Loader {
     const unsigned char* xs2;
     size_t xstride;            // bytes between the 16-byte units one thread moves per step
     int g0[W];                 // GATHER_POW2: first gathered row of this task's octet
+    int gpend[W];              // GATHER_POW2: block id requested for the step after this one
 
     static constexpr int XGRP_PER_PASS = GT / T::BM;         // groups covered by one pass of the block
     static_assert(GT % T::BM == 0, "tile rows must divide the block");
 
     // piece list of one step, in execution order
     static constexpr int P_DMA = 0;
-    static constexpr int P_LOAD = P_DMA + T::XVEC;
-    static constexpr int P_DIGIT = P_LOAD + 8 * W;
-    static constexpr int P_TRANS = P_DIGIT + 8 * W;
+    static constexpr int P_LOAD = P_DMA + T::XVEC;     // split word e into digits, then reload it
+    static constexpr int P_TRANS = P_LOAD + 8 * W;
     static constexpr int P_WRITE = P_TRANS + 4 * W;
-    static constexpr int P_MOVE = P_WRITE + 8 * W;
-    static constexpr int P_END = P_MOVE + 8 * W;
+    static constexpr int P_END = P_WRITE + 8 * W;
 
     __device__ __forceinline__ void setup(const GemmParams& p, int tm, int tn, int n_eff) {
 #pragma unroll
@@ -306,12 +304,48 @@ struct Loader {
         xstride = (size_t)XGRP_PER_PASS * p.mpad * 16;
     }
 
-    // fix the step the following dma / load pieces work on
-    __device__ __forceinline__ void begin(const GemmParams& p, int ks, int KS) {
+    // block id that holds compact row octet (step ks, task j); GATHER_POW2 only
+    __device__ __forceinline__ int gather_id(const GemmParams& p, int ks, int KS, int kc, int j) {
+        const int h = ks >= KS ? 1 : 0;
+        const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * j) / T::BN));
+        const int k0 = (ks - h * KS) * KSTEP + oct * 8;
+        const int kb = k0 <= kc - 8 ? k0 : kc - 8;
+        return p.blk_idx[h ? 0 : (kb >> p.bs_shift)];
+    }
+
+    // first step of a segment: nothing has been requested ahead yet
+    __device__ __forceinline__ void prime(const GemmParams& p, int ks, int KS, int kc) {
+        if (GMODE == GATHER_POW2) {
+#pragma unroll
+            for (int j = 0; j < W; ++j) gpend[j] = gather_id(p, ks, KS, kc, j);
+        }
+    }
+
+    // Fix the step the following dma / load pieces work on.  Steps are visited in
+    // order (ks, then ks + 1 capped at ks_limit), which lets the block id of the
+    // next step be requested here, a whole step before it is needed: the scalar
+    // load returns long before the next call consumes it, so consuming it never
+    // stalls on the LDS reads that share its counter.
+    __device__ __forceinline__ void begin(const GemmParams& p, int ks, int KS, int kc, int ks_limit) {
         h2 = ks >= KS ? 1 : 0;
         s2 = ks - h2 * KS;
         ld2 = (int)(h2 ? p.ldf : p.ldb);
         xs2 = xsrc + (size_t)(h2 * p.ks_cap + s2) * 16 * p.mpad * 16;
+        if (GMODE == GATHER_POW2) {
+            const int ksn = ks + 1 < ks_limit ? ks + 1 : ks_limit;
+#pragma unroll
+            for (int j = 0; j < W; ++j) {
+                // consumed here, ahead of the fragment reads (the scheduling fence that follows
+                // them keeps this arithmetic from sinking to its first use)
+                const int id = __builtin_amdgcn_readfirstlane(gpend[j]);
+                const long st = (long)id * p.bs;
+                const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * j) / T::BN));
+                const int k0 = s2 * KSTEP + oct * 8;
+                const int kb = k0 <= kc - 8 ? k0 : kc - 8;
+                g0[j] = (int)((st < 0 || st + p.bs > p.full_extent) ? 0 : st) + (kb & (p.bs - 1));
+                gpend[j] = gather_id(p, ksn, KS, kc, j);
+            }
+        }
     }
 
     // one 16-byte unit per lane of the activation planes -> LDS stage (asynchronous)
@@ -329,10 +363,13 @@ struct Loader {
                      : "memory", "m0");
     }
 
-    // word E of task J -> wn.  The choice between the two halves of the stacked
-    // contraction and the row gather are selects on wave-uniform values.
-    template <int J, int E>
+    // Word E of task J: split the word that is in the register into digits
+    // (it was requested a step ago), then request the word of the step fixed by
+    // begin() into the same register.  The choice between the two halves of the
+    // stacked contraction and the row gather are selects on wave-uniform values.
+    template <int J, int E, bool SPLIT>
     __device__ __forceinline__ void load_piece(const GemmParams& p, int kc) {
+        if (SPLIT) wa[J][E] = to_digits(wn[J][E]);
         // octet index is the same for all lanes of a wavefront
         const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * J) / T::BN));
         const int k0 = s2 * KSTEP + oct * 8;
@@ -340,13 +377,8 @@ struct Loader {
         const int kk = (k0 + E) < kc ? (k0 + E) : kc - 1;
         int row = kk;
         if (GMODE == GATHER_POW2) {
-            // B_i rows are the kept neurons; bs is a power of two >= 8, so an octet of
-            // compact rows lies inside one block and kc is a positive multiple of 8
-            if (E == 0) {
-                const int kb = k0 <= kc - 8 ? k0 : kc - 8;
-                const long st = block_start(p, kb >> p.bs_shift);
-                g0[J] = (int)(st < 0 ? 0 : st) + (kb & (p.bs - 1));
-            }
+            // B_i rows are the kept neurons; bs is a power of two >= 8, so an octet of compact
+            // rows lies inside one block (g0 is its first row, set by begin())
             row = h2 ? kk : g0[J] + E;
         } else if (GMODE == GATHER_ANY) {
             const int blk = kk / p.bs;
@@ -356,12 +388,6 @@ struct Loader {
         // every operand holds fewer than 2^31 words (host check), so the word offset fits 32 bits
         const unsigned off = (unsigned)row * (unsigned)ld2;
         wn[J][E] = src[off];
-    }
-
-    // word E of task J of the staged set -> signed digits
-    template <int J, int E>
-    __device__ __forceinline__ void digit_piece() {
-        wa[J][E] = to_digits(wa[J][E]);
     }
 
     // quarter Q of the byte transpose of task J: Q = 0: low digits of words 0..3,
@@ -386,27 +412,19 @@ struct Loader {
         *reinterpret_cast<u64*>(wstage + ((size_t)(Tt * 4 + oct) * T::BN + c) * 8) = v;
     }
 
-    // the words that were in flight become the staged set of the next step
-    template <int J, int E>
-    __device__ __forceinline__ void move_piece() {
-        wa[J][E] = wn[J][E];
-    }
-
-    template <int P>
+    template <int P, bool SPLIT>
     __device__ __forceinline__ void piece(const GemmParams& p, int kc, unsigned char* xstage,
                                           unsigned char* wstage) {
         if constexpr (P < P_LOAD) dma_piece<P - P_DMA>(p, xstage);
-        else if constexpr (P < P_DIGIT) load_piece<(P - P_LOAD) / 8, (P - P_LOAD) % 8>(p, kc);
-        else if constexpr (P < P_TRANS) digit_piece<(P - P_DIGIT) / 8, (P - P_DIGIT) % 8>();
+        else if constexpr (P < P_TRANS) load_piece<(P - P_LOAD) / 8, (P - P_LOAD) % 8, SPLIT>(p, kc);
         else if constexpr (P < P_WRITE) transpose_piece<(P - P_TRANS) / 4, (P - P_TRANS) % 4>();
-        else if constexpr (P < P_MOVE) write_piece<(P - P_WRITE) / 8, (P - P_WRITE) % 8>(wstage);
-        else if constexpr (P < P_END) move_piece<(P - P_MOVE) / 8, (P - P_MOVE) % 8>();
+        else if constexpr (P < P_END) write_piece<(P - P_WRITE) / 8, (P - P_WRITE) % 8>(wstage);
     }
 
-    template <int P0, int... Ps>
+    template <int P0, bool SPLIT, int... Ps>
     __device__ __forceinline__ void pieces(std::integer_sequence<int, Ps...>, const GemmParams& p,
                                            int kc, unsigned char* xstage, unsigned char* wstage) {
-        (piece<P0 + Ps>(p, kc, xstage, wstage), ...);
+        (piece<P0 + Ps, SPLIT>(p, kc, xstage, wstage), ...);
     }
 
 };
@@ -449,13 +467,13 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
                                                Loader<T, KIND, GMODE>& ld, v16i (&acc)[WM][WN][8],
                                                const unsigned char* xs, const unsigned char* ws,
                                                unsigned char* ws_next, unsigned char* xs_next2,
-                                               int a_off, int b_off, int ks_next2, int KS, int kc) {
+                                               int a_off, int b_off, int ks_next2, int ks_limit, int KS, int kc) {
     using L = Loader<T, KIND, GMODE>;
     using SM = SlotMap<WM, WN>;
     constexpr int NM = 36 * WM * WN;
     v4i bf[WN][8];
     v4i a[8][WM];
-    ld.begin(p, ks_next2, KS);
+    ld.begin(p, ks_next2, KS, kc, ks_limit);
     // all fragment reads of the step, in the order the matrix instructions consume them
 #pragma unroll
     for (int ii = 0; ii < WM; ++ii) a[0][ii] = lds_frag(xs + a_off + (ii * 32) * 16);
@@ -476,7 +494,7 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
             acc[ii][j][t + uu] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t][ii], bf[j][uu],
                                                                         acc[ii][j][t + uu], 0, 0, 0);
             constexpr int p0 = (int)((long)M * L::P_END / NM), p1 = (int)((long)(M + 1) * L::P_END / NM);
-            ld.template pieces<p0>(std::make_integer_sequence<int, p1 - p0>{}, p, kc, xs_next2, ws_next);
+            ld.template pieces<p0, true>(std::make_integer_sequence<int, p1 - p0>{}, p, kc, xs_next2, ws_next);
             __builtin_amdgcn_sched_barrier(0);
         }(),
         ...);
@@ -490,9 +508,10 @@ __device__ __forceinline__ void gemm_step(const GemmParams& p, Loader<T, KIND, G
                                           v16i (&acc)[WM][WN][8], const unsigned char* xs,
                                           const unsigned char* ws, unsigned char* ws_next,
                                           unsigned char* xs_next2, int a_off, int b_off,
-                                          int ks_next2, int KS, int kc) {
+                                          int ks_next2, int ks_limit, int KS, int kc) {
     gemm_step_impl<T, KIND, GMODE, WM, WN>(std::make_integer_sequence<int, 36 * WM * WN>{}, p, ld, acc,
-                                           xs, ws, ws_next, xs_next2, a_off, b_off, ks_next2, KS, kc);
+                                           xs, ws, ws_next, xs_next2, a_off, b_off, ks_next2, ks_limit,
+                                           KS, kc);
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE>
@@ -566,33 +585,30 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
                     for (int e = 0; e < 16; ++e) acc[i][j][s][e] = 0;
 
         // prologue: step ks0 staged, step ks0+1 in flight
+        const int ks_last = ks0 + L - 1;
         {
             using LD = Loader<T, KIND, GMODE>;
-            ld.begin(p, ks0, KS);
-            ld.template pieces<LD::P_DMA>(std::make_integer_sequence<int, LD::P_DIGIT - LD::P_DMA>{}, p, kc, xs0, wsm);
-            ld.template pieces<LD::P_MOVE>(std::make_integer_sequence<int, LD::P_END - LD::P_MOVE>{}, p, kc, xs0, wsm);
-            ld.template pieces<LD::P_DIGIT>(std::make_integer_sequence<int, LD::P_MOVE - LD::P_DIGIT>{}, p, kc, xs0, wsm);
-            const int ksn = ks0 + 1 < KT ? ks0 + 1 : KT - 1;
-            ld.begin(p, ksn, KS);
-            ld.template pieces<LD::P_DMA>(std::make_integer_sequence<int, LD::P_DIGIT - LD::P_DMA>{}, p, kc, xs1, wsm);
-            ld.template pieces<LD::P_MOVE>(std::make_integer_sequence<int, LD::P_END - LD::P_MOVE>{}, p, kc, xs1, wsm);
+            ld.prime(p, ks0, KS, kc);
+            ld.begin(p, ks0, KS, kc, ks_last);
+            ld.template pieces<LD::P_DMA, false>(std::make_integer_sequence<int, LD::P_TRANS - LD::P_DMA>{}, p, kc, xs0, wsm);
+            ld.begin(p, ks0 + 1 < ks_last ? ks0 + 1 : ks_last, KS, kc, ks_last);
+            ld.template pieces<LD::P_DMA, true>(std::make_integer_sequence<int, LD::P_END - LD::P_DMA>{}, p, kc, xs1, wsm);
         }
         wait_and_barrier<0>();
 
-        const int ks_last = ks0 + L - 1;
         for (int i = 0; i < L; i += 3) {
             const int k2 = ks0 + i + 2;
             gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs0, wsm + (i & 1) * T::WBYTES,
-                                       wsm + ((i + 1) & 1) * T::WBYTES, xs2, a_off, b_off,
-                                       k2 < ks_last ? k2 : ks_last, KS, kc);
+                                              wsm + ((i + 1) & 1) * T::WBYTES, xs2, a_off, b_off,
+                                              k2 < ks_last ? k2 : ks_last, ks_last, KS, kc);
             if (i + 1 < L)
                 gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs1, wsm + ((i + 1) & 1) * T::WBYTES,
-                                           wsm + (i & 1) * T::WBYTES, xs0, a_off, b_off,
-                                           k2 + 1 < ks_last ? k2 + 1 : ks_last, KS, kc);
+                                                  wsm + (i & 1) * T::WBYTES, xs0, a_off, b_off,
+                                                  k2 + 1 < ks_last ? k2 + 1 : ks_last, ks_last, KS, kc);
             if (i + 2 < L)
                 gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs2, wsm + (i & 1) * T::WBYTES,
-                                           wsm + ((i + 1) & 1) * T::WBYTES, xs1, a_off, b_off,
-                                           k2 + 2 < ks_last ? k2 + 2 : ks_last, KS, kc);
+                                                  wsm + ((i + 1) & 1) * T::WBYTES, xs1, a_off, b_off,
+                                                  k2 + 2 < ks_last ? k2 + 2 : ks_last, ks_last, KS, kc);
         }
         // the look-ahead transfers of the last steps are redundant; let them land before the
         // stages are reused
@@ -618,7 +634,7 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
-int launch_gemm(comet_ctx* ctx, const char* what, const GemmParams& p, long units_cap) {
+int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     void (*kern)(GemmParams) = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, GATHER_NONE>;
     if (p.kind == KIND_SIMM) {
@@ -629,12 +645,27 @@ int launch_gemm(comet_ctx* ctx, const char* what, const GemmParams& p, long unit
         else
             kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_ANY>;
     }
+    const long tiles = (long)((p.m + T::BM - 1) / T::BM) * ((p.n_cap + T::BN - 1) / T::BN);
+    const long kt = 2l * p.ks_cap;
+    const long units_cap = tiles * kt;
     // a chip-sized grid, shrunk when there is too little work to share out
     long grid = (ctx->num_cu / 8) * 8 * (WM * WN == 1 ? 2 : 1);
     if (grid < 8) grid = 8;
     const long want = (units_cap + 3) / 4;
     if (want < grid) grid = want < 8 ? (want < 1 ? 1 : want) : (want / 8) * 8;
     if (ctx->gemm_grid > 0) grid = ctx->gemm_grid;
+    // Slice length: as many slices as there are workgroups per tile, so that a workgroup's
+    // share of the units is one slice of one tile and all workgroups sweep their slice in
+    // lockstep (the activation planes of a slice are then shared through L2).
+    if (ctx->gemm_chunk > 0) {
+        p.chunk = ctx->gemm_chunk;
+    } else {
+        long slices = (grid + tiles / 2) / tiles;
+        if (slices < 1) slices = 1;
+        p.chunk = (int)((kt + slices - 1) / slices);
+    }
+    if (p.chunk > MAX_SEG) p.chunk = MAX_SEG;
+    if (p.chunk < 1) p.chunk = 1;
     const bool timed = ctx->ev && ctx->ev_used + 2 <= ctx->ev_cap;
     if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], ctx->stream);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), 0, ctx->stream, p);
@@ -671,7 +702,6 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     p.bs_shift = -1;
     for (int sh = 0; sh < 30; ++sh)
         if (p.bs == (1 << sh)) p.bs_shift = sh;
-    p.chunk = ctx->gemm_chunk > 0 ? (ctx->gemm_chunk < MAX_SEG ? ctx->gemm_chunk : MAX_SEG) : 128;
 
     if (p.n_cap == 0) return COMET_OK;
     // Z := C on the kept region
@@ -692,21 +722,10 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
                        dim3(128), 0, ctx->stream, p);
     COMET_LAUNCH_CHECK(ctx, what);
 
-    const long kt = 2l * p.ks_cap;
-    if (ctx->gemm_tile == 2) {
-        const long units = (long)((p.m + 63) / 64) * ((p.n_cap + 63) / 64) * kt;
-        return launch_gemm<2, 2, 1, 1>(ctx, what, p, units);
-    }
-    if (p.m <= 32) {
-        const long units = (long)((p.m + 31) / 32) * ((p.n_cap + 255) / 256) * kt;
-        return launch_gemm<1, 4, 1, 2>(ctx, what, p, units);
-    }
-    if (p.m <= 64) {
-        const long units = (long)((p.m + 63) / 64) * ((p.n_cap + 63) / 64) * kt;
-        return launch_gemm<2, 2, 1, 1>(ctx, what, p, units);
-    }
-    const long units = (long)((p.m + 127) / 128) * ((p.n_cap + 63) / 64) * kt;
-    return launch_gemm<2, 2, 2, 1>(ctx, what, p, units);
+    if (ctx->gemm_tile == 2) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+    if (p.m <= 32) return launch_gemm<1, 4, 1, 2>(ctx, what, p);
+    if (p.m <= 64) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+    return launch_gemm<2, 2, 2, 1>(ctx, what, p);
 }
 
 int check_common(comet_ctx* ctx, const char* what, int party, int64_t m, int bs, int n_blk_cap,
