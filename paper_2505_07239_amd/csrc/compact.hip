@@ -9,9 +9,11 @@
 //   small (nb <= 4096): one 256-thread workgroup does everything in one launch;
 //     this is every real FFN mask (a few hundred blocks) and is latency-bound.
 //   large: three wait-free launches.  (1) each lane ORs 16 adjacent flags over
-//     all tokens into a 16-bit word and each workgroup stores its popcount;
+//     the tokens into a 16-bit word and each workgroup stores its popcount
+//     (with many tokens and few columns the tokens are split over workgroups,
+//     which meet through atomic ORs, and a small extra pass counts);
 //     (2) one workgroup scans the workgroup counts; (3) each workgroup scans its
-//     own 16-bit words with wavefront prefix sums and writes the indices.
+//     own words with wavefront prefix sums and writes the indices through LDS.
 //     The mask bytes are read exactly once; passes 2 and 3 touch only the
 //     bit-packed words (1/8 of a byte per flag) and the outputs.
 #include "common.h"
@@ -107,60 +109,146 @@ __global__ __launch_bounds__(CT) void compact_small_kernel(const uint8_t* __rest
     if (threadIdx.x == 0) *n_blk_dev = total;
 }
 
-// pass 1: bit-pack and count
+// pass 1: bit-pack and count.  gridDim.y > 1 splits the tokens over several
+// workgroups per column chunk; their partial ORs meet in the (pre-cleared)
+// words through 32-bit atomic ORs and the counting is left to pass 1b.
 __global__ __launch_bounds__(CT) void compact_pack_kernel(const uint8_t* __restrict__ mask,
                                                           long n_tok, long nb, bool rows_aligned,
                                                           unsigned short* __restrict__ words,
                                                           int* __restrict__ counts) {
     __shared__ int sm[CT / 64 + 1];
     const long base = (long)blockIdx.x * CHUNK;
+    const bool split = gridDim.y > 1;
+    const long tok_per = (n_tok + gridDim.y - 1) / gridDim.y;
+    const long t0 = (long)blockIdx.y * tok_per;
+    const long t1 = t0 + tok_per < n_tok ? t0 + tok_per : n_tok;
+    if (t0 >= t1) return;
     u32 bits[ITEMS];
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j)
-        bits[j] = or_flags16(mask, n_tok, nb, base + ((long)j * CT + threadIdx.x) * FL, rows_aligned);
+        bits[j] = or_flags16(mask + t0 * nb, t1 - t0, nb, base + ((long)j * CT + threadIdx.x) * FL,
+                             rows_aligned);
     int cnt = 0;
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
         cnt += __builtin_popcount(bits[j]);
         const long w = (base / FL) + (long)j * CT + threadIdx.x;
-        if (w * FL < nb) words[w] = (unsigned short)bits[j];
+        if (w * FL < nb) {
+            if (split) {
+                if (bits[j]) atomicOr(reinterpret_cast<u32*>(words) + (w >> 1), bits[j] << (16 * (int)(w & 1)));
+            } else {
+                words[w] = (unsigned short)bits[j];
+            }
+        }
     }
+    if (split) return;
     int total;
     (void)block_excl_scan(cnt, sm, &total);
     if (threadIdx.x == 0) counts[blockIdx.x] = total;
 }
 
-// pass 2: exclusive scan of the workgroup counts, in place; writes the grand total
-__global__ __launch_bounds__(CT) void compact_scan_kernel(int* __restrict__ counts, int n,
-                                                          int* __restrict__ n_blk_dev) {
+// clears the words before a token-split pass 1 (a fill kernel rather than a memset
+// so that the whole call can be captured in a HIP graph)
+__global__ __launch_bounds__(CT) void compact_clear_kernel(u32* __restrict__ words32, long n) {
+    for (long i = (long)blockIdx.x * CT + threadIdx.x; i < n; i += (long)gridDim.x * CT) words32[i] = 0u;
+}
+
+// pass 1b (token-split only): population count of each workgroup-sized chunk of words
+__global__ __launch_bounds__(CT) void compact_count_kernel(const unsigned short* __restrict__ words,
+                                                           long nb, int* __restrict__ counts) {
     __shared__ int sm[CT / 64 + 1];
+    const long w0 = (long)blockIdx.x * (CHUNK / FL) + (long)threadIdx.x * ITEMS;
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j)
+        if ((w0 + j) * FL < nb) cnt += __builtin_popcount((u32)words[w0 + j]);
+    int total;
+    (void)block_excl_scan(cnt, sm, &total);
+    if (threadIdx.x == 0) counts[blockIdx.x] = total;
+}
+
+// pass 2: exclusive scan of the workgroup counts, in place; writes the grand total.
+// One workgroup; the counts pass through LDS in tiles so that global accesses are
+// coalesced and each thread scans a contiguous run out of LDS.
+constexpr int ST = 1024;
+constexpr int SCAN_PER = 8;                       // counts per thread per tile
+__global__ __launch_bounds__(ST) void compact_scan_kernel(int* __restrict__ counts, int n,
+                                                          int* __restrict__ n_blk_dev) {
+    __shared__ int tile[ST * SCAN_PER];
+    __shared__ int sm[ST / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int carry = 0;
-    for (int base = 0; base < n; base += CT) {
-        const int i = base + threadIdx.x;
-        const int v = i < n ? counts[i] : 0;
-        int total;
-        const int ex = block_excl_scan(v, sm, &total);
-        if (i < n) counts[i] = carry + ex;
-        carry += total;
+    for (int base = 0; base < n; base += ST * SCAN_PER) {
+#pragma unroll
+        for (int j = 0; j < SCAN_PER; ++j) {
+            const int i = base + j * ST + threadIdx.x;
+            tile[j * ST + threadIdx.x] = i < n ? counts[i] : 0;
+        }
+        __syncthreads();
+        int v[SCAN_PER], sum = 0;
+#pragma unroll
+        for (int j = 0; j < SCAN_PER; ++j) { v[j] = tile[threadIdx.x * SCAN_PER + j]; sum += v[j]; }
+        int wtot;
+        const int ex = wave_excl_scan(sum, lane, &wtot);
+        if (lane == 0) sm[wave] = wtot;
+        __syncthreads();
+        int wbase = 0, tot = 0;
+#pragma unroll
+        for (int w = 0; w < ST / 64; ++w) {
+            const int x = sm[w];
+            if (w < wave) wbase += x;
+            tot += x;
+        }
+        int run = carry + wbase + ex;
+#pragma unroll
+        for (int j = 0; j < SCAN_PER; ++j) { tile[threadIdx.x * SCAN_PER + j] = run; run += v[j]; }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < SCAN_PER; ++j) {
+            const int i = base + j * ST + threadIdx.x;
+            if (i < n) counts[i] = tile[j * ST + threadIdx.x];
+        }
+        carry += tot;
+        __syncthreads();
     }
     if (threadIdx.x == 0) *n_blk_dev = carry;
 }
 
-// pass 3: positions inside the workgroup, then write the indices
+// pass 3: each lane owns 64 consecutive flags (four 16-bit words), one workgroup scan gives
+// the positions.  When the workgroup's indices fit the LDS stage they are scattered there
+// and copied out as one contiguous run (full-width global stores); a denser chunk writes its
+// indices directly.
+constexpr int STAGE_CAP = 6144;
 __global__ __launch_bounds__(CT) void compact_emit_kernel(const unsigned short* __restrict__ words,
                                                           const int* __restrict__ offsets, long nb,
                                                           int* __restrict__ blk_idx) {
     __shared__ int sm[CT / 64 + 1];
-    const long base = (long)blockIdx.x * CHUNK;
-    int carry = offsets[blockIdx.x];
+    __shared__ int stage[STAGE_CAP];
+    const long w0 = (long)blockIdx.x * (CHUNK / FL) + (long)threadIdx.x * ITEMS;
+    u32 bits[ITEMS];
+    int cnt = 0;
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
-        const long w = (base / FL) + (long)j * CT + threadIdx.x;
-        const u32 bits = (w * FL < nb) ? words[w] : 0u;
-        int total;
-        const int ex = block_excl_scan(__builtin_popcount(bits), sm, &total);
-        emit_bits(bits, (int)(w * FL), blk_idx + carry + ex);
-        carry += total;
+        bits[j] = ((w0 + j) * FL < nb) ? (u32)words[w0 + j] : 0u;
+        cnt += __builtin_popcount(bits[j]);
+    }
+    int total;
+    int pos = block_excl_scan(cnt, sm, &total);
+    int* out = blk_idx + offsets[blockIdx.x];
+    if (total <= STAGE_CAP) {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            emit_bits(bits[j], (int)((w0 + j) * FL), stage + pos);
+            pos += __builtin_popcount(bits[j]);
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < total; i += CT) out[i] = stage[i];
+    } else {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            emit_bits(bits[j], (int)((w0 + j) * FL), out + pos);
+            pos += __builtin_popcount(bits[j]);
+        }
     }
 }
 
@@ -208,10 +296,28 @@ extern "C" int comet_compact_mask(comet_ctx* ctx, const uint8_t* mask, int64_t n
     unsigned short* words = static_cast<unsigned short*>(ws);
     const size_t words_bytes = ((size_t)groups * CT * ITEMS * sizeof(unsigned short) + 255) & ~(size_t)255;
     int* counts = reinterpret_cast<int*>(static_cast<char*>(ws) + words_bytes);
-    hipLaunchKernelGGL(compact_pack_kernel, dim3(groups), dim3(CT), 0, ctx->stream, mask, (long)n_tok,
-                       (long)nb, rows_aligned, words, counts);
+    // enough workgroups to fill the chip: split the tokens when the column chunks alone are too few
+    long gy = 1;
+    if (n_tok > 1 && groups < 8 * ctx->num_cu) {
+        gy = (8l * ctx->num_cu + groups - 1) / groups;
+        if (gy > n_tok) gy = n_tok;
+        if (gy > 65535) gy = 65535;
+    }
+    if (gy > 1) {
+        const long n32 = (long)(words_bytes / 4);
+        hipLaunchKernelGGL(compact_clear_kernel, dim3((unsigned)((n32 + CT - 1) / CT)), dim3(CT), 0,
+                           ctx->stream, reinterpret_cast<u32*>(words), n32);
+        COMET_LAUNCH_CHECK(ctx, what);
+    }
+    hipLaunchKernelGGL(compact_pack_kernel, dim3(groups, (unsigned)gy), dim3(CT), 0, ctx->stream, mask,
+                       (long)n_tok, (long)nb, rows_aligned, words, counts);
     COMET_LAUNCH_CHECK(ctx, what);
-    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(CT), 0, ctx->stream, counts, groups,
+    if (gy > 1) {
+        hipLaunchKernelGGL(compact_count_kernel, dim3(groups), dim3(CT), 0, ctx->stream, words, (long)nb,
+                           counts);
+        COMET_LAUNCH_CHECK(ctx, what);
+    }
+    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(ST), 0, ctx->stream, counts, groups,
                        n_blk_dev);
     COMET_LAUNCH_CHECK(ctx, what);
     hipLaunchKernelGGL(compact_emit_kernel, dim3(groups), dim3(CT), 0, ctx->stream, words, counts,

@@ -146,61 +146,95 @@ __device__ __host__ __forceinline__ size_t xp_group(int h, int s, int t, int g, 
 // ---------------------------------------------------------------------------
 // xpack: digit planes of the stacked activation-side operand, and Z := C
 // ---------------------------------------------------------------------------
+// grid: x = chunks of four 16-word groups, y = chunks of 64 rows, z = 0 (E), 1 (A'), 2 (Z := C).
+// A workgroup packs a 64-row x 64-word tile: four adjacent lanes read 512 contiguous bytes of
+// one row, and the sixteen lanes that share a group write sixteen adjacent 16-byte units.
 __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
     const int nblk = n_blocks(p);
+    if (blockIdx.z == 2) {
+        // Z := C on the kept region (the GEMM adds its partial sums onto it)
+        const int n_eff = p.kind == KIND_SOMM ? nblk * p.bs : p.n_cap;
+        const long total = (long)p.m * n_eff;
+        const long stride = (long)gridDim.x * gridDim.y * GT;
+        for (long i = ((long)blockIdx.y * gridDim.x + blockIdx.x) * GT + threadIdx.x; i < total; i += stride) {
+            const long r = i / n_eff, c = i - r * n_eff;
+            p.Z[r * p.ldz + c] = p.C[r * p.ldz + c];
+        }
+        return;
+    }
     const int kc = p.kind == KIND_SOMM ? p.kc_cap : nblk * p.bs;
-    const int row = blockIdx.y * 128 + threadIdx.x;    // < mpad by construction (128 threads)
-    const int half16 = blockIdx.x;                     // 16-word group over the half: 0 .. ks_cap*2
-    const int h = blockIdx.z;                          // 0: E, 1: A'
+    const int row = blockIdx.y * 64 + (threadIdx.x >> 2);      // < mpad by construction
+    const int half16 = blockIdx.x * 4 + (threadIdx.x & 3);     // 16-word group over the half
+    if (half16 >= p.ks_cap * 2) return;
+    const int h = blockIdx.z;                                  // 0: E, 1: A'
     const int k0 = half16 * 16;
+    typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+    u64 w[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) w[j] = 0;
+    // fast path: the sixteen words are inside the contraction, 16-byte aligned, and (when A_i is
+    // indexed) inside one block -- eight 16-byte loads per operand
+    const bool wide = row < p.m && k0 + 16 <= kc && (p.lde & 1) == 0 && (p.lda & 1) == 0 &&
+                      (!p.a_full || (p.bs & 15) == 0);
+    if (wide) {
+        const u64* e = p.E + (size_t)row * p.lde + k0;
+        u64x2 ev[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ev[j] = *reinterpret_cast<const u64x2*>(e + 2 * j);
+        if (h == 0) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { w[2 * j] = ev[j].x; w[2 * j + 1] = ev[j].y; }
+        } else {
+            long col = k0;
+            if (p.a_full) {
+                const int blk = k0 / p.bs;
+                const long st = block_start(p, blk);
+                col = (st < 0 ? 0 : st) + (k0 - blk * p.bs);
+            }
+            const u64* a = p.A + (size_t)row * p.lda + col;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const u64x2 av = *reinterpret_cast<const u64x2*>(a + 2 * j);
+                w[2 * j] = av.x + (p.party ? ev[j].x : 0ull);
+                w[2 * j + 1] = av.y + (p.party ? ev[j].y : 0ull);
+            }
+        }
+    } else if (row < p.m && k0 < kc) {
+        int blk = 0, off = 0;
+        if (h == 1 && p.a_full) { blk = k0 / p.bs; off = k0 - blk * p.bs; }
+        for (int j = 0; j < 16; ++j) {
+            const int k = k0 + j;
+            if (k < kc) {
+                const u64 e = p.E[(size_t)row * p.lde + k];
+                u64 x = e;
+                if (h == 1) {
+                    long col = k;
+                    if (p.a_full) {
+                        while (off >= p.bs) { off -= p.bs; ++blk; }
+                        const long st = block_start(p, blk);
+                        col = (st < 0 ? 0 : st) + off;
+                        ++off;
+                    }
+                    x = p.A[(size_t)row * p.lda + col] + (p.party ? e : 0ull);
+                }
+                w[j] = x;
+            }
+        }
+    }
     u64 plane[2][8];
 #pragma unroll
     for (int o = 0; o < 2; ++o) {
         u64 v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = 0;
-        const int kb = k0 + 8 * o;
-        if (row < p.m && kb < kc) {
-            int blk = 0, off = 0;
-            if (h == 1 && p.a_full) { blk = kb / p.bs; off = kb - blk * p.bs; }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int k = kb + j;
-                if (k < kc) {
-                    const u64 e = p.E[(size_t)row * p.lde + k];
-                    u64 x = e;
-                    if (h == 1) {
-                        long col = k;
-                        if (p.a_full) {
-                            while (off >= p.bs) { off -= p.bs; ++blk; }
-                            const long st = block_start(p, blk);
-                            col = st < 0 ? -1 : st + off;
-                            ++off;
-                        }
-                        const u64 a = col < 0 ? 0ull : p.A[(size_t)row * p.lda + col];
-                        x = a + (p.party ? e : 0ull);
-                    }
-                    v[j] = to_digits(x);
-                }
-            }
-        }
+        for (int j = 0; j < 8; ++j) v[j] = (row < p.m && k0 + 8 * o + j < kc) ? to_digits(w[8 * o + j]) : 0ull;
         digits_to_planes(v, plane[o]);
     }
     const int s = half16 >> 1, g = half16 & 1;
-    typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         u64x2* dst = reinterpret_cast<u64x2*>(p.xp) + xp_group(h, s, t, g, p.ks_cap) * p.mpad + row;
         *dst = u64x2{plane[0][t], plane[1][t]};
     }
-}
-
-__global__ __launch_bounds__(GT) void init_z_kernel(GemmParams p) {
-    const int nblk = n_blocks(p);
-    const int n_eff = p.kind == KIND_SOMM ? nblk * p.bs : p.n_cap;
-    const int r = blockIdx.y;
-    for (int c = blockIdx.x * GT + threadIdx.x; c < n_eff; c += gridDim.x * GT)
-        p.Z[(size_t)r * p.ldz + c] = p.C[(size_t)r * p.ldz + c];
 }
 
 // ---------------------------------------------------------------------------
@@ -704,24 +738,14 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         if (p.bs == (1 << sh)) p.bs_shift = sh;
 
     if (p.n_cap == 0) return COMET_OK;
-    // Z := C on the kept region
+    // digit planes of [E | A'] and Z := C, one launch
     {
-        unsigned gx = (unsigned)((p.n_cap + GT - 1) / GT);
-        if (gx > 64) gx = 64;
-        for (int r0 = 0; r0 < p.m; r0 += 65535) {
-            GemmParams q = p;
-            q.Z = p.Z + (size_t)r0 * p.ldz;
-            q.C = p.C + (size_t)r0 * p.ldz;
-            const unsigned gy = (unsigned)((p.m - r0) < 65535 ? (p.m - r0) : 65535);
-            hipLaunchKernelGGL(init_z_kernel, dim3(gx, gy), dim3(GT), 0, ctx->stream, q);
-            COMET_LAUNCH_CHECK(ctx, what);
-        }
+        unsigned gx = (unsigned)((p.ks_cap * 2 + 3) / 4);
+        if (gx < 1) gx = 1;
+        hipLaunchKernelGGL(xpack_kernel, dim3(gx, (unsigned)(p.mpad / 64), 3), dim3(GT), 0, ctx->stream, p);
+        COMET_LAUNCH_CHECK(ctx, what);
     }
     if (p.ks_cap == 0) return COMET_OK;
-    hipLaunchKernelGGL(xpack_kernel, dim3((unsigned)(p.ks_cap * 2), (unsigned)(p.mpad / 128), 2),
-                       dim3(128), 0, ctx->stream, p);
-    COMET_LAUNCH_CHECK(ctx, what);
-
     if (ctx->gemm_tile == 2) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
     if (p.m <= 32) return launch_gemm<1, 4, 1, 2>(ctx, what, p);
     if (p.m <= 64) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
