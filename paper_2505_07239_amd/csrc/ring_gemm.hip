@@ -311,12 +311,13 @@ struct Loader {
     static constexpr int XGRP_PER_PASS = GT / T::BM;         // groups covered by one pass of the block
     static_assert(GT % T::BM == 0, "tile rows must divide the block");
 
-    // piece list of one step, in execution order
+    // Piece list of one step, in execution order: the DMA issues, then task by task the eight
+    // split-and-reload pieces, the four transposes and the eight LDS stores (task-major, so the
+    // digits and transposed planes of a task are dead before the next task starts).
     static constexpr int P_DMA = 0;
-    static constexpr int P_LOAD = P_DMA + T::XVEC;     // split word e into digits, then reload it
-    static constexpr int P_TRANS = P_LOAD + 8 * W;
-    static constexpr int P_WRITE = P_TRANS + 4 * W;
-    static constexpr int P_END = P_WRITE + 8 * W;
+    static constexpr int P_TASK = P_DMA + T::XVEC;
+    static constexpr int PER_TASK = 8 + 4 + 8;
+    static constexpr int P_END = P_TASK + PER_TASK * W;
 
     __device__ __forceinline__ void setup(const GemmParams& p, int tm, int tn, int n_eff) {
 #pragma unroll
@@ -435,24 +436,29 @@ struct Loader {
         transpose4(x[0], x[1], x[2], x[3], pl[J][o], pl[J][o + 1], pl[J][o + 2], pl[J][o + 3]);
     }
 
-    // digit plane Tt of task J -> LDS
+    // digit plane Tt of task J -> LDS.  Weight stage layout: 16-byte fragments ordered
+    // (digit, k-half, column); an octet is one 8-byte half of a fragment, so a matrix-instruction
+    // operand is a single 16-byte LDS read.
     template <int J, int Tt>
     __device__ __forceinline__ void write_piece(unsigned char* wstage) {
         const int id = threadIdx.x + GT * J;
         const int c = id % T::BN, oct = id / T::BN;
         const u64 v = (u64)pl[J][Tt] | ((u64)pl[J][8 + Tt] << 32);
-        // weight stage layout: 8-byte units ordered (digit, k-half, octet-in-half, column), so
-        // that the 64 lanes of a store hit 64 consecutive units
-        *reinterpret_cast<u64*>(wstage + ((size_t)(Tt * 4 + oct) * T::BN + c) * 8) = v;
+        *reinterpret_cast<u64*>(wstage + ((size_t)(Tt * 2 + (oct >> 1)) * T::BN + c) * 16 + (oct & 1) * 8) = v;
     }
 
+    // SPLIT = false: first visit of a segment, nothing to split or store yet, loads only
     template <int P, bool SPLIT>
     __device__ __forceinline__ void piece(const GemmParams& p, int kc, unsigned char* xstage,
                                           unsigned char* wstage) {
-        if constexpr (P < P_LOAD) dma_piece<P - P_DMA>(p, xstage);
-        else if constexpr (P < P_TRANS) load_piece<(P - P_LOAD) / 8, (P - P_LOAD) % 8, SPLIT>(p, kc);
-        else if constexpr (P < P_WRITE) transpose_piece<(P - P_TRANS) / 4, (P - P_TRANS) % 4>();
-        else if constexpr (P < P_END) write_piece<(P - P_WRITE) / 8, (P - P_WRITE) % 8>(wstage);
+        if constexpr (P < P_TASK) {
+            dma_piece<P - P_DMA>(p, xstage);
+        } else if constexpr (P < P_END) {
+            constexpr int J = (P - P_TASK) / PER_TASK, R = (P - P_TASK) % PER_TASK;
+            if constexpr (R < 8) load_piece<J, R, SPLIT>(p, kc);
+            else if constexpr (R < 12) { if (SPLIT) transpose_piece<J, R - 8>(); }
+            else { if (SPLIT) write_piece<J, R - 12>(wstage); }
+        }
     }
 
     template <int P0, bool SPLIT, int... Ps>
@@ -465,13 +471,6 @@ struct Loader {
 
 __device__ __forceinline__ v4i lds_frag(const unsigned char* p) {
     return *reinterpret_cast<const v4i*>(p);
-}
-
-// weight-side fragment: the two octets of a k-half sit stride_bytes apart
-__device__ __forceinline__ v4i lds_frag2(const unsigned char* p, int stride_bytes) {
-    const u64 x0 = *reinterpret_cast<const u64*>(p);
-    const u64 x1 = *reinterpret_cast<const u64*>(p + stride_bytes);
-    return v4i{(int)(u32)x0, (int)(u32)(x0 >> 32), (int)(u32)x1, (int)(u32)(x1 >> 32)};
 }
 
 // position of matrix instruction M inside a step: digit plane t of the activation side,
@@ -514,7 +513,7 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
 #pragma unroll
     for (int t = 0; t < 8; ++t)
 #pragma unroll
-        for (int j = 0; j < WN; ++j) bf[j][t] = lds_frag2(ws + b_off + (t * 4 * T::BN + j * 32) * 8, T::BN * 8);
+        for (int j = 0; j < WN; ++j) bf[j][t] = lds_frag(ws + b_off + (t * 2 * T::BN + j * 32) * 16);
 #pragma unroll
     for (int t = 1; t < 8; ++t)
 #pragma unroll
@@ -582,7 +581,7 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
     const int g = lane >> 5, r = lane & 31;
     // this lane's fragment offsets inside a stage (digit 0)
     const int a_off = (g * T::BM + wm * WM * 32 + r) * 16;
-    const int b_off = (2 * g * T::BN + wn * WN * 32 + r) * 8;
+    const int b_off = (g * T::BN + wn * WN * 32 + r) * 16;
 
     Loader<T, KIND, GMODE> ld;
 
@@ -624,7 +623,7 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
             using LD = Loader<T, KIND, GMODE>;
             ld.prime(p, ks0, KS, kc);
             ld.begin(p, ks0, KS, kc, ks_last);
-            ld.template pieces<LD::P_DMA, false>(std::make_integer_sequence<int, LD::P_TRANS - LD::P_DMA>{}, p, kc, xs0, wsm);
+            ld.template pieces<LD::P_DMA, false>(std::make_integer_sequence<int, LD::P_END - LD::P_DMA>{}, p, kc, xs0, wsm);
             ld.begin(p, ks0 + 1 < ks_last ? ks0 + 1 : ks_last, KS, kc, ks_last);
             ld.template pieces<LD::P_DMA, true>(std::make_integer_sequence<int, LD::P_END - LD::P_DMA>{}, p, kc, xs1, wsm);
         }
