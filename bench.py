@@ -32,9 +32,11 @@ PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 INT8_OPS_PER_RING_MAC = 72   # 36 digit products, 2 ops each
 
-# HBM bytes per ring-GEMM launch from rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled by
-# the same counters on a plain copy); see profiles/.  None until measured for that workload.
-GEMM_TRAFFIC_BYTES = {}
+# HBM bytes per ring-GEMM launch (average over the launches of one step) from rocprofv3 --pmc
+# runs of this file: FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for
+# the copy probe of known size in the same run; the summaries are under profiles/.  None until
+# measured for that workload.
+GEMM_TRAFFIC_BYTES = {"c3": 203003583}
 
 
 def log(msg):
