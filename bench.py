@@ -236,6 +236,8 @@ def main():
     ap.add_argument("--gemm-chunk", type=int, default=0, help="tuning sweep: scheduling slice length")
     ap.add_argument("--gemm-grid", type=int, default=0, help="tuning sweep: workgroups per launch")
     ap.add_argument("--gemm-tile", type=int, default=0, help="tuning sweep: 2 = 64x64 tile")
+    ap.add_argument("--skinny", type=int, default=0, help="tuning sweep: 1 = matrix cores even for m <= 16")
+    ap.add_argument("--skinny-slices", type=int, default=0, help="tuning sweep: contraction slices of the m <= 16 kernel")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (both parties are simulated on it); "
@@ -257,6 +259,8 @@ def main():
     ctx.set_tuning(comet.TUNE_GEMM_CHUNK, args.gemm_chunk)
     ctx.set_tuning(comet.TUNE_GEMM_GRID, args.gemm_grid)
     ctx.set_tuning(comet.TUNE_GEMM_TILE, args.gemm_tile)
+    ctx.set_tuning(comet.TUNE_SKINNY, args.skinny)
+    ctx.set_tuning(comet.TUNE_SKINNY_SLICES, args.skinny_slices)
     layer = Layer(ctx, cfg, rng.BASE_SEED)
     log("workload %s: %s, m=%d d=%d f=%d bs=%d kept blocks %d/%d (n_act=%d), %.2f G ring ops/step" %
         (wname, cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs, layer.n_blk, cfg.nb,
@@ -300,11 +304,27 @@ def main():
                      "note": "algorithmic int8 ops: 36 digit products x 2 ops per ring MAC, two "
                              "products per party (2*m*k*n_act ring MACs per launch)"},
     }
+    if cfg.tokens <= 16 and not args.skinny:
+        # a few activation rows: the share calls take the vector-ALU kernel, bound by reading the
+        # two weight-side operands (B_i and F, kc x n words each) once per launch
+        wbytes = sum(b["macs_per_launch"] for b in layer.mm) / len(layer.mm) / cfg.tokens * 8.0
+        ach = wbytes / (gemm_ms_avg * 1e-3) / 1e9
+        result["roofline"] = {"bound": "hbm", "kernel": "ring_skinny_kernel", "achieved": ach,
+                              "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                              "traffic": GEMM_TRAFFIC_BYTES.get(wname),
+                              "avg_launch_ms": gemm_ms_avg, "launches_timed": n_timed,
+                              "ring_macs_per_launch": macs_per_launch,
+                              "gemm_share_of_step": gemm_ms / ((t1 - t0) * 1e3),
+                              "note": "algorithmic bytes: the weight-side operands B_i and F of "
+                                      "one launch, 8 bytes per word, read once"}
     if not args.no_micro:
         result["kernels"] = micro(ctx, layer)
         for k, v in result["kernels"].items():
             log("%s = %.4g" % (k, v))
-        result["roofline"]["frac_of_measured_mfma_issue"] = achieved / result["kernels"]["mfma_i8_issue_TOPs"]
+        if result["roofline"]["bound"] == "mfma":
+            result["roofline"]["frac_of_measured_mfma_issue"] = achieved / result["kernels"]["mfma_i8_issue_TOPs"]
+        else:
+            result["roofline"]["frac_of_measured_copy"] = result["roofline"]["achieved"] / result["kernels"]["copy_GBs"]
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(layer)
         log("cpu oracle: %.2f Gop/s on %d threads; rows match GPU: %s" %

@@ -170,8 +170,15 @@ int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64
  *   COMET_TUNE_GEMM_CHUNK: contraction steps (of 32 words) per scheduling slice,
  *                         clamped to 256
  *   COMET_TUNE_GEMM_TILE: 2 forces the 64 x 64 output tile (two workgroups per
- *                         compute unit) whatever m is */
-enum { COMET_TUNE_GEMM_GRID = 0, COMET_TUNE_GEMM_CHUNK = 1, COMET_TUNE_GEMM_TILE = 2 };
+ *                         compute unit) whatever m is
+ *   COMET_TUNE_SKINNY:    calls with m <= 16 normally take a vector-ALU kernel
+ *                         bound by reading the weights once; 1 sends them to the
+ *                         matrix-core kernel like any other call
+ *   COMET_TUNE_SKINNY_SLICES: pieces the stacked contraction is cut into by
+ *                         the vector-ALU kernel (default: about eight
+ *                         workgroups per compute unit) */
+enum { COMET_TUNE_GEMM_GRID = 0, COMET_TUNE_GEMM_CHUNK = 1, COMET_TUNE_GEMM_TILE = 2,
+       COMET_TUNE_SKINNY = 3, COMET_TUNE_SKINNY_SLICES = 4 };
 int comet_set_tuning(comet_ctx* ctx, int key, int value);
 
 /* Device-side timing of the ring-GEMM kernel alone (the share calls also run a

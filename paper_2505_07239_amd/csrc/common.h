@@ -21,6 +21,8 @@ struct comet_ctx {
     int gemm_grid;   // 0 = automatic
     int gemm_chunk;  // 0 = default
     int gemm_tile;   // 0 = automatic
+    int skinny_mode;   // 0 = automatic, 1 = never take the vector-ALU path
+    int skinny_slices; // 0 = automatic
     hipEvent_t* ev;  // timing event pairs, or null
     int ev_cap, ev_used;
     char err[512];

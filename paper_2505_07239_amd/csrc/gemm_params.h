@@ -1,0 +1,56 @@
+// Operand description shared by the two implementations of a party's output share
+// (the matrix-core kernel for tall activations and the vector-ALU kernel for a few rows).
+#pragma once
+
+#include "common.h"
+
+constexpr int KIND_SOMM = 0;
+constexpr int KIND_SIMM = 1;
+
+struct GemmParams {
+    int kind, party;
+    int m;          // rows of X / Z
+    int kc_cap;     // contraction length bound: SOMM k, SIMM n_blk_cap * bs
+    int n_cap;      // output width bound: SOMM n_blk_cap * bs, SIMM n
+    int bs, n_blk_cap;
+    int bs_shift;   // log2(bs) when bs is a power of two, else -1
+    int full_extent; // length of the axis blk_idx refers to (neurons)
+    const int* blk_idx;
+    const int* n_blk_dev;
+    // X side
+    const u64* E;  long lde;
+    const u64* A;  long lda;  int a_full;
+    // W side
+    const u64* B;  long ldb;  int b_full;
+    const u64* F;  long ldf;
+    const u64* C;
+    u64* Z;        long ldz;
+    // packed digit planes of [E | A']
+    unsigned char* xp;
+    int mpad;       // rows of xp, multiple of 128
+    int chunk;      // contraction steps per scheduling slice, 1 .. MAX_SEG
+    int ks_cap;     // contraction steps per half, ceil(kc_cap / 32)
+};
+
+static __device__ __forceinline__ int n_blocks(const GemmParams& p) {
+    int nb = p.n_blk_cap;
+    if (p.n_blk_dev) {
+        const int d = *p.n_blk_dev;
+        nb = d < 0 ? 0 : (d < nb ? d : nb);
+    }
+    return nb;
+}
+
+// Start of block `blk` on the indexed axis, or -1 when the id does not fit the
+// axis.  Callers clamp such a block to the start of the axis: a bad id can make
+// the outputs it feeds meaningless, but it can never make an access fault.
+static __device__ __forceinline__ long block_start(const GemmParams& p, int blk) {
+    const long s = (long)p.blk_idx[blk] * p.bs;
+    return (s < 0 || s + p.bs > p.full_extent) ? -1 : s;
+}
+
+// Vector-ALU path for at most COMET_SKINNY_MAX_ROWS activation rows (decoding): computes the
+// whole share, Z := C included.  p.xp is the workspace of the matrix-core path, which is
+// always large enough.
+static const int COMET_SKINNY_MAX_ROWS = 16;
+int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p);

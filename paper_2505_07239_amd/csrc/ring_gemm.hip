@@ -39,6 +39,7 @@
 //                  to v_mfma_i32_32x32x32_i8.  The weight matrices are the
 //                  large operands; they are never re-written to memory.
 #include "common.h"
+#include "gemm_params.h"
 
 #include <type_traits>
 #include <utility>
@@ -55,55 +56,10 @@ constexpr int MAX_SEG = 256;    // contraction steps an int32 plane can absorb
 constexpr int GT = 256;         // threads per workgroup (4 wavefronts)
 constexpr u64 DIGIT_BIAS = 0x0080808080808080ull;
 
-constexpr int KIND_SOMM = 0;
-constexpr int KIND_SIMM = 1;
-
 // how the weight-side rows of B_i are addressed (SIMM with a full-size B_i only)
 constexpr int GATHER_NONE = 0;   // rows are the compact contraction index
 constexpr int GATHER_POW2 = 1;   // block gather, bs a power of two >= 8
 constexpr int GATHER_ANY = 2;    // block gather, any bs
-
-struct GemmParams {
-    int kind, party;
-    int m;          // rows of X / Z
-    int kc_cap;     // contraction length bound: SOMM k, SIMM n_blk_cap * bs
-    int n_cap;      // output width bound: SOMM n_blk_cap * bs, SIMM n
-    int bs, n_blk_cap;
-    int bs_shift;   // log2(bs) when bs is a power of two, else -1
-    int full_extent; // length of the axis blk_idx refers to (neurons)
-    const int* blk_idx;
-    const int* n_blk_dev;
-    // X side
-    const u64* E;  long lde;
-    const u64* A;  long lda;  int a_full;
-    // W side
-    const u64* B;  long ldb;  int b_full;
-    const u64* F;  long ldf;
-    const u64* C;
-    u64* Z;        long ldz;
-    // packed digit planes of [E | A']
-    unsigned char* xp;
-    int mpad;       // rows of xp, multiple of 128
-    int chunk;      // contraction steps per scheduling slice, 1 .. MAX_SEG
-    int ks_cap;     // contraction steps per half, ceil(kc_cap / 32)
-};
-
-__device__ __forceinline__ int n_blocks(const GemmParams& p) {
-    int nb = p.n_blk_cap;
-    if (p.n_blk_dev) {
-        const int d = *p.n_blk_dev;
-        nb = d < 0 ? 0 : (d < nb ? d : nb);
-    }
-    return nb;
-}
-
-// Start of block `blk` on the indexed axis, or -1 when the id does not fit the
-// axis.  Callers clamp such a block to the start of the axis: a bad id can make
-// the outputs it feeds meaningless, but it can never make an access fault.
-__device__ __forceinline__ long block_start(const GemmParams& p, int blk) {
-    const long s = (long)p.blk_idx[blk] * p.bs;
-    return (s < 0 || s + p.bs > p.full_extent) ? -1 : s;
-}
 
 __device__ __forceinline__ u64 to_digits(u64 x) { return (x + DIGIT_BIAS) ^ DIGIT_BIAS; }
 
@@ -737,6 +693,7 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         if (p.bs == (1 << sh)) p.bs_shift = sh;
 
     if (p.n_cap == 0) return COMET_OK;
+    if (p.m <= COMET_SKINNY_MAX_ROWS && ctx->skinny_mode != 1) return comet_launch_skinny(ctx, what, p);
     // digit planes of [E | A'] and Z := C, one launch
     {
         unsigned gx = (unsigned)((p.ks_cap * 2 + 3) / 4);

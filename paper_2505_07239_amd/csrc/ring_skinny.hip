@@ -1,0 +1,248 @@
+// One party's output share (paper Eq. 1 on the indexed sub-matrices of Protocols 2 and 3)
+// when the activation side has only a few rows, as in token-by-token decoding:
+//
+//     [Z]_i = [C]_i + [ E | A' ] . [ B_i ; F ],   A' = A_i + party * E      (mod 2^64)
+//
+// With m <= 16 rows every weight word is used m times and the product is bound by reading the
+// two weight operands once from memory, not by arithmetic: the matrix cores would spend most of
+// their 32-row tiles on padding, and the digit split they need costs more vector work per
+// weight word than the m multiply-adds themselves.  So this path multiplies directly in the
+// vector ALU.  A ring multiply-add  z += x w  is three 32 x 32 -> 64 bit multiply-adds
+// (v_mad_u64_u32, full rate on this chip): the low halves go into one 64-bit accumulator with
+// their carry, the two cross products into a second one of which only the low 32 bits matter,
+// and the result is  acc + (cross << 32); the high x high product lies beyond 2^64.
+//   * a wavefront owns 64 * VEC adjacent output columns and a run of the stacked contraction;
+//     per contraction index it issues one coalesced load of the weight row segment and takes
+//     the m activation words from scalar registers (they are the same for every lane);
+//   * the activation words are first rewritten k-major (prep kernel), so that the words of one
+//     contraction index are one aligned scalar load; the same kernel sets Z := C;
+//   * the four wavefronts of a workgroup take consecutive runs, add their partial sums in LDS
+//     and issue one 64-bit atomic add per output element; addition mod 2^64 is associative and
+//     commutative, so the result is bit-exact for any split.
+// The block gather of Protocols 2 and 3 is folded into the addressing: a column offset per lane
+// (SOMM with a full-size B_i) or a row offset per contraction index (SIMM).
+#include "gemm_params.h"
+
+namespace {
+
+constexpr int ST = 256;        // threads per workgroup
+constexpr int SW = ST / 64;    // wavefronts per workgroup
+constexpr int UNROLL = 8;      // weight rows in flight per wavefront
+constexpr int RG = 8;          // rows reduced through LDS at a time
+
+typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+
+// xs[(h * kc_cap + k) * MR + r]: h = 0: E[r][k], h = 1: A'[r][k]; rows r >= m hold zero.
+// blockIdx.y == 1: Z := C on the kept region.
+__global__ __launch_bounds__(ST) void skinny_prep_kernel(GemmParams p, u64* xs, int MR) {
+    const int nblk = n_blocks(p);
+    const long stride = (long)gridDim.x * ST;
+    const long t0 = (long)blockIdx.x * ST + threadIdx.x;
+    if (blockIdx.y == 1) {
+        const int n_eff = p.kind == KIND_SOMM ? nblk * p.bs : p.n_cap;
+        const long total = (long)p.m * n_eff;
+        for (long i = t0; i < total; i += stride) {
+            const long r = i / n_eff, c = i - r * n_eff;
+            p.Z[r * p.ldz + c] = p.C[r * p.ldz + c];
+        }
+        return;
+    }
+    const int kc = p.kind == KIND_SOMM ? p.kc_cap : nblk * p.bs;
+    const long total = 2l * MR * kc;
+    for (long i = t0; i < total; i += stride) {
+        const int k = (int)(i % kc);
+        const int r = (int)((i / kc) % MR);
+        const int h = (int)(i / ((long)kc * MR));
+        u64 x = 0;
+        if (r < p.m) {
+            const u64 e = p.E[(size_t)r * p.lde + k];
+            x = e;
+            if (h == 1) {
+                long col = k;
+                if (p.a_full) {
+                    const int blk = k / p.bs;
+                    const long st = block_start(p, blk);
+                    col = (st < 0 ? 0 : st) + (k - blk * p.bs);
+                }
+                x = p.A[(size_t)r * p.lda + col] + (p.party ? e : 0ull);
+            }
+        }
+        xs[((size_t)h * p.kc_cap + k) * MR + r] = x;
+    }
+}
+
+template <int VEC>
+struct WVec;
+template <>
+struct WVec<1> {
+    u64 v[1];
+    __device__ __forceinline__ void load(const u64* q) { v[0] = *q; }
+};
+template <>
+struct WVec<2> {
+    u64 v[2];
+    __device__ __forceinline__ void load(const u64* q) {
+        const u64x2 t = *reinterpret_cast<const u64x2*>(q);
+        v[0] = t.x; v[1] = t.y;
+    }
+};
+
+__device__ __forceinline__ void mac(u64& acc, u64& cross, u64 x, u64 w) {
+    const u32 xl = (u32)x, xh = (u32)(x >> 32), wl = (u32)w, wh = (u32)(w >> 32);
+    acc += (u64)xl * wl;
+    cross += (u64)xh * wl;
+    cross += (u64)xl * wh;
+}
+
+// Weight row of stacked contraction index kk (wave-uniform): rows [0, kc) are B_i (gathered by
+// block when B_i is the full-size operand of a SIMM call), rows [kc, 2 kc) are F.
+template <int KIND>
+__device__ __forceinline__ const u64* weight_row(const GemmParams& p, int kk, int kc, const u64* wB,
+                                                 const u64* wF) {
+    if (kk >= kc) return wF + (size_t)(kk - kc) * p.ldf;
+    long row = kk;
+    if (KIND == KIND_SIMM && p.b_full) {
+        const int blk = p.bs_shift >= 0 ? (kk >> p.bs_shift) : kk / p.bs;
+        const long st = block_start(p, blk);
+        row = (st < 0 ? 0 : st) + (kk - blk * p.bs);
+    }
+    return wB + (size_t)row * p.ldb;
+}
+
+template <int MR, int VEC, int KIND>
+__global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64* __restrict__ xs,
+                                                         int slices) {
+    __shared__ __align__(16) u64 red[SW][RG][64 * VEC];
+    const int nblk = n_blocks(p);
+    const int n_eff = KIND == KIND_SOMM ? nblk * p.bs : p.n_cap;
+    const int kc = KIND == KIND_SOMM ? p.kc_cap : nblk * p.bs;
+    const int tile0 = blockIdx.x * 64 * VEC;
+    if (tile0 >= n_eff || kc <= 0) return;                    // uniform over the workgroup
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    int col = tile0 + lane * VEC;
+    if (col >= n_eff) col = n_eff - VEC;                      // loads stay in range; never written back
+    long colB = col;
+    if (KIND == KIND_SOMM && p.b_full) {
+        const int blk = col / p.bs;
+        const long st = block_start(p, blk);
+        colB = (st < 0 ? 0 : st) + (col - blk * p.bs);
+    }
+    const u64* wB = p.B + colB;
+    const u64* wF = p.F + col;
+
+    // this wavefront's run [k0, k1) of the stacked contraction [0, 2 kc)
+    const int kt = 2 * kc;
+    const int per_wg = (kt + slices - 1) / slices;
+    const int per_wave = (per_wg + SW - 1) / SW;
+    const int wg0 = blockIdx.y * per_wg;
+    int wg1 = wg0 + per_wg;
+    wg1 = wg1 < kt ? wg1 : kt;
+    int k0 = wg0 + wave * per_wave;
+    int k1 = k0 + per_wave;
+    k1 = k1 < wg1 ? k1 : wg1;
+
+    u64 acc[MR][VEC], cross[MR][VEC];
+#pragma unroll
+    for (int r = 0; r < MR; ++r)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[r][v] = cross[r][v] = 0;
+
+    int kk = k0;
+    for (; kk + UNROLL <= k1; kk += UNROLL) {
+        WVec<VEC> w[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) w[u].load(weight_row<KIND>(p, kk + u, kc, wB, wF));
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int q = kk + u;
+            const u64* x = xs + ((size_t)(q >= kc ? p.kc_cap + (q - kc) : q)) * MR;
+#pragma unroll
+            for (int r = 0; r < MR; ++r)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) mac(acc[r][v], cross[r][v], x[r], w[u].v[v]);
+        }
+    }
+    for (; kk < k1; ++kk) {
+        WVec<VEC> w;
+        w.load(weight_row<KIND>(p, kk, kc, wB, wF));
+        const u64* x = xs + ((size_t)(kk >= kc ? p.kc_cap + (kk - kc) : kk)) * MR;
+#pragma unroll
+        for (int r = 0; r < MR; ++r)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) mac(acc[r][v], cross[r][v], x[r], w.v[v]);
+    }
+
+    // partial sums of the four wavefronts -> LDS -> one atomic add per output element
+#pragma unroll
+    for (int r0 = 0; r0 < MR; r0 += RG) {
+        if (r0) __syncthreads();
+#pragma unroll
+        for (int r = 0; r < RG; ++r)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+                red[wave][r][lane * VEC + v] = acc[r0 + r][v] + (cross[r0 + r][v] << 32);
+        __syncthreads();
+        for (int i = threadIdx.x; i < RG * 64 * VEC; i += ST) {
+            const int r = i / (64 * VEC), c = i - r * (64 * VEC);
+            u64 s = 0;
+#pragma unroll
+            for (int wv = 0; wv < SW; ++wv) s += red[wv][r][c];
+            const int row = r0 + r, oc = tile0 + c;
+            if (row < p.m && oc < n_eff) atomicAdd(p.Z + (size_t)row * p.ldz + oc, s);
+        }
+    }
+}
+
+template <int MR, int VEC>
+void (*pick_kernel(int kind))(GemmParams, const u64*, int) {
+    return kind == KIND_SOMM ? ring_skinny_kernel<MR, VEC, KIND_SOMM> : ring_skinny_kernel<MR, VEC, KIND_SIMM>;
+}
+
+}  // namespace
+
+int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p) {
+    if (p.m < 1 || p.m > COMET_SKINNY_MAX_ROWS)
+        return comet_fail(ctx, COMET_EINVAL, "%s: row count outside the vector-ALU path", what);
+    const int MR = p.m <= 8 ? 8 : 16;
+    u64* xs = reinterpret_cast<u64*>(p.xp);
+    // k-major activation words and Z := C (the workspace of the matrix-core path, 2048 bytes per
+    // contraction index, always covers the 2 * MR * 8 bytes per index used here)
+    {
+        long work = 2l * MR * p.kc_cap;
+        const long zwork = (long)p.m * p.n_cap;
+        if (zwork > work) work = zwork;
+        long gx = (work + ST - 1) / ST;
+        if (gx > 2048) gx = 2048;
+        if (gx < 1) gx = 1;
+        hipLaunchKernelGGL(skinny_prep_kernel, dim3((unsigned)gx, 2), dim3(ST), 0, ctx->stream, p, xs, MR);
+        COMET_LAUNCH_CHECK(ctx, what);
+    }
+    if (p.kc_cap == 0) return COMET_OK;
+    // two columns per lane need 16-byte aligned row segments on both weight operands and
+    // column pairs that never straddle a gathered block
+    const bool vec2 = (p.ldb & 1) == 0 && (p.ldf & 1) == 0 && (p.n_cap & 1) == 0 && (p.bs & 1) == 0;
+    const int cols = vec2 ? 128 : 64;
+    const long tiles = (p.n_cap + cols - 1) / cols;
+    // about eight workgroups per compute unit, each wavefront with at least one full batch of
+    // rows in flight
+    long slices = (8l * ctx->num_cu + tiles - 1) / tiles;
+    const long max_slices = (2l * p.kc_cap) / (SW * UNROLL);
+    if (slices > max_slices) slices = max_slices;
+    if (ctx->skinny_slices > 0) slices = ctx->skinny_slices;
+    if (slices > 65535) slices = 65535;
+    if (slices < 1) slices = 1;
+    void (*kern)(GemmParams, const u64*, int);
+    if (MR == 8) kern = vec2 ? pick_kernel<8, 2>(p.kind) : pick_kernel<8, 1>(p.kind);
+    else kern = vec2 ? pick_kernel<16, 2>(p.kind) : pick_kernel<16, 1>(p.kind);
+    const bool timed = ctx->ev && ctx->ev_used + 2 <= ctx->ev_cap;
+    if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], ctx->stream);
+    hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)slices), dim3(ST), 0, ctx->stream, p,
+                       (const u64*)xs, (int)slices);
+    if (timed) {
+        (void)hipEventRecord(ctx->ev[ctx->ev_used + 1], ctx->stream);
+        ctx->ev_used += 2;
+    }
+    COMET_LAUNCH_CHECK(ctx, what);
+    return COMET_OK;
+}

@@ -213,6 +213,80 @@ def test_share_ragged_shapes(ctx, kind, m, k, n, bs, keep):
         assert np.array_equal(down(z), case.z[party])
 
 
+@pytest.mark.parametrize("kind,m,k,n,bs,keep", [
+    ("somm", 1, 70, 96, 3, 5), ("somm", 2, 300, 512, 16, 20), ("somm", 5, 45, 200, 8, 9),
+    ("somm", 8, 1100, 640, 64, 7), ("somm", 9, 520, 600, 20, 17), ("somm", 13, 33, 63, 7, 4),
+    ("somm", 16, 777, 384, 32, 5),
+    ("simm", 1, 96, 70, 3, 5), ("simm", 2, 512, 300, 16, 20), ("simm", 5, 200, 45, 8, 9),
+    ("simm", 8, 640, 1100, 64, 7), ("simm", 9, 600, 520, 20, 17), ("simm", 13, 63, 33, 7, 4),
+    ("simm", 16, 384, 777, 32, 5)])
+@pytest.mark.parametrize("path", ["vector", "matrix"])
+def test_share_few_rows(ctx, kind, m, k, n, bs, keep, path):
+    """m <= 16 takes the vector-ALU kernel by default; the matrix-core kernel must give the
+    same bits for the same call (odd widths and odd bs reach the one-column-per-lane variant)."""
+    import paper_2505_07239_amd as comet
+    case = _random_case(kind, m, k, n, bs, keep, 140 + m)
+    t = len(case.idx)
+    ctx.set_tuning(comet.TUNE_SKINNY, 1 if path == "matrix" else 0)
+    try:
+        for party in (0, 1):
+            say("few rows (%s) %s m=%d k=%d n=%d bs=%d party %d" % (path, kind, m, k, n, bs, party))
+            z = _run_share(ctx, kind, party, bs, case.idx, t, case.e, case.f, case.a[party],
+                           case.b[party], case.c[party])
+            torch.cuda.synchronize()
+            assert np.array_equal(down(z), case.z[party])
+    finally:
+        ctx.set_tuning(comet.TUNE_SKINNY, 0)
+
+
+@pytest.mark.parametrize("slices", [1, 3, 64, 5000])
+@pytest.mark.parametrize("kind", ["somm", "simm"])
+def test_share_few_rows_any_split(ctx, kind, slices):
+    """The split of the stacked contraction over workgroups never changes the result, also when
+    most wavefronts get an empty run (more slices than contraction rows)."""
+    import paper_2505_07239_amd as comet
+    m, k, n, bs, keep = 7, 130, 192, 16, 6
+    if kind == "simm":
+        k, n = n, k
+    case = _random_case(kind, m, k, n, bs, keep, 160)
+    ctx.set_tuning(comet.TUNE_SKINNY_SLICES, slices)
+    try:
+        for party in (0, 1):
+            say("few rows split %s slices=%d party %d" % (kind, slices, party))
+            z = _run_share(ctx, kind, party, bs, case.idx, len(case.idx), case.e, case.f,
+                           case.a[party], case.b[party], case.c[party])
+            torch.cuda.synchronize()
+            assert np.array_equal(down(z), case.z[party])
+    finally:
+        ctx.set_tuning(comet.TUNE_SKINNY_SLICES, 0)
+
+
+@pytest.mark.parametrize("kind", ["somm", "simm"])
+def test_share_few_rows_compact_triples(ctx, kind):
+    """Vector-ALU kernel with already indexed triple shares and spare block capacity."""
+    m, k, n, bs, keep = 6, 96, 128, 8, 5
+    case = _random_case(kind, m, k, n, bs, keep, 161)
+    t, cap = len(case.idx), len(case.idx) + 2
+    ld = cap * bs
+    for party in (0, 1):
+        say("few rows compact triples %s party %d" % (kind, party))
+        if kind == "somm":
+            b_sel = co.index_cols(case.b[party], case.idx, bs)
+            args = (case.e, _pad_cols(case.f, ld), case.a[party], _pad_cols(b_sel, ld),
+                    _pad_cols(case.c[party], ld))
+            z = _run_share(ctx, kind, party, bs, case.idx, cap, *args, b_full=False)
+            torch.cuda.synchronize()
+            assert np.array_equal(down(z)[:, :t * bs], case.z[party])
+        else:
+            a_sel = co.index_cols(case.a[party], case.idx, bs)
+            b_sel = co.index_rows(case.b[party], case.idx, bs)
+            args = (_pad_cols(case.e, ld), _pad_rows(case.f, ld), _pad_cols(a_sel, ld),
+                    _pad_rows(b_sel, ld), case.c[party])
+            z = _run_share(ctx, kind, party, bs, case.idx, cap, *args, a_full=False, b_full=False)
+            torch.cuda.synchronize()
+            assert np.array_equal(down(z), case.z[party])
+
+
 @pytest.mark.parametrize("kind", ["somm", "simm"])
 def test_share_compact_triples_and_spare_capacity(ctx, kind):
     """Triple shares passed already indexed; n_blk on the device below n_blk_cap."""
