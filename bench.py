@@ -216,6 +216,10 @@ def micro(ctx, layer):
     macs = ctx.probe_mfma_i8(1024, 2000)
     t = timed(lambda: ctx.probe_mfma_i8(1024, 2000), reps=5)
     out["mfma_i8_issue_TOPs"] = 2.0 * macs / t / 1e12
+    # same instruction stream on uniformly random operand bytes (what share digits look like):
+    # the chip clocks down under the extra switching power
+    t = timed(lambda: ctx.probe_mfma_i8(1024, 2000, True), reps=10)
+    out["mfma_i8_issue_random_operands_TOPs"] = 2.0 * macs / t / 1e12
     macs = ctx.probe_valu_mac64(2048, 2000)
     t = timed(lambda: ctx.probe_valu_mac64(2048, 2000), reps=5)
     out["valu_mac64_Gops"] = 2.0 * macs / t / 1e9
@@ -323,6 +327,8 @@ def main():
             log("%s = %.4g" % (k, v))
         if result["roofline"]["bound"] == "mfma":
             result["roofline"]["frac_of_measured_mfma_issue"] = achieved / result["kernels"]["mfma_i8_issue_TOPs"]
+            result["roofline"]["frac_of_measured_mfma_issue_random_operands"] = \
+                achieved / result["kernels"]["mfma_i8_issue_random_operands_TOPs"]
         else:
             result["roofline"]["frac_of_measured_copy"] = result["roofline"]["achieved"] / result["kernels"]["copy_GBs"]
     if not args.no_cpu_baseline:

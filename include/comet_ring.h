@@ -192,9 +192,14 @@ int comet_timing_end(comet_ctx* ctx, double* total_ms, int* launches);
 
 /* Register-resident issue loop of the int8 matrix instruction the ring GEMM
  * uses: launches `blocks` x 256 threads, `iters` dependent-free MFMA groups
- * each.  out (device, blocks*256 int32) keeps the results alive.  Returns the
- * number of int8 multiply-accumulates issued through *macs (host). */
-int comet_probe_mfma_i8(comet_ctx* ctx, int blocks, int iters, int32_t* out, double* macs);
+ * each.  random_operands = 0: small constant operands; 1: uniformly random
+ * operand bytes (the digits of secret shares are uniformly random; the same
+ * instruction stream then draws more power and the chip clocks down, so this
+ * is the rate a real kernel can approach).  out (device, blocks*256 int32)
+ * keeps the results alive.  Returns the number of int8 multiply-accumulates
+ * issued through *macs (host). */
+int comet_probe_mfma_i8(comet_ctx* ctx, int blocks, int iters, int random_operands, int32_t* out,
+                        double* macs);
 /* Same for the plain 64-bit vector multiply-add: *macs = ring MACs issued. */
 int comet_probe_valu_mac64(comet_ctx* ctx, int blocks, int iters, uint64_t* out, double* macs);
 /* Plain device copy of n_elems words (bandwidth yardstick, 16 B per element). */

@@ -63,7 +63,7 @@ def load_library() -> ctypes.CDLL:
     share = [vp, i32, i64, i64, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz]
     lib.comet_somm_share.argtypes = share
     lib.comet_simm_share.argtypes = share
-    lib.comet_probe_mfma_i8.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.comet_probe_mfma_i8.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
     lib.comet_probe_valu_mac64.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
     lib.comet_probe_copy.argtypes = [vp, vp, vp, sz]
     lib.comet_set_tuning.argtypes = [vp, i32, i32]
@@ -221,11 +221,12 @@ class Context:
         self._check(self.lib.comet_timing_end(self.h, ctypes.byref(ms), ctypes.byref(n)))
         return ms.value, n.value
 
-    def probe_mfma_i8(self, blocks: int, iters: int) -> float:
+    def probe_mfma_i8(self, blocks: int, iters: int, random_operands: bool = False) -> float:
         out = torch.empty(blocks * 256, dtype=torch.int32, device="cuda:%d" % self.device)
         macs = ctypes.c_double()
         self._sync_stream()
-        self._check(self.lib.comet_probe_mfma_i8(self.h, blocks, iters, _ptr(out), ctypes.byref(macs)))
+        self._check(self.lib.comet_probe_mfma_i8(self.h, blocks, iters, int(random_operands), _ptr(out),
+                                                 ctypes.byref(macs)))
         return macs.value
 
     def probe_valu_mac64(self, blocks: int, iters: int) -> float:

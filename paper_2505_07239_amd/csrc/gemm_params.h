@@ -30,6 +30,9 @@ struct GemmParams {
     int mpad;       // rows of xp, multiple of 128
     int chunk;      // contraction steps per scheduling slice, 1 .. MAX_SEG
     int ks_cap;     // contraction steps per half, ceil(kc_cap / 32)
+#ifdef EXP_TRACE
+    u64* trace;
+#endif
 };
 
 static __device__ __forceinline__ int n_blocks(const GemmParams& p) {

@@ -360,7 +360,16 @@ struct Loader {
     // stacked contraction and the row gather are selects on wave-uniform values.
     template <int J, int E, bool SPLIT>
     __device__ __forceinline__ void load_piece(const GemmParams& p, int kc) {
-        if (SPLIT) wa[J][E] = to_digits(wn[J][E]);
+        if (SPLIT) {
+            // The word was requested one step ago.  Like the LDS-DMA, the request is issued from
+            // inline assembly, so the wait is written here by hand: everything but the
+            // VM_PER_STEP - 1 vector-memory operations issued after it may still be in flight.
+            // (Left to the compiler, the wait would not count the LDS-DMA transfers issued in
+            // between and would stall every step until those have landed.)  The register is
+            // an in/out operand of the wait, so nothing that uses the word can move above it.
+            asm volatile("s_waitcnt vmcnt(%1)" : "+v"(wn[J][E]) : "n"(T::VM_PER_STEP - 1) : "memory");
+            wa[J][E] = to_digits(wn[J][E]);
+        }
         // octet index is the same for all lanes of a wavefront
         const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * J) / T::BN));
         const int k0 = s2 * KSTEP + oct * 8;
@@ -378,7 +387,7 @@ struct Loader {
         }
         // every operand holds fewer than 2^31 words (host check), so the word offset fits 32 bits
         const unsigned off = (unsigned)row * (unsigned)ld2;
-        wn[J][E] = src[off];
+        asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(wn[J][E]) : "v"(src + off) : "memory");
     }
 
     // quarter Q of the byte transpose of task J: Q = 0: low digits of words 0..3,
@@ -446,6 +455,24 @@ struct SlotMap {
     }
 };
 
+// Fragment reads of a step in consumption order: a[0][*], then bf[*][0..7] (all first used
+// with digit plane 0 of the activation side), then a[1..7][*].  slot(R) is the matrix
+// instruction after which read R is issued, -1 for the reads issued before the first one.
+template <int WM, int WN>
+struct ReadMap {
+    static constexpr int NR = 8 * (WM + WN);
+    static constexpr int READ_LEAD = 8;
+    static constexpr int need(int r) {
+        if (r < WM) return r * WN;
+        if (r < WM + 8 * WN) return ((r - WM) / WN) * WM * WN + (r - WM) % WN;
+        const int t = 1 + (r - WM - 8 * WN) / WM, ii = (r - WM - 8 * WN) % WM;
+        int start = 0;
+        for (int q = 0; q < t; ++q) start += (8 - q) * WM * WN;
+        return start + ii * WN;
+    }
+    static constexpr int slot(int r) { return need(r) - READ_LEAD < 0 ? -1 : need(r) - READ_LEAD; }
+};
+
 // One contraction step of a workgroup: 36 * WM * WN matrix instructions on the
 // fragments of activation stage xs and weight stage ws, each followed by its
 // share of the look-ahead pieces (see Loader).  The scheduling fences keep the
@@ -463,17 +490,30 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
     v4i bf[WN][8];
     v4i a[8][WM];
     ld.begin(p, ks_next2, KS, kc, ks_limit);
-    // all fragment reads of the step, in the order the matrix instructions consume them
-#pragma unroll
-    for (int ii = 0; ii < WM; ++ii) a[0][ii] = lds_frag(xs + a_off + (ii * 32) * 16);
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-#pragma unroll
-        for (int j = 0; j < WN; ++j) bf[j][t] = lds_frag(ws + b_off + (t * 2 * T::BN + j * 32) * 16);
-#pragma unroll
-    for (int t = 1; t < 8; ++t)
-#pragma unroll
-        for (int ii = 0; ii < WM; ++ii) a[t][ii] = lds_frag(xs + a_off + (t * 2 * T::BM + ii * 32) * 16);
+    // Fragment reads are issued in the order the matrix instructions consume them, each
+    // READ_LEAD instructions ahead of its first use: the first instruction of a step then waits
+    // for a handful of reads instead of the whole step's, and a fragment of a late digit plane
+    // does not hold its registers through the early ones.
+    using RM = ReadMap<WM, WN>;
+    auto read_frag = [&](auto rc) {
+        constexpr int R = decltype(rc)::value;
+        if constexpr (R < WM) {
+            a[0][R] = lds_frag(xs + a_off + (R * 32) * 16);
+        } else if constexpr (R < WM + 8 * WN) {
+            constexpr int uu = (R - WM) / WN, j = (R - WM) % WN;
+            bf[j][uu] = lds_frag(ws + b_off + (uu * 2 * T::BN + j * 32) * 16);
+        } else {
+            constexpr int t = 1 + (R - WM - 8 * WN) / WM, ii = (R - WM - 8 * WN) % WM;
+            a[t][ii] = lds_frag(xs + a_off + (t * 2 * T::BM + ii * 32) * 16);
+        }
+    };
+    auto reads_at = [&](auto slot) {
+        constexpr int S = decltype(slot)::value;
+        [&]<int... Rs>(std::integer_sequence<int, Rs...>) {
+            ([&] { if constexpr (RM::slot(Rs) == S) read_frag(std::integral_constant<int, Rs>{}); }(), ...);
+        }(std::make_integer_sequence<int, RM::NR>{});
+    };
+    reads_at(std::integral_constant<int, -1>{});
     __builtin_amdgcn_sched_barrier(0);
     (
         [&] {
@@ -482,6 +522,7 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
             constexpr int uu = r / (WM * WN), ii = (r / WN) % WM, j = r % WN;
             acc[ii][j][t + uu] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t][ii], bf[j][uu],
                                                                         acc[ii][j][t + uu], 0, 0, 0);
+            reads_at(std::integral_constant<int, M>{});
             constexpr int p0 = (int)((long)M * L::P_END / NM), p1 = (int)((long)(M + 1) * L::P_END / NM);
             ld.template pieces<p0, true>(std::make_integer_sequence<int, p1 - p0>{}, p, kc, xs_next2, ws_next);
             __builtin_amdgcn_sched_barrier(0);
