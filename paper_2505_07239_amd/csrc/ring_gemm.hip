@@ -110,11 +110,24 @@ __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
     if (blockIdx.z == 2) {
         // Z := C on the kept region (the GEMM adds its partial sums onto it)
         const int n_eff = p.kind == KIND_SOMM ? nblk * p.bs : p.n_cap;
-        const long total = (long)p.m * n_eff;
         const long stride = (long)gridDim.x * gridDim.y * GT;
-        for (long i = ((long)blockIdx.y * gridDim.x + blockIdx.x) * GT + threadIdx.x; i < total; i += stride) {
-            const long r = i / n_eff, c = i - r * n_eff;
-            p.Z[r * p.ldz + c] = p.C[r * p.ldz + c];
+        const long t0 = ((long)blockIdx.y * gridDim.x + blockIdx.x) * GT + threadIdx.x;
+        if (((n_eff | p.ldz) & 1) == 0) {
+            // 16-byte accesses (the operands are 16-byte aligned and every row starts on a pair)
+            typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+            const int half = n_eff >> 1;
+            const long total = (long)p.m * half;
+            for (long i = t0; i < total; i += stride) {
+                const long r = i / half, c = (i - r * half) * 2;
+                *reinterpret_cast<u64x2*>(p.Z + r * p.ldz + c) =
+                    *reinterpret_cast<const u64x2*>(p.C + r * p.ldz + c);
+            }
+        } else {
+            const long total = (long)p.m * n_eff;
+            for (long i = t0; i < total; i += stride) {
+                const long r = i / n_eff, c = i - r * n_eff;
+                p.Z[r * p.ldz + c] = p.C[r * p.ldz + c];
+            }
         }
         return;
     }
@@ -739,6 +752,10 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     {
         unsigned gx = (unsigned)((p.ks_cap * 2 + 3) / 4);
         if (gx < 1) gx = 1;
+        // the Z := C slab shares the launch: give it enough workgroups for about four 16-byte
+        // accesses per thread (the packing slabs return at once from the extra ones)
+        const long zgx = ((long)p.m * p.n_cap / (2l * 4 * GT) + p.mpad / 64 - 1) / (p.mpad / 64);
+        if (zgx > gx) gx = (unsigned)(zgx > 4096 ? 4096 : zgx);
         hipLaunchKernelGGL(xpack_kernel, dim3(gx, (unsigned)(p.mpad / 64), 3), dim3(GT), 0, ctx->stream, p);
         COMET_LAUNCH_CHECK(ctx, what);
     }
