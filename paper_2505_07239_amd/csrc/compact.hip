@@ -124,10 +124,26 @@ __global__ __launch_bounds__(CT) void compact_pack_kernel(const uint8_t* __restr
     const long t1 = t0 + tok_per < n_tok ? t0 + tok_per : n_tok;
     if (t0 >= t1) return;
     u32 bits[ITEMS];
+    if (rows_aligned && base + CHUNK <= nb) {
+        // whole chunk inside the mask: the 16-byte loads of a token row are all in flight at once
+        u32x4 acc[ITEMS];
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j)
-        bits[j] = or_flags16(mask + t0 * nb, t1 - t0, nb, base + ((long)j * CT + threadIdx.x) * FL,
-                             rows_aligned);
+        for (int j = 0; j < ITEMS; ++j) acc[j] = u32x4{0, 0, 0, 0};
+        const uint8_t* src = mask + t0 * nb + base + (long)threadIdx.x * FL;
+        for (long t = t0; t < t1; ++t, src += nb) {
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j)
+                acc[j] |= __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (long)j * CT * FL));
+        }
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+            bits[j] = nz_bits4(acc[j].x, 0) | nz_bits4(acc[j].y, 4) | nz_bits4(acc[j].z, 8) | nz_bits4(acc[j].w, 12);
+    } else {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+            bits[j] = or_flags16(mask + t0 * nb, t1 - t0, nb, base + ((long)j * CT + threadIdx.x) * FL,
+                                 rows_aligned);
+    }
     int cnt = 0;
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
@@ -214,35 +230,54 @@ __global__ __launch_bounds__(ST) void compact_scan_kernel(int* __restrict__ coun
     if (threadIdx.x == 0) *n_blk_dev = carry;
 }
 
-// pass 3: each lane owns 64 consecutive flags (four 16-bit words), one workgroup scan gives
-// the positions.  When the workgroup's indices fit the LDS stage they are scattered there
-// and copied out as one contiguous run (full-width global stores); a denser chunk writes its
-// indices directly.
-constexpr int STAGE_CAP = 6144;
+// pass 3: each lane owns 64 consecutive flags (four 16-bit words, one 8-byte load), one
+// workgroup scan gives the positions.  When the workgroup's indices fit the LDS stage they are
+// scattered there and copied out as one contiguous run with 16-byte stores: the run is placed
+// in the stage at the same position inside a 16-byte quad as in the output, so that aligned quads of the
+// stage are aligned quads of the output, and only the ragged ends are written one by one.
+// A denser chunk writes its indices directly.
+constexpr int STAGE_CAP = 4092;
 __global__ __launch_bounds__(CT) void compact_emit_kernel(const unsigned short* __restrict__ words,
                                                           const int* __restrict__ offsets, long nb,
                                                           int* __restrict__ blk_idx) {
     __shared__ int sm[CT / 64 + 1];
-    __shared__ int stage[STAGE_CAP];
+    __shared__ __align__(16) int stage[STAGE_CAP + 4];
     const long w0 = (long)blockIdx.x * (CHUNK / FL) + (long)threadIdx.x * ITEMS;
+    static_assert(ITEMS == 4, "one 8-byte load per lane");
+    // the word array is padded to whole workgroup chunks, so the load is always in range
+    const unsigned long long packed = *reinterpret_cast<const unsigned long long*>(words + w0);
     u32 bits[ITEMS];
     int cnt = 0;
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) {
-        bits[j] = ((w0 + j) * FL < nb) ? (u32)words[w0 + j] : 0u;
+        bits[j] = ((w0 + j) * FL < nb) ? (u32)((packed >> (16 * j)) & 0xffffu) : 0u;
         cnt += __builtin_popcount(bits[j]);
     }
     int total;
     int pos = block_excl_scan(cnt, sm, &total);
-    int* out = blk_idx + offsets[blockIdx.x];
+    const long off = offsets[blockIdx.x];
+    int* out = blk_idx + off;
     if (total <= STAGE_CAP) {
+        const int ph = (int)((reinterpret_cast<uintptr_t>(out) >> 2) & 3);   // position inside a 16-byte quad
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {
-            emit_bits(bits[j], (int)((w0 + j) * FL), stage + pos);
+            emit_bits(bits[j], (int)((w0 + j) * FL), stage + ph + pos);
             pos += __builtin_popcount(bits[j]);
         }
         __syncthreads();
-        for (int i = threadIdx.x; i < total; i += CT) out[i] = stage[i];
+        // stage[ph .. ph + total) -> out[0 .. total); quads q cover stage[4q .. 4q + 4)
+        const int end = ph + total;
+        const int q0 = ph ? 1 : 0, q1 = end >> 2;            // whole quads inside the run
+        typedef int int4v __attribute__((ext_vector_type(4)));
+        int4v* out4 = reinterpret_cast<int4v*>(out - ph);     // 16-byte aligned by construction
+        const int4v* st4 = reinterpret_cast<const int4v*>(stage);
+        for (int q = q0 + threadIdx.x; q < q1; q += CT) out4[q] = st4[q];
+        // ragged head (before the first whole quad) and tail (after the last)
+        const int head_end = q0 * 4 < end ? q0 * 4 : end;
+        if ((int)threadIdx.x >= ph && (int)threadIdx.x < head_end) out[threadIdx.x - ph] = stage[threadIdx.x];
+        const int tail0 = q1 * 4 > head_end ? q1 * 4 : head_end;
+        const int ti = tail0 + (int)threadIdx.x;
+        if (ti < end) out[ti - ph] = stage[ti];
     } else {
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) {

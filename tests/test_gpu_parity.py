@@ -144,6 +144,27 @@ def test_compact_mask_degenerate(ctx):
     assert int(n_dev.item()) == len(want) and np.array_equal(idx[:len(want)].cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("shift", [0, 1, 2, 3])
+@pytest.mark.parametrize("density", [0.001, 0.15, 0.9])
+def test_compact_mask_output_alignment(ctx, shift, density):
+    """The index list may start at any 4-byte boundary; the large path writes whole 16-byte
+    quads in the middle of each workgroup's run and single words at its ragged ends.  Dense
+    masks overflow the LDS stage and take the direct path."""
+    nb = 200_003
+    say("compact output shift %d density %.3f" % (shift, density))
+    m = masks.stress_mask(36, 3 + shift, nb, density)[None, :]
+    backing = torch.full((nb + 8,), -7, dtype=torch.int32, device="cuda")
+    n_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ctx.compact_mask(torch.from_numpy(m).cuda(), backing[shift:shift + nb], n_dev)
+    torch.cuda.synchronize()
+    want = co.compact_mask(m)
+    got = backing.cpu().numpy()
+    assert int(n_dev.item()) == len(want)
+    assert np.array_equal(got[shift:shift + len(want)], want)
+    # nothing outside the list is touched
+    assert np.all(got[:shift] == -7) and np.all(got[shift + len(want):] == -7)
+
+
 # ---------------------------------------------------------------------------
 # (3) output shares
 # ---------------------------------------------------------------------------
