@@ -187,3 +187,34 @@ def beaver_share_at(party: int, e, f, a_i, b_i, c_i, r: int, c: int) -> int:
     n = f.shape[1]
     return int(lib().co_beaver_share_at(party, _p(e), _p(f), _p(a_i), _p(b_i), _p(c_i),
                                         m, k, n, r, c))
+
+
+# ---- Protocols 2 and 3 in general form, one pass over all components / columns ----
+
+def beaver_share_blocks(party: int, e, f, a_i, b_i, c_i, row_comp, col_comp) -> np.ndarray:
+    """Protocol 2 merged: element (r, c) is computed iff ``row_comp[r] == col_comp[c] >= 0``."""
+    e, f, a_i, b_i, c_i = map(_u64, (e, f, a_i, b_i, c_i))
+    row_comp = np.ascontiguousarray(row_comp, dtype=np.int32)
+    col_comp = np.ascontiguousarray(col_comp, dtype=np.int32)
+    m, k = e.shape
+    n = f.shape[1]
+    assert f.shape == (k, n) and a_i.shape == (m, k) and b_i.shape == (k, n) and c_i.shape == (m, n)
+    assert row_comp.shape == (m,) and col_comp.shape == (n,)
+    z = np.empty((m, n), dtype=np.uint64)
+    lib().co_beaver_share_blocks(party, _p(e), _p(f), _p(a_i), _p(b_i), _p(c_i), _p(row_comp),
+                                 _p(col_comp), _p(z), m, k, n)
+    return z
+
+
+def beaver_share_sparse_input(party: int, e, f, a_i, b_i, c_i, s) -> np.ndarray:
+    """Protocol 3 summed over its columns: entries of E / A_i outside ``s`` take no part."""
+    e, f, a_i, b_i, c_i = map(_u64, (e, f, a_i, b_i, c_i))
+    s = np.ascontiguousarray(s, dtype=np.uint8)
+    m, k = e.shape
+    n = f.shape[1]
+    assert f.shape == (k, n) and a_i.shape == (m, k) and b_i.shape == (k, n) and c_i.shape == (m, n)
+    assert s.shape == (m, k)
+    z = np.empty((m, n), dtype=np.uint64)
+    lib().co_beaver_share_sparse_input(party, _p(e), _p(f), _p(a_i), _p(b_i), _p(c_i), _p(s), _p(z),
+                                       m, k, n)
+    return z

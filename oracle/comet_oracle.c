@@ -174,3 +174,59 @@ u64 co_beaver_share_at(int party, const u64* E, const u64* F, const u64* A_i, co
         for (int l = 0; l < k; ++l) z += E[(size_t)r * k + l] * F[(size_t)l * n + c];
     return z;
 }
+
+/* ---- Protocol 2 (SOMM), all components in one pass ----
+ * The components of the bipartite graph partition the participating rows of X
+ * and columns of Y; rows and columns carry the number of their component
+ * (row_comp[r], col_comp[c]; a negative number = takes part in none).  Output
+ * element (r, c) belongs to the result block of a component exactly when both
+ * numbers agree, and is then that component's Pi_MatMul share by Eq. 1 with
+ * the component's own triple, stored in the same m x n layout (A_i row r is the
+ * triple row of X row r, B_i column c that of Y column c, C_i(r, c) defined on
+ * the blocks only).  Everything else is zero ("Merge" into an empty matrix).
+ * E, A_i: m x k;  F, B_i: k x n;  C_i, Z_i: m x n. */
+void co_beaver_share_blocks(int party, const u64* E, const u64* F, const u64* A_i, const u64* B_i,
+                            const u64* C_i, const int32_t* row_comp, const int32_t* col_comp,
+                            u64* Z_i, int m, int k, int n) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < m; ++r)
+        for (int c = 0; c < n; ++c) {
+            u64 z = 0;
+            if (row_comp[r] >= 0 && row_comp[r] == col_comp[c]) {
+                z = C_i[(size_t)r * n + c];
+                for (int l = 0; l < k; ++l) z += E[(size_t)r * k + l] * B_i[(size_t)l * n + c];
+                for (int l = 0; l < k; ++l) z += A_i[(size_t)r * k + l] * F[(size_t)l * n + c];
+                if (party == 1)
+                    for (int l = 0; l < k; ++l) z += E[(size_t)r * k + l] * F[(size_t)l * n + c];
+            }
+            Z_i[(size_t)r * n + c] = z;
+        }
+}
+
+/* ---- Protocol 3 (SIMM), all columns in one pass ----
+ * Column j of X contributes the outer product of its sub-vector on the row set
+ * R_j = { r : S(r, j) != 0 } with row j of Y; Merge&Sum adds the result blocks
+ * of a row.  With the column triples stored at their positions (A_i(r, j) for
+ * r in R_j, B_i row j, and C_i = the sum over j of the scattered C shares) the
+ * sum over the columns of Eq. 1 is
+ *   Z_i(r, :) = C_i(r, :) + sum_{j : S(r,j) != 0} ( E(r,j) B_i(j,:) + A_i(r,j) F(j,:) + (i-1) E(r,j) F(j,:) ).
+ * S: m x k bytes.  E, A_i: m x k (entries outside S never read);  F, B_i: k x n. */
+void co_beaver_share_sparse_input(int party, const u64* E, const u64* F, const u64* A_i,
+                                  const u64* B_i, const u64* C_i, const uint8_t* S, u64* Z_i,
+                                  int m, int k, int n) {
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < m; ++r) {
+        u64* z = Z_i + (size_t)r * n;
+        for (int c = 0; c < n; ++c) z[c] = C_i[(size_t)r * n + c];
+        for (int j = 0; j < k; ++j) {
+            if (!S[(size_t)r * k + j]) continue;
+            const u64 e = E[(size_t)r * k + j], a = A_i[(size_t)r * k + j];
+            const u64* f = F + (size_t)j * n;
+            const u64* b = B_i + (size_t)j * n;
+            for (int c = 0; c < n; ++c) z[c] += e * b[c];
+            for (int c = 0; c < n; ++c) z[c] += a * f[c];
+            if (party == 1)
+                for (int c = 0; c < n; ++c) z[c] += e * f[c];
+        }
+    }
+}

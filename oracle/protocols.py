@@ -240,3 +240,88 @@ def block_case(kind: str, x_sh, y_sh, mask: np.ndarray, bs: int, a: np.ndarray, 
         case.g = (trace["g0"], trace["g1"])
         case.e, case.f = trace["e"], trace["f"]
     return case
+
+
+# ---------------------------------------------------------------------------
+# Protocols 2 and 3 in one pass (what a party computes locally, all components
+# / all columns at once), from the same material as the literal forms above
+# ---------------------------------------------------------------------------
+
+@dataclass
+class GeneralCase:
+    """Material of one general-form protocol run in the layout of the full matrices.
+
+    ``a``, ``b``, ``c``: the two parties' triple shares (for SOMM ``c`` is
+    defined on the result blocks and zero elsewhere; for SIMM it is the sum of
+    the scattered column triples); ``e``, ``f``: opened masked operands;
+    ``z``: the two parties' output shares by the one-pass formula.
+    ``row_comp`` / ``col_comp`` (SOMM only): component number of every row of
+    X / column of Y, -1 for the ones that take part in no dot product;
+    ``comps``: the components as (rows, cols), ordered by smallest row."""
+    kind: str
+    s: np.ndarray
+    a: Tuple[np.ndarray, np.ndarray]
+    b: Tuple[np.ndarray, np.ndarray]
+    c: Tuple[np.ndarray, np.ndarray]
+    e: np.ndarray
+    f: np.ndarray
+    z: Tuple[np.ndarray, np.ndarray]
+    row_comp: Optional[np.ndarray] = None
+    col_comp: Optional[np.ndarray] = None
+    comps: Optional[list] = None
+
+
+def component_numbers(s: np.ndarray):
+    """(components, row_comp, col_comp) of the bipartite graph of ``s``."""
+    m, n = np.asarray(s).shape
+    comps = components(s)
+    row_comp = np.full(m, -1, dtype=np.int32)
+    col_comp = np.full(n, -1, dtype=np.int32)
+    for t, (i_x, i_y) in enumerate(comps):
+        row_comp[i_x] = t
+        col_comp[i_y] = t
+    return comps, row_comp, col_comp
+
+
+def somm_general(x, y, s, a, b, a_split, b_split, c_split) -> GeneralCase:
+    """Protocol 2 with the per-component triples of :func:`somm_literal` laid out
+    at their rows and columns, evaluated by ``oracle.beaver_share_blocks``."""
+    comps, row_comp, col_comp = component_numbers(s)
+    a_sh, b_sh = co.share(a, a_split), co.share(b, b_split)
+    m, n = np.asarray(s).shape
+    c_sh = [np.zeros((m, n), dtype=np.uint64) for _ in (0, 1)]
+    for i_x, i_y in comps:                                # the TTP's C = A[I_x] B[:, I_y], shared
+        ct = co.ring_matmul(co.index_rows(a, i_x, 1), co.index_cols(b, i_y, 1))
+        c0 = co.index_cols(co.index_rows(c_split, i_x, 1), i_y, 1)
+        c_sh[0][np.ix_(i_x, i_y)] = c0
+        c_sh[1][np.ix_(i_x, i_y)] = ct - c0
+    d = [co.mask_share(x[i], a_sh[i]) for i in (0, 1)]
+    g = [co.mask_share(y[i], b_sh[i]) for i in (0, 1)]
+    e, f = co.open_(d[0], d[1]), co.open_(g[0], g[1])
+    z = tuple(co.beaver_share_blocks(i, e, f, a_sh[i], b_sh[i], c_sh[i], row_comp, col_comp)
+              for i in (0, 1))
+    return GeneralCase("somm", np.asarray(s), a_sh, b_sh, tuple(c_sh), e, f, z, row_comp, col_comp, comps)
+
+
+def simm_general(x, y, s, a, b, a_split, b_split, c_split_cols) -> GeneralCase:
+    """Protocol 3 with the column triples of :func:`simm_literal` laid out at their
+    positions, evaluated by ``oracle.beaver_share_sparse_input``."""
+    s = (np.asarray(s) != 0).astype(np.uint8)
+    m, k = s.shape
+    p = y[0].shape[1]
+    a_sh, b_sh = co.share(a, a_split), co.share(b, b_split)
+    c_sh = [np.zeros((m, p), dtype=np.uint64) for _ in (0, 1)]
+    for j in range(k):
+        r_j = np.nonzero(s[:, j])[0].astype(np.int32)
+        if not len(r_j):
+            continue
+        jj = np.array([j], dtype=np.int32)
+        cj = co.ring_matmul(co.index_rows(co.index_cols(a, jj, 1), r_j, 1), co.index_rows(b, jj, 1))
+        c0 = co.index_rows(np.ascontiguousarray(c_split_cols[j]), r_j, 1)
+        c_sh[0][r_j, :] += c0
+        c_sh[1][r_j, :] += cj - c0
+    d = [co.mask_share(x[i], a_sh[i]) for i in (0, 1)]
+    g = [co.mask_share(y[i], b_sh[i]) for i in (0, 1)]
+    e, f = co.open_(d[0], d[1]), co.open_(g[0], g[1])
+    z = tuple(co.beaver_share_sparse_input(i, e, f, a_sh[i], b_sh[i], c_sh[i], s) for i in (0, 1))
+    return GeneralCase("simm", s, a_sh, b_sh, tuple(c_sh), e, f, z)

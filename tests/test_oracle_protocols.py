@@ -255,3 +255,74 @@ def test_shares_look_uniform():
         expect = top.size / 256.0
         chi2 = float(((counts - expect) ** 2 / expect).sum())
         assert chi2 < 400.0        # 255 dof: mean 255, sd 22.6
+
+
+# ---------------------------------------------------------------------------
+# one-pass general forms (what the GPU path is compared with) against the
+# literal protocols
+# ---------------------------------------------------------------------------
+
+def _random_s(seed, m, n, one_in):
+    return (u64(seed, 40, m, n) % np.uint64(one_in) == 0).astype(np.uint8)
+
+
+@pytest.mark.parametrize("seed,m,k,n,one_in", [(31, 5, 4, 7, 4), (32, 9, 6, 11, 6), (33, 6, 3, 6, 2),
+                                               (34, 12, 5, 16, 9), (35, 3, 2, 4, 1)])
+def test_somm_one_pass_equals_literal_per_party(seed, m, k, n, one_in):
+    """Protocol 2 evaluated in one pass over all components gives each party the very share
+    the component-by-component protocol gives it (same triples, same splits)."""
+    s = _random_s(seed, m, n, one_in)
+    x_sh, y_sh = (u64(seed, 1, m, k), u64(seed, 2, m, k)), (u64(seed, 3, k, n), u64(seed, 4, k, n))
+    args = (u64(seed, 5, m, k), u64(seed, 6, k, n), u64(seed, 7, m, k), u64(seed, 8, k, n), u64(seed, 9, m, n))
+    lit = protocols.somm_literal(x_sh, y_sh, s, *args)
+    gen = protocols.somm_general(x_sh, y_sh, s, *args)
+    for i in (0, 1):
+        assert np.array_equal(gen.z[i], lit[i])
+    # the merged result holds X Y on the result blocks and nothing elsewhere
+    xy = co.ring_matmul(co.reconstruct(*x_sh), co.reconstruct(*y_sh))
+    on_blocks = (gen.row_comp[:, None] >= 0) & (gen.row_comp[:, None] == gen.col_comp[None, :])
+    assert np.array_equal(co.reconstruct(*gen.z), np.where(on_blocks, xy, np.uint64(0)))
+    # every requested output lies on a block
+    assert np.all(on_blocks[s != 0])
+
+
+def test_somm_one_pass_all_ones_is_the_dense_share():
+    m, k, n = 4, 5, 6
+    s = np.ones((m, n), np.uint8)
+    x_sh, y_sh = (u64(36, 1, m, k), u64(36, 2, m, k)), (u64(36, 3, k, n), u64(36, 4, k, n))
+    gen = protocols.somm_general(x_sh, y_sh, s, u64(36, 5, m, k), u64(36, 6, k, n), u64(36, 7, m, k),
+                                 u64(36, 8, k, n), u64(36, 9, m, n))
+    assert len(gen.comps) == 1
+    for i in (0, 1):
+        assert np.array_equal(gen.z[i], co.beaver_share(i, gen.e, gen.f, gen.a[i], gen.b[i], gen.c[i]))
+
+
+@pytest.mark.parametrize("seed,m,k,p,one_in", [(41, 5, 7, 4, 3), (42, 9, 11, 6, 5), (43, 4, 6, 3, 1),
+                                               (44, 8, 16, 5, 8)])
+def test_simm_one_pass_equals_literal_per_party(seed, m, k, p, one_in):
+    """Protocol 3 summed over its columns in one pass gives each party the share the
+    column-by-column protocol gives it."""
+    s = _random_s(seed, m, k, one_in)
+    x_sh, y_sh = (u64(seed, 1, m, k), u64(seed, 2, m, k)), (u64(seed, 3, k, p), u64(seed, 4, k, p))
+    args = (u64(seed, 5, m, k), u64(seed, 6, k, p), u64(seed, 7, m, k), u64(seed, 8, k, p),
+            [u64(seed, 100 + j, m, p) for j in range(k)])
+    lit = protocols.simm_literal(x_sh, y_sh, s, *args)
+    gen = protocols.simm_general(x_sh, y_sh, s, *args)
+    for i in (0, 1):
+        assert np.array_equal(gen.z[i], lit[i])
+    xs = np.where(s != 0, co.reconstruct(*x_sh), np.uint64(0))
+    assert np.array_equal(co.reconstruct(*gen.z), co.ring_matmul(xs, co.reconstruct(*y_sh)))
+
+
+def test_simm_one_pass_ignores_entries_outside_s():
+    """Entries of the opened X side outside the sparsity distribution are never sent; whatever
+    stands there must not influence the share."""
+    m, k, p = 6, 9, 4
+    s = _random_s(45, m, k, 3)
+    x_sh, y_sh = (u64(45, 1, m, k), u64(45, 2, m, k)), (u64(45, 3, k, p), u64(45, 4, k, p))
+    gen = protocols.simm_general(x_sh, y_sh, s, u64(45, 5, m, k), u64(45, 6, k, p), u64(45, 7, m, k),
+                                 u64(45, 8, k, p), [u64(45, 100 + j, m, p) for j in range(k)])
+    junk_e = np.where(s != 0, gen.e, u64(45, 50, m, k))
+    junk_a = np.where(s != 0, gen.a[1], u64(45, 51, m, k))
+    assert np.array_equal(co.beaver_share_sparse_input(1, junk_e, gen.f, junk_a, gen.b[1], gen.c[1], s),
+                          gen.z[1])
