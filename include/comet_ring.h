@@ -161,6 +161,62 @@ int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64
                      const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i,
                      void* ws, size_t ws_bytes);
 
+/* ---- (4) Protocols 2 and 3 in general form: per-token sparsity ---------- */
+
+/* Protocol 2 step 1 at (token, neuron block) granularity: connected components
+ * of the bipartite graph whose left nodes are the tokens (rows of X), right
+ * nodes the neuron blocks (column blocks of Y) and edges the non-zero bytes of
+ * mask (n_tok x nb).  Components are numbered by their smallest token.
+ *   row_idx / row_comp [n_tok]: the tokens that have at least one active block,
+ *       ordered by (component, token), and the component number of each;
+ *   blk_idx / blk_comp [nb]: the blocks at least one token uses, ordered by
+ *       (component, block), and their component numbers;
+ *   *n_row_dev, *n_blk_dev, *n_comp_dev: the three counts (device).
+ * Entries beyond the counts are left untouched.  One workgroup does the whole
+ * search in LDS (label propagation, then a sort): n_tok <= 1024, nb <= 4096 and
+ * n_tok * ceil(nb / 32) <= 16384, else COMET_ECAP.  All outputs int32, 4-byte
+ * aligned.  No workspace. */
+int comet_components(comet_ctx* ctx, const uint8_t* mask, int64_t n_tok, int64_t nb,
+                     int32_t* row_idx, int32_t* row_comp, int32_t* n_row_dev,
+                     int32_t* blk_idx, int32_t* blk_comp, int32_t* n_blk_dev,
+                     int32_t* n_comp_dev);
+
+/* Protocol 2 with the result blocks of all components computed by one call.
+ * Operands are in the order comet_components lists them: row r of E, A_i, C_i,
+ * Z_i is token row_idx[r], column c of the compact operands is neuron
+ * blk_idx[c / bs] * bs + c % bs.  Element (r, c) lies on a result block when
+ * row_comp[r] == blk_comp[c / bs]; there
+ *     [Z]_i = [C]_i + E [B]_i + [A]_i F + party * E F        (mod 2^64)
+ * with the component's own triple stored at those rows and columns; everywhere
+ * else on the first *n_row_dev rows and *n_blk_dev * bs columns Z_i is set to
+ * zero (the merge into an empty matrix).  Tiles of the output that touch no
+ * block are skipped.
+ *   E, A_i : m_cap x k   (rows at or beyond *n_row_dev are ignored)
+ *   F      : k x ld;  B_i: k x n_full when flags & COMET_FULL_B, else k x ld
+ *   C_i,Z_i: m_cap x ld, ld = n_blk_cap * bs
+ * n_row_dev may be null (then all m_cap rows take part).  Limits as for
+ * comet_somm_share. */
+int comet_somm_share_blocks(comet_ctx* ctx, int party, int64_t m_cap, int64_t k, int64_t n_full,
+                            int bs, const int32_t* blk_idx, const int32_t* blk_comp,
+                            const int32_t* n_blk_dev, int n_blk_cap, const int32_t* row_comp,
+                            const int32_t* n_row_dev, int flags, const uint64_t* E,
+                            const uint64_t* F, const uint64_t* A_i, const uint64_t* B_i,
+                            const uint64_t* C_i, uint64_t* Z_i, void* ws, size_t ws_bytes);
+
+/* Protocol 3 with per-token row sets: as comet_simm_share, but entry (r, j) of
+ * the activation-side operands takes part only when token r uses the block of
+ * neuron j, i.e. token_mask[r * nb + blk_idx[j / bs]] != 0 (token_mask: m x nb
+ * bytes, the sparsity distribution of X at block granularity; R_j of Protocol 3
+ * is the set of such r).  Entries outside it are never read as values: they
+ * are the ones the parties do not exchange.  C_i is the sum of the scattered
+ * column triples' C shares. */
+int comet_simm_share_masked(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64_t n,
+                            int bs, const int32_t* blk_idx, const int32_t* n_blk_dev,
+                            int n_blk_cap, int flags, const uint8_t* token_mask, int64_t nb,
+                            const uint64_t* E, const uint64_t* F, const uint64_t* A_i,
+                            const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i,
+                            void* ws, size_t ws_bytes);
+
 /* ---- measurement aids (roofline probes; not part of the protocol) ------- */
 
 /* Launch-shape overrides for sweeps and for tests that must reach a particular

@@ -26,6 +26,7 @@ EXPORTS = [
     "comet_create", "comet_destroy", "comet_set_stream", "comet_last_error", "comet_version",
     "comet_workspace_bytes", "comet_mask_share", "comet_mask_share_gather", "comet_open",
     "comet_compact_mask", "comet_somm_share", "comet_simm_share",
+    "comet_components", "comet_somm_share_blocks", "comet_simm_share_masked",
     "comet_set_tuning", "comet_timing_begin", "comet_timing_end", "comet_probe_mfma_i8", "comet_probe_valu_mac64", "comet_probe_copy",
 ]
 
@@ -63,6 +64,11 @@ def load_library() -> ctypes.CDLL:
     share = [vp, i32, i64, i64, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz]
     lib.comet_somm_share.argtypes = share
     lib.comet_simm_share.argtypes = share
+    lib.comet_components.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.comet_somm_share_blocks.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, i32, vp, vp, i32,
+                                            vp, vp, vp, vp, vp, vp, vp, sz]
+    lib.comet_simm_share_masked.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, i32, i32, vp, i64,
+                                            vp, vp, vp, vp, vp, vp, vp, sz]
     lib.comet_probe_mfma_i8.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
     lib.comet_probe_valu_mac64.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
     lib.comet_probe_copy.argtypes = [vp, vp, vp, sz]
@@ -207,6 +213,63 @@ class Context:
                                               _ptr(n_blk_dev), n_blk_cap, flags, _ptr(e), _ptr(f),
                                               _ptr(a_i), _ptr(b_i), _ptr(c_i), _ptr(out), _ptr(ws),
                                               need))
+        return out
+
+    # ---- (4) Protocols 2 and 3 in general form ----
+    def components(self, mask):
+        """Connected components of the (token, block) graph.  Returns a dict of int32 tensors:
+        row_idx, row_comp [n_tok]; blk_idx, blk_comp [nb]; n_row, n_blk, n_comp [1]."""
+        if mask.dtype != torch.uint8 or not mask.is_cuda or not mask.is_contiguous() or mask.dim() != 2:
+            raise TypeError("mask must be a contiguous 2-D uint8 tensor on the GPU")
+        n_tok, nb = mask.shape
+        i32 = lambda n: torch.empty(max(n, 1), dtype=torch.int32, device=mask.device)
+        out = dict(row_idx=i32(n_tok), row_comp=i32(n_tok), n_row=i32(1), blk_idx=i32(nb),
+                   blk_comp=i32(nb), n_blk=i32(1), n_comp=i32(1))
+        self._sync_stream()
+        self._check(self.lib.comet_components(self.h, _ptr(mask), n_tok, nb, _ptr(out["row_idx"]),
+                                              _ptr(out["row_comp"]), _ptr(out["n_row"]),
+                                              _ptr(out["blk_idx"]), _ptr(out["blk_comp"]),
+                                              _ptr(out["n_blk"]), _ptr(out["n_comp"])))
+        return out
+
+    def somm_share_blocks(self, party, bs, blk_idx, blk_comp, n_blk_dev, n_blk_cap, row_comp, n_row_dev,
+                          e, f, a_i, b_i, c_i, b_full=True, out=None):
+        for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
+            _words(t, nm)
+        m, k = e.shape
+        n_full = b_i.shape[1] if b_full else 0
+        ld = n_blk_cap * bs
+        out = torch.empty((m, ld), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        need = workspace_bytes(OP_SOMM, m, k, ld, bs)
+        ws = self.workspace(need)
+        self._sync_stream()
+        self._check(self.lib.comet_somm_share_blocks(
+            self.h, party, m, k, n_full, bs, _ptr(blk_idx), _ptr(blk_comp), _ptr(n_blk_dev), n_blk_cap,
+            _ptr(row_comp), _ptr(n_row_dev), FULL_B if b_full else 0, _ptr(e), _ptr(f), _ptr(a_i),
+            _ptr(b_i), _ptr(c_i), _ptr(out), _ptr(ws), need))
+        return out
+
+    def simm_share_masked(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, token_mask, e, f, a_i, b_i, c_i,
+                          a_full=True, b_full=True, out=None):
+        for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
+            _words(t, nm)
+        if token_mask.dtype != torch.uint8 or not token_mask.is_cuda or not token_mask.is_contiguous():
+            raise TypeError("token_mask must be a contiguous uint8 tensor on the GPU")
+        m = e.shape[0]
+        n = f.shape[1]
+        if token_mask.dim() != 2 or token_mask.shape[0] != m:
+            raise ValueError("token_mask must have one row per row of E")
+        ld = n_blk_cap * bs
+        k_full = a_i.shape[1] if a_full else (b_i.shape[0] if b_full else 0)
+        out = torch.empty((m, n), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        need = workspace_bytes(OP_SIMM, m, ld, n, bs)
+        ws = self.workspace(need)
+        flags = (FULL_A if a_full else 0) | (FULL_B if b_full else 0)
+        self._sync_stream()
+        self._check(self.lib.comet_simm_share_masked(
+            self.h, party, m, k_full, n, bs, _ptr(blk_idx), _ptr(n_blk_dev), n_blk_cap, flags,
+            _ptr(token_mask), token_mask.shape[1], _ptr(e), _ptr(f), _ptr(a_i), _ptr(b_i), _ptr(c_i),
+            _ptr(out), _ptr(ws), need))
         return out
 
     # ---- probes ----

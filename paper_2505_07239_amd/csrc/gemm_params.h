@@ -30,6 +30,12 @@ struct GemmParams {
     int mpad;       // rows of xp, multiple of 128
     int chunk;      // contraction steps per scheduling slice, 1 .. MAX_SEG
     int ks_cap;     // contraction steps per half, ceil(kc_cap / 32)
+    // general forms of Protocols 2 and 3 (null when unused)
+    const int* row_comp;      // SOMM blocks: component number of each listed row
+    const int* blk_comp;      // SOMM blocks: component number of each listed block
+    const int* n_row_dev;     // SOMM blocks: number of listed rows (device), or null
+    const unsigned char* tmask;   // SIMM masked: m x tmask_nb bytes, token r uses block b
+    long tmask_nb;
 #ifdef EXP_TRACE
     u64* trace;
 #endif
@@ -42,6 +48,22 @@ static __device__ __forceinline__ int n_blocks(const GemmParams& p) {
         nb = d < 0 ? 0 : (d < nb ? d : nb);
     }
     return nb;
+}
+
+// rows that take part: all m, or the device-resident count of listed rows
+static __device__ __forceinline__ int n_rows(const GemmParams& p) {
+    int m = p.m;
+    if (p.n_row_dev) {
+        const int d = *p.n_row_dev;
+        m = d < 0 ? 0 : (d < m ? d : m);
+    }
+    return m;
+}
+
+// does token `row` use listed block `blk`?  (SIMM with per-token row sets)
+static __device__ __forceinline__ bool token_uses(const GemmParams& p, int row, int blk) {
+    const long b = p.blk_idx[blk];
+    return b >= 0 && b < p.tmask_nb && p.tmask[(long)row * p.tmask_nb + b] != 0;
 }
 
 // Start of block `blk` on the indexed axis, or -1 when the id does not fit the

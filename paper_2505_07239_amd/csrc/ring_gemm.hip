@@ -107,26 +107,32 @@ __device__ __host__ __forceinline__ size_t xp_group(int h, int s, int t, int g, 
 // one row, and the sixteen lanes that share a group write sixteen adjacent 16-byte units.
 __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
     const int nblk = n_blocks(p);
+    const int m_eff = n_rows(p);
     if (blockIdx.z == 2) {
-        // Z := C on the kept region (the GEMM adds its partial sums onto it)
+        // Z := C on the kept region (the GEMM adds its partial sums onto it); with result blocks
+        // (Protocol 2 in general form) Z := C on the blocks and zero between them
         const int n_eff = p.kind == KIND_SOMM ? nblk * p.bs : p.n_cap;
         const long stride = (long)gridDim.x * gridDim.y * GT;
         const long t0 = ((long)blockIdx.y * gridDim.x + blockIdx.x) * GT + threadIdx.x;
-        if (((n_eff | p.ldz) & 1) == 0) {
-            // 16-byte accesses (the operands are 16-byte aligned and every row starts on a pair)
+        if (((n_eff | p.ldz | p.bs) & 1) == 0 || (!p.row_comp && ((n_eff | p.ldz) & 1) == 0)) {
+            // 16-byte accesses (the operands are 16-byte aligned, every row starts on a pair, and
+            // a pair never straddles two blocks when that matters)
             typedef u64 u64x2 __attribute__((ext_vector_type(2)));
             const int half = n_eff >> 1;
-            const long total = (long)p.m * half;
+            const long total = (long)m_eff * half;
             for (long i = t0; i < total; i += stride) {
                 const long r = i / half, c = (i - r * half) * 2;
-                *reinterpret_cast<u64x2*>(p.Z + r * p.ldz + c) =
-                    *reinterpret_cast<const u64x2*>(p.C + r * p.ldz + c);
+                u64x2 v = *reinterpret_cast<const u64x2*>(p.C + r * p.ldz + c);
+                if (p.row_comp && p.row_comp[r] != p.blk_comp[c / p.bs]) v = u64x2{0, 0};
+                *reinterpret_cast<u64x2*>(p.Z + r * p.ldz + c) = v;
             }
         } else {
-            const long total = (long)p.m * n_eff;
+            const long total = (long)m_eff * n_eff;
             for (long i = t0; i < total; i += stride) {
                 const long r = i / n_eff, c = i - r * n_eff;
-                p.Z[r * p.ldz + c] = p.C[r * p.ldz + c];
+                u64 v = p.C[r * p.ldz + c];
+                if (p.row_comp && p.row_comp[r] != p.blk_comp[c / p.bs]) v = 0;
+                p.Z[r * p.ldz + c] = v;
             }
         }
         return;
@@ -143,9 +149,11 @@ __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
     for (int j = 0; j < 16; ++j) w[j] = 0;
     // fast path: the sixteen words are inside the contraction, 16-byte aligned, and (when A_i is
     // indexed) inside one block -- eight 16-byte loads per operand
-    const bool wide = row < p.m && k0 + 16 <= kc && (p.lde & 1) == 0 && (p.lda & 1) == 0 &&
-                      (!p.a_full || (p.bs & 15) == 0);
-    if (wide) {
+    const bool wide = row < m_eff && k0 + 16 <= kc && (p.lde & 1) == 0 && (p.lda & 1) == 0 &&
+                      ((!p.a_full && !p.tmask) || (p.bs & 15) == 0);
+    if (wide && p.tmask && !token_uses(p, row, k0 / p.bs)) {
+        // the token does not use this block: its sixteen entries take no part (w stays zero)
+    } else if (wide) {
         const u64* e = p.E + (size_t)row * p.lde + k0;
         u64x2 ev[8];
 #pragma unroll
@@ -168,26 +176,23 @@ __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
                 w[2 * j + 1] = av.y + (p.party ? ev[j].y : 0ull);
             }
         }
-    } else if (row < p.m && k0 < kc) {
-        int blk = 0, off = 0;
-        if (h == 1 && p.a_full) { blk = k0 / p.bs; off = k0 - blk * p.bs; }
+    } else if (row < m_eff && k0 < kc) {
         for (int j = 0; j < 16; ++j) {
             const int k = k0 + j;
-            if (k < kc) {
-                const u64 e = p.E[(size_t)row * p.lde + k];
-                u64 x = e;
-                if (h == 1) {
-                    long col = k;
-                    if (p.a_full) {
-                        while (off >= p.bs) { off -= p.bs; ++blk; }
-                        const long st = block_start(p, blk);
-                        col = (st < 0 ? 0 : st) + off;
-                        ++off;
-                    }
-                    x = p.A[(size_t)row * p.lda + col] + (p.party ? e : 0ull);
+            if (k >= kc) break;
+            const int blk = k / p.bs;
+            if (p.tmask && !token_uses(p, row, blk)) continue;
+            const u64 e = p.E[(size_t)row * p.lde + k];
+            u64 x = e;
+            if (h == 1) {
+                long col = k;
+                if (p.a_full) {
+                    const long st = block_start(p, blk);
+                    col = (st < 0 ? 0 : st) + (k - blk * p.bs);
                 }
-                w[j] = x;
+                x = p.A[(size_t)row * p.lda + col] + (p.party ? e : 0ull);
             }
+            w[j] = x;
         }
     }
     u64 plane[2][8];
@@ -195,7 +200,7 @@ __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
     for (int o = 0; o < 2; ++o) {
         u64 v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = (row < p.m && k0 + 8 * o + j < kc) ? to_digits(w[8 * o + j]) : 0ull;
+        for (int j = 0; j < 8; ++j) v[j] = (row < m_eff && k0 + 8 * o + j < kc) ? to_digits(w[8 * o + j]) : 0ull;
         digits_to_planes(v, plane[o]);
     }
     const int s = half16 >> 1, g = half16 & 1;
@@ -573,7 +578,8 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
     const int kc = KIND == KIND_SOMM ? p.kc_cap : nblk * p.bs;
     const int KS = (kc + KSTEP - 1) / KSTEP;
     const int KT = 2 * KS;
-    const int tiles_m = (p.m + T::BM - 1) / T::BM;
+    const int m_eff = n_rows(p);
+    const int tiles_m = (m_eff + T::BM - 1) / T::BM;
     const int tiles_n = (n_eff + T::BN - 1) / T::BN;
     const long units = (long)tiles_m * tiles_n * KT;
     if (units == 0) return;
@@ -615,6 +621,17 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
         if (len > u_end - u) len = u_end - u;
         const int L = (int)len;
         const int tm = tile % tiles_m, tn = tile / tiles_m;
+
+        if (p.row_comp) {
+            // Result blocks (Protocol 2 in general form): rows and columns are listed component
+            // by component, so a tile touches a block exactly when the component ranges of its
+            // rows and of its columns overlap; the other tiles are not computed at all.
+            const int r_hi = (tm + 1) * T::BM < m_eff ? (tm + 1) * T::BM - 1 : m_eff - 1;
+            const int c_hi = (tn + 1) * T::BN < n_eff ? (tn + 1) * T::BN - 1 : n_eff - 1;
+            const int rc0 = p.row_comp[tm * T::BM], rc1 = p.row_comp[r_hi];
+            const int cc0 = p.blk_comp[tn * T::BN / p.bs], cc1 = p.blk_comp[c_hi / p.bs];
+            if (rc1 < cc0 || cc1 < rc0) { u += len; continue; }
+        }
 
         ld.setup(p, tm, tn, n_eff);
         v16i acc[WM][WN][8];
@@ -663,13 +680,16 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
 #pragma unroll
             for (int j = 0; j < WN; ++j) {
                 const int col = tn * T::BN + (wn * WN + j) * 32 + r;
+                const int ccomp = (p.row_comp && col < n_eff) ? p.blk_comp[col / p.bs] : 0;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int row = tm * T::BM + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
                     u64 z = 0;
 #pragma unroll
                     for (int s = 0; s < 8; ++s) z += (u64)(long long)acc[i][j][s][e] << (8 * s);
-                    if (row < p.m && col < n_eff) atomicAdd(p.Z + (size_t)row * p.ldz + col, z);
+                    bool live = row < m_eff && col < n_eff;
+                    if (live && p.row_comp) live = p.row_comp[row] == ccomp;   // on a result block
+                    if (live) atomicAdd(p.Z + (size_t)row * p.ldz + col, z);
                 }
             }
         u += len;
@@ -783,6 +803,57 @@ int check_common(comet_ctx* ctx, const char* what, int party, int64_t m, int bs,
     return COMET_OK;
 }
 
+int somm_params(comet_ctx* ctx, const char* what, GemmParams& p, int party, int64_t m, int64_t k,
+                int64_t n_full, int bs, const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap,
+                int flags, const uint64_t* E, const uint64_t* F, const uint64_t* A_i,
+                const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i) {
+    const void* ptrs[] = {E, F, A_i, B_i, C_i, Z_i};
+    int rc = check_common(ctx, what, party, m, bs, n_blk_cap, flags, ptrs, 6, blk_idx);
+    if (rc) return rc;
+    if (k < 1 || n_full < 0) return comet_fail(ctx, COMET_EINVAL, "%s: bad size", what);
+    if (flags & COMET_FULL_A) return comet_fail(ctx, COMET_EINVAL, "%s: A_i is never indexed in SOMM", what);
+    if (k > COMET_DIM_MAX || n_full > COMET_DIM_MAX) return comet_fail(ctx, COMET_ECAP, "%s: dimension beyond 2^24", what);
+    const int64_t ld = (int64_t)n_blk_cap * bs;
+    if ((flags & COMET_FULL_B) && ld > n_full)
+        return comet_fail(ctx, COMET_EINVAL, "%s: n_blk_cap * bs exceeds n_full", what);
+    if (k * ((flags & COMET_FULL_B) ? n_full : ld) >= (1ll << 31) || k * ld >= (1ll << 31))
+        return comet_fail(ctx, COMET_ECAP, "%s: a weight-side operand holds 2^31 words or more", what);
+    p.kind = KIND_SOMM; p.party = party; p.m = (int)m; p.kc_cap = (int)k; p.n_cap = (int)ld;
+    p.bs = bs; p.n_blk_cap = n_blk_cap; p.blk_idx = blk_idx; p.n_blk_dev = n_blk_dev;
+    p.full_extent = (int)n_full;
+    p.E = (const u64*)E; p.lde = k;
+    p.A = (const u64*)A_i; p.lda = k; p.a_full = 0;
+    p.B = (const u64*)B_i; p.b_full = (flags & COMET_FULL_B) ? 1 : 0; p.ldb = p.b_full ? n_full : ld;
+    p.F = (const u64*)F; p.ldf = ld;
+    p.C = (const u64*)C_i; p.Z = (u64*)Z_i; p.ldz = ld;
+    return COMET_OK;
+}
+
+int simm_params(comet_ctx* ctx, const char* what, GemmParams& p, int party, int64_t m, int64_t k_full,
+                int64_t n, int bs, const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap,
+                int flags, const uint64_t* E, const uint64_t* F, const uint64_t* A_i,
+                const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i) {
+    const void* ptrs[] = {E, F, A_i, B_i, C_i, Z_i};
+    int rc = check_common(ctx, what, party, m, bs, n_blk_cap, flags, ptrs, 6, blk_idx);
+    if (rc) return rc;
+    if (n < 1 || k_full < 0) return comet_fail(ctx, COMET_EINVAL, "%s: bad size", what);
+    if (n > COMET_DIM_MAX || k_full > COMET_DIM_MAX) return comet_fail(ctx, COMET_ECAP, "%s: dimension beyond 2^24", what);
+    const int64_t ld = (int64_t)n_blk_cap * bs;
+    if ((flags & (COMET_FULL_A | COMET_FULL_B)) && ld > k_full)
+        return comet_fail(ctx, COMET_EINVAL, "%s: n_blk_cap * bs exceeds k_full", what);
+    if (((flags & COMET_FULL_B) ? k_full : ld) * n >= (1ll << 31))
+        return comet_fail(ctx, COMET_ECAP, "%s: a weight-side operand holds 2^31 words or more", what);
+    p.kind = KIND_SIMM; p.party = party; p.m = (int)m; p.kc_cap = (int)ld; p.n_cap = (int)n;
+    p.bs = bs; p.n_blk_cap = n_blk_cap; p.blk_idx = blk_idx; p.n_blk_dev = n_blk_dev;
+    p.full_extent = (int)k_full;
+    p.E = (const u64*)E; p.lde = ld;
+    p.A = (const u64*)A_i; p.a_full = (flags & COMET_FULL_A) ? 1 : 0; p.lda = p.a_full ? k_full : ld;
+    p.B = (const u64*)B_i; p.b_full = (flags & COMET_FULL_B) ? 1 : 0; p.ldb = n;
+    p.F = (const u64*)F; p.ldf = n;
+    p.C = (const u64*)C_i; p.Z = (u64*)Z_i; p.ldz = n;
+    return COMET_OK;
+}
+
 }  // namespace
 
 size_t comet_gemm_workspace_bytes(int64_t m, int64_t kc_cap) { return gemm_ws_bytes(m, kc_cap); }
@@ -796,26 +867,28 @@ int comet_somm_share(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_
                      size_t ws_bytes) {
     const char* what = "comet_somm_share";
     COMET_CHECK_CTX(ctx);
-    const void* ptrs[] = {E, F, A_i, B_i, C_i, Z_i};
-    int rc = check_common(ctx, what, party, m, bs, n_blk_cap, flags, ptrs, 6, blk_idx);
-    if (rc) return rc;
-    if (k < 1 || n_full < 0) return comet_fail(ctx, COMET_EINVAL, "%s: bad size", what);
-    if (flags & COMET_FULL_A) return comet_fail(ctx, COMET_EINVAL, "%s: A_i is never indexed in SOMM", what);
-    if (k > COMET_DIM_MAX || n_full > COMET_DIM_MAX) return comet_fail(ctx, COMET_ECAP, "%s: dimension beyond 2^24", what);
-    const int64_t ld = (int64_t)n_blk_cap * bs;
-    if ((flags & COMET_FULL_B) && ld > n_full)
-        return comet_fail(ctx, COMET_EINVAL, "%s: n_blk_cap * bs exceeds n_full", what);
-    if (k * ((flags & COMET_FULL_B) ? n_full : ld) >= (1ll << 31) || k * ld >= (1ll << 31))
-        return comet_fail(ctx, COMET_ECAP, "%s: a weight-side operand holds 2^31 words or more", what);
     GemmParams p = {};
-    p.kind = KIND_SOMM; p.party = party; p.m = (int)m; p.kc_cap = (int)k; p.n_cap = (int)ld;
-    p.bs = bs; p.n_blk_cap = n_blk_cap; p.blk_idx = blk_idx; p.n_blk_dev = n_blk_dev;
-    p.full_extent = (int)n_full;
-    p.E = (const u64*)E; p.lde = k;
-    p.A = (const u64*)A_i; p.lda = k; p.a_full = 0;
-    p.B = (const u64*)B_i; p.b_full = (flags & COMET_FULL_B) ? 1 : 0; p.ldb = p.b_full ? n_full : ld;
-    p.F = (const u64*)F; p.ldf = ld;
-    p.C = (const u64*)C_i; p.Z = (u64*)Z_i; p.ldz = ld;
+    const int rc = somm_params(ctx, what, p, party, m, k, n_full, bs, blk_idx, n_blk_dev, n_blk_cap, flags,
+                               E, F, A_i, B_i, C_i, Z_i);
+    if (rc) return rc;
+    return run_share(ctx, what, p, ws, ws_bytes);
+}
+
+int comet_somm_share_blocks(comet_ctx* ctx, int party, int64_t m_cap, int64_t k, int64_t n_full,
+                            int bs, const int32_t* blk_idx, const int32_t* blk_comp,
+                            const int32_t* n_blk_dev, int n_blk_cap, const int32_t* row_comp,
+                            const int32_t* n_row_dev, int flags, const uint64_t* E,
+                            const uint64_t* F, const uint64_t* A_i, const uint64_t* B_i,
+                            const uint64_t* C_i, uint64_t* Z_i, void* ws, size_t ws_bytes) {
+    const char* what = "comet_somm_share_blocks";
+    COMET_CHECK_CTX(ctx);
+    if (!blk_idx || !blk_comp || !row_comp)
+        return comet_fail(ctx, COMET_EINVAL, "%s: blk_idx, blk_comp and row_comp are required", what);
+    GemmParams p = {};
+    const int rc = somm_params(ctx, what, p, party, m_cap, k, n_full, bs, blk_idx, n_blk_dev, n_blk_cap,
+                               flags, E, F, A_i, B_i, C_i, Z_i);
+    if (rc) return rc;
+    p.row_comp = row_comp; p.blk_comp = blk_comp; p.n_row_dev = n_row_dev;
     return run_share(ctx, what, p, ws, ws_bytes);
 }
 
@@ -826,25 +899,29 @@ int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64
                      size_t ws_bytes) {
     const char* what = "comet_simm_share";
     COMET_CHECK_CTX(ctx);
-    const void* ptrs[] = {E, F, A_i, B_i, C_i, Z_i};
-    int rc = check_common(ctx, what, party, m, bs, n_blk_cap, flags, ptrs, 6, blk_idx);
-    if (rc) return rc;
-    if (n < 1 || k_full < 0) return comet_fail(ctx, COMET_EINVAL, "%s: bad size", what);
-    if (n > COMET_DIM_MAX || k_full > COMET_DIM_MAX) return comet_fail(ctx, COMET_ECAP, "%s: dimension beyond 2^24", what);
-    const int64_t ld = (int64_t)n_blk_cap * bs;
-    if ((flags & (COMET_FULL_A | COMET_FULL_B)) && ld > k_full)
-        return comet_fail(ctx, COMET_EINVAL, "%s: n_blk_cap * bs exceeds k_full", what);
-    if (((flags & COMET_FULL_B) ? k_full : ld) * n >= (1ll << 31))
-        return comet_fail(ctx, COMET_ECAP, "%s: a weight-side operand holds 2^31 words or more", what);
     GemmParams p = {};
-    p.kind = KIND_SIMM; p.party = party; p.m = (int)m; p.kc_cap = (int)ld; p.n_cap = (int)n;
-    p.bs = bs; p.n_blk_cap = n_blk_cap; p.blk_idx = blk_idx; p.n_blk_dev = n_blk_dev;
-    p.full_extent = (int)k_full;
-    p.E = (const u64*)E; p.lde = ld;
-    p.A = (const u64*)A_i; p.a_full = (flags & COMET_FULL_A) ? 1 : 0; p.lda = p.a_full ? k_full : ld;
-    p.B = (const u64*)B_i; p.b_full = (flags & COMET_FULL_B) ? 1 : 0; p.ldb = n;
-    p.F = (const u64*)F; p.ldf = n;
-    p.C = (const u64*)C_i; p.Z = (u64*)Z_i; p.ldz = n;
+    const int rc = simm_params(ctx, what, p, party, m, k_full, n, bs, blk_idx, n_blk_dev, n_blk_cap, flags,
+                               E, F, A_i, B_i, C_i, Z_i);
+    if (rc) return rc;
+    return run_share(ctx, what, p, ws, ws_bytes);
+}
+
+int comet_simm_share_masked(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64_t n,
+                            int bs, const int32_t* blk_idx, const int32_t* n_blk_dev,
+                            int n_blk_cap, int flags, const uint8_t* token_mask, int64_t nb,
+                            const uint64_t* E, const uint64_t* F, const uint64_t* A_i,
+                            const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i, void* ws,
+                            size_t ws_bytes) {
+    const char* what = "comet_simm_share_masked";
+    COMET_CHECK_CTX(ctx);
+    if (!token_mask || !blk_idx)
+        return comet_fail(ctx, COMET_EINVAL, "%s: token_mask and blk_idx are required", what);
+    if (nb < 1 || nb > COMET_DIM_MAX) return comet_fail(ctx, COMET_EINVAL, "%s: bad nb", what);
+    GemmParams p = {};
+    const int rc = simm_params(ctx, what, p, party, m, k_full, n, bs, blk_idx, n_blk_dev, n_blk_cap, flags,
+                               E, F, A_i, B_i, C_i, Z_i);
+    if (rc) return rc;
+    p.tmask = token_mask; p.tmask_nb = nb;
     return run_share(ctx, what, p, ws, ws_bytes);
 }
 

@@ -36,14 +36,18 @@ typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 // blockIdx.y == 1: Z := C on the kept region.
 __global__ __launch_bounds__(ST) void skinny_prep_kernel(GemmParams p, u64* xs, int MR) {
     const int nblk = n_blocks(p);
+    const int m_eff = n_rows(p);
     const long stride = (long)gridDim.x * ST;
     const long t0 = (long)blockIdx.x * ST + threadIdx.x;
     if (blockIdx.y == 1) {
+        // with result blocks (Protocol 2 in general form): C on the blocks, zero between them
         const int n_eff = p.kind == KIND_SOMM ? nblk * p.bs : p.n_cap;
-        const long total = (long)p.m * n_eff;
+        const long total = (long)m_eff * n_eff;
         for (long i = t0; i < total; i += stride) {
             const long r = i / n_eff, c = i - r * n_eff;
-            p.Z[r * p.ldz + c] = p.C[r * p.ldz + c];
+            u64 v = p.C[r * p.ldz + c];
+            if (p.row_comp && p.row_comp[r] != p.blk_comp[c / p.bs]) v = 0;
+            p.Z[r * p.ldz + c] = v;
         }
         return;
     }
@@ -54,7 +58,8 @@ __global__ __launch_bounds__(ST) void skinny_prep_kernel(GemmParams p, u64* xs, 
         const int r = (int)((i / kc) % MR);
         const int h = (int)(i / ((long)kc * MR));
         u64 x = 0;
-        if (r < p.m) {
+        // entries the token does not use take no part (Protocol 3 with per-token row sets)
+        if (r < m_eff && (!p.tmask || token_uses(p, r, k / p.bs))) {
             const u64 e = p.E[(size_t)r * p.lde + k];
             x = e;
             if (h == 1) {
@@ -116,6 +121,7 @@ __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64
     const int nblk = n_blocks(p);
     const int n_eff = KIND == KIND_SOMM ? nblk * p.bs : p.n_cap;
     const int kc = KIND == KIND_SOMM ? p.kc_cap : nblk * p.bs;
+    const int m_eff = n_rows(p);
     const int tile0 = blockIdx.x * 64 * VEC;
     if (tile0 >= n_eff || kc <= 0) return;                    // uniform over the workgroup
     const int lane = threadIdx.x & 63;
@@ -189,7 +195,9 @@ __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64
 #pragma unroll
             for (int wv = 0; wv < SW; ++wv) s += red[wv][r][c];
             const int row = r0 + r, oc = tile0 + c;
-            if (row < p.m && oc < n_eff) atomicAdd(p.Z + (size_t)row * p.ldz + oc, s);
+            bool live = row < m_eff && oc < n_eff;
+            if (live && p.row_comp) live = p.row_comp[row] == p.blk_comp[oc / p.bs];   // on a result block
+            if (live) atomicAdd(p.Z + (size_t)row * p.ldz + oc, s);
         }
     }
 }

@@ -1,0 +1,235 @@
+"""GPU parity of Protocols 2 and 3 in general form (per-token sparsity at block granularity):
+the component search, the result-block share of Protocol 2 and the per-token row sets of
+Protocol 3, element by element against the oracle's one-pass forms (which are pinned against
+the literal protocols in the CPU suite)."""
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle as co                                   # noqa: E402
+from oracle import protocols                          # noqa: E402
+from workloads import configs, masks, rng             # noqa: E402
+
+
+def say(msg):
+    print("[gpu-general] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2505_07239_amd as comet
+    c = comet.Context(0)
+    yield c
+    c.close()
+
+
+def up(a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int64)).cuda()
+
+
+def down(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+def u64(seed, stream, *shape):
+    return rng.uniform_u64(seed, stream, int(np.prod(shape))).reshape(shape)
+
+
+def grouped_mask(seed, n_tok, nb, groups, per_tok):
+    """Tokens fall into ``groups`` clusters that draw their blocks from disjoint ranges (several
+    components), plus a few tokens without any block."""
+    r = rng.uniform_u64(seed, 60, n_tok * (per_tok + 1)).reshape(n_tok, per_tok + 1)
+    m = np.zeros((n_tok, nb), np.uint8)
+    span = nb // groups
+    for t in range(n_tok):
+        g = int(r[t, 0] % np.uint64(groups + 1))
+        if g == groups:
+            continue                              # this token predicts nothing
+        for j in range(per_tok):
+            m[t, g * span + int(r[t, 1 + j] % np.uint64(span))] = 1
+    return m
+
+
+def flat_components(mask_blk):
+    comps = protocols.components(mask_blk)
+    row_idx = np.concatenate([r for r, _ in comps]) if comps else np.zeros(0, np.int32)
+    blk_idx = np.concatenate([c for _, c in comps]) if comps else np.zeros(0, np.int32)
+    row_comp = np.concatenate([np.full(len(r), t, np.int32) for t, (r, _) in enumerate(comps)]) \
+        if comps else np.zeros(0, np.int32)
+    blk_comp = np.concatenate([np.full(len(c), t, np.int32) for t, (_, c) in enumerate(comps)]) \
+        if comps else np.zeros(0, np.int32)
+    return comps, row_idx.astype(np.int32), row_comp, blk_idx.astype(np.int32), blk_comp
+
+
+def check_components(ctx, mask_blk):
+    out = ctx.components(torch.from_numpy(mask_blk).cuda())
+    torch.cuda.synchronize()
+    comps, row_idx, row_comp, blk_idx, blk_comp = flat_components(mask_blk)
+    assert int(out["n_comp"].item()) == len(comps)
+    assert int(out["n_row"].item()) == len(row_idx) and int(out["n_blk"].item()) == len(blk_idx)
+    assert np.array_equal(out["row_idx"][:len(row_idx)].cpu().numpy(), row_idx)
+    assert np.array_equal(out["row_comp"][:len(row_idx)].cpu().numpy(), row_comp)
+    assert np.array_equal(out["blk_idx"][:len(blk_idx)].cpu().numpy(), blk_idx)
+    assert np.array_equal(out["blk_comp"][:len(blk_idx)].cpu().numpy(), blk_comp)
+    return out
+
+
+@pytest.mark.parametrize("n_tok,nb,groups,per_tok", [(1, 1, 1, 1), (8, 216, 3, 5), (40, 96, 4, 2),
+                                                     (200, 344, 6, 3), (512, 344, 1, 8), (1024, 500, 9, 2),
+                                                     (33, 4096, 7, 4), (5, 37, 5, 1)])
+def test_components_match_depth_first_search(ctx, n_tok, nb, groups, per_tok):
+    say("components n_tok=%d nb=%d groups=%d" % (n_tok, nb, groups))
+    check_components(ctx, grouped_mask(70 + n_tok, n_tok, nb, groups, per_tok))
+
+
+def test_components_chain_needs_many_rounds(ctx):
+    """A path token 0 - block 0 - token 1 - block 1 - ... is the slowest case for label
+    propagation (one hop per round)."""
+    n = 300
+    m = np.zeros((n, n), np.uint8)
+    for t in range(n):
+        m[t, t] = 1
+        if t + 1 < n:
+            m[t + 1, t] = 1
+    say("components chain of %d" % n)
+    out = check_components(ctx, m[::-1].copy())      # reversed, so that labels travel the whole way
+    assert int(out["n_comp"].item()) == 1
+
+
+def test_components_degenerate_and_config_masks(ctx):
+    say("components degenerate")
+    check_components(ctx, np.zeros((7, 50), np.uint8))
+    check_components(ctx, np.ones((9, 70), np.uint8))
+    check_components(ctx, np.eye(64, dtype=np.uint8))
+    for cid in (1, 2, 4):
+        cfg = configs.config(cid)
+        mk = configs.token_masks(cfg)
+        if mk.shape[0] == 1:                          # one mask for the whole batch
+            mk = np.repeat(mk, 4, axis=0)
+        check_components(ctx, np.ascontiguousarray(mk))
+
+
+def test_components_rejects_oversize(ctx):
+    import paper_2505_07239_amd as comet
+    with pytest.raises(comet.CometError) as ei:
+        ctx.components(torch.zeros((1025, 8), dtype=torch.uint8, device="cuda"))
+    assert ei.value.code == -3      # COMET_ECAP
+
+
+# ---------------------------------------------------------------------------
+# Protocol 3 with per-token row sets
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("m,nb,bs,n,groups,per_tok", [(3, 12, 8, 40, 2, 2), (8, 24, 16, 96, 3, 3),
+                                                      (13, 10, 3, 33, 2, 2), (40, 20, 32, 70, 4, 2),
+                                                      (130, 16, 16, 200, 3, 4), (70, 9, 5, 64, 1, 3)])
+@pytest.mark.parametrize("compact_triples", [False, True])
+def test_simm_per_token_row_sets(ctx, m, nb, bs, n, groups, per_tok, compact_triples):
+    seed = 300 + m
+    k = nb * bs
+    mask_blk = grouped_mask(seed, m, nb, groups, per_tok)
+    s = np.repeat(mask_blk, bs, axis=1)
+    x_sh, y_sh = (u64(seed, 1, m, k), u64(seed, 2, m, k)), (u64(seed, 3, k, n), u64(seed, 4, k, n))
+    gen = protocols.simm_general(x_sh, y_sh, s, u64(seed, 5, m, k), u64(seed, 6, k, n), u64(seed, 7, m, k),
+                                 u64(seed, 8, k, n), [u64(seed, 100 + j, m, n) for j in range(k)])
+    idx_np = co.compact_mask(mask_blk)
+    t = len(idx_np)
+    idx, n_dev = ctx.compact_mask(torch.from_numpy(mask_blk).cuda())
+    # what is never exchanged may hold anything
+    e_sent = np.where(s != 0, gen.e, u64(seed, 50, m, k))
+    e_c, f_c = co.index_cols(e_sent, idx_np, bs), co.index_rows(gen.f, idx_np, bs)
+    tm = torch.from_numpy(mask_blk).cuda()
+    for party in (0, 1):
+        say("simm row sets m=%d nb=%d bs=%d n=%d party %d compact=%s" % (m, nb, bs, n, party, compact_triples))
+        if compact_triples:
+            a_arg, b_arg = co.index_cols(gen.a[party], idx_np, bs), co.index_rows(gen.b[party], idx_np, bs)
+        else:
+            a_arg, b_arg = gen.a[party], gen.b[party]
+        z = ctx.simm_share_masked(party, bs, idx, n_dev, t, tm, up(e_c), up(f_c), up(a_arg), up(b_arg),
+                                  up(gen.c[party]), a_full=not compact_triples, b_full=not compact_triples)
+        torch.cuda.synchronize()
+        assert np.array_equal(down(z), gen.z[party])
+
+
+# ---------------------------------------------------------------------------
+# Protocol 2 with result blocks
+# ---------------------------------------------------------------------------
+
+def _somm_blocks_case(ctx, seed, m, k, nb, bs, groups, per_tok, spare_rows=0, spare_blocks=0, b_full=True):
+    n_full = nb * bs
+    mask_blk = grouped_mask(seed, m, nb, groups, per_tok)
+    s = np.repeat(mask_blk, bs, axis=1)
+    x_sh, y_sh = (u64(seed, 1, m, k), u64(seed, 2, m, k)), (u64(seed, 3, k, n_full), u64(seed, 4, k, n_full))
+    gen = protocols.somm_general(x_sh, y_sh, s, u64(seed, 5, m, k), u64(seed, 6, k, n_full),
+                                 u64(seed, 7, m, k), u64(seed, 8, k, n_full), u64(seed, 9, m, n_full))
+    comp = check_components(ctx, mask_blk)
+    comps, row_idx, row_comp, blk_idx, blk_comp = flat_components(mask_blk)
+    n_row, n_blk = len(row_idx), len(blk_idx)
+    m_cap, cap = n_row + spare_rows, n_blk + spare_blocks
+    ld = cap * bs
+    cols = (blk_idx.astype(np.int64)[:, None] * bs + np.arange(bs)[None, :]).ravel()
+
+    def rows_padded(a):                       # listed rows first, then spare rows of junk
+        out = u64(seed, 77, m_cap, a.shape[1])
+        out[:n_row] = a[row_idx]
+        return out
+
+    def cols_padded(a):
+        out = u64(seed, 78, a.shape[0], ld)
+        out[:, :n_blk * bs] = a[:, cols]
+        return out
+
+    e_p, f_c = rows_padded(gen.e), cols_padded(gen.f)
+    got = []
+    for party in (0, 1):
+        a_p = rows_padded(gen.a[party])
+        c_p = cols_padded(rows_padded(gen.c[party]))
+        b_arg = gen.b[party] if b_full else cols_padded(gen.b[party])
+        z = ctx.somm_share_blocks(party, bs, comp["blk_idx"], comp["blk_comp"], comp["n_blk"], cap,
+                                  comp["row_comp"], comp["n_row"], up(e_p), up(f_c), up(a_p), up(b_arg),
+                                  up(c_p), b_full=b_full)
+        torch.cuda.synchronize()
+        zz = down(z)
+        want = gen.z[party][np.ix_(row_idx, cols)] if n_row and n_blk else np.zeros((n_row, n_blk * bs), np.uint64)
+        assert np.array_equal(zz[:n_row, :n_blk * bs], want), "party %d" % party
+        got.append(zz[:n_row, :n_blk * bs])
+    if n_row and n_blk:
+        # merged result: X Y on the result blocks, zero between them
+        xy = co.ring_matmul(co.reconstruct(*x_sh), co.reconstruct(*y_sh))[np.ix_(row_idx, cols)]
+        on = row_comp[:, None] == np.repeat(blk_comp, bs)[None, :]
+        assert np.array_equal(got[0] + got[1], np.where(on, xy, np.uint64(0)))
+    return len(comps)
+
+
+@pytest.mark.parametrize("m,k,nb,bs,groups,per_tok", [(8, 64, 24, 16, 3, 3), (5, 40, 12, 8, 2, 2),
+                                                      (16, 96, 10, 3, 2, 2), (40, 70, 20, 32, 4, 2),
+                                                      (200, 130, 16, 16, 3, 3), (300, 64, 40, 32, 5, 2),
+                                                      (70, 33, 9, 5, 1, 3)])
+def test_somm_result_blocks(ctx, m, k, nb, bs, groups, per_tok):
+    say("somm blocks m=%d k=%d nb=%d bs=%d groups=%d" % (m, k, nb, bs, groups))
+    n_comp = _somm_blocks_case(ctx, 400 + m, m, k, nb, bs, groups, per_tok)
+    assert n_comp >= 1
+
+
+@pytest.mark.parametrize("m", [6, 150])
+def test_somm_result_blocks_spare_capacity_and_compact_triples(ctx, m):
+    say("somm blocks spare capacity m=%d" % m)
+    _somm_blocks_case(ctx, 450 + m, m, 48, 14, 16, 3, 2, spare_rows=5, spare_blocks=2, b_full=False)
+
+
+def test_somm_result_blocks_matrix_path_for_few_rows(ctx):
+    """m <= 16 with the vector-ALU path switched off: the matrix-core kernel's 32-row tile."""
+    import paper_2505_07239_amd as comet
+    ctx.set_tuning(comet.TUNE_SKINNY, 1)
+    try:
+        _somm_blocks_case(ctx, 470, 12, 64, 18, 16, 3, 2)
+    finally:
+        ctx.set_tuning(comet.TUNE_SKINNY, 0)
