@@ -174,6 +174,55 @@ def cpu_baseline(layer, budget_s=20.0):
             "matches_gpu": bool(ok)}
 
 
+def general_forms(ctx, timed):
+    """Protocols 2 and 3 with per-token masks on a batch of four unrelated requests (256 tokens,
+    LLaMA-7B gate projection, 15 % of the blocks per token): component search, the share
+    restricted to the result blocks against the same call on the union of all masks, and the
+    down projection with per-token row sets."""
+    import numpy as np
+    import torch
+    from workloads import masks, rng
+    m, k, nb, bs, groups = 256, 4096, 344, 32, 4
+    dev = torch.device("cuda:0")
+    mk = masks.grouped_token_masks(rng.BASE_SEED, 9000, m, nb, groups, 0.15)
+    tm = torch.from_numpy(mk).to(dev)
+    comp = ctx.components(tm)
+    torch.cuda.synchronize()
+    n_row, n_blk, n_comp = (int(comp[q].item()) for q in ("n_row", "n_blk", "n_comp"))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(77)
+    words = lambda *shape: torch.randint(-(2 ** 63), 2 ** 63 - 1, shape, dtype=torch.int64, device=dev,
+                                         generator=gen)
+    n_act = n_blk * bs
+    e, a, f, b, c = words(m, k), words(m, k), words(k, n_act), words(k, nb * bs), words(m, n_act)
+    z = torch.empty_like(c)
+    out = {"general_n_components": n_comp, "general_rows": n_row, "general_blocks": n_blk}
+    out["components_us"] = timed(lambda: ctx.components(tm), reps=20) * 1e6
+    t_blocks = timed(lambda: ctx.somm_share_blocks(1, bs, comp["blk_idx"], comp["blk_comp"], comp["n_blk"],
+                                                   n_blk, comp["row_comp"], comp["n_row"], e, f, a, b, c,
+                                                   out=z), reps=10)
+    t_union = timed(lambda: ctx.somm_share(1, bs, comp["blk_idx"], comp["n_blk"], n_blk, e, f, a, b, c,
+                                           out=z), reps=10)
+    out["somm_result_blocks_us"] = t_blocks * 1e6
+    out["somm_union_of_masks_us"] = t_union * 1e6
+    # ring MACs on the result blocks only: sum over components of rows x columns x 2k
+    rc = comp["row_comp"][:n_row].cpu().numpy()
+    bc = comp["blk_comp"][:n_blk].cpu().numpy()
+    macs = sum(int((rc == q).sum()) * int((bc == q).sum()) * bs for q in range(n_comp)) * 2 * k
+    out["somm_result_blocks_Gops"] = 2.0 * macs / t_blocks / 1e9
+    # down projection with per-token row sets (same masks, union of the blocks contracted)
+    idx, n_dev = ctx.compact_mask(tm)
+    kc = n_blk * bs
+    e2, a2, f2, b2, c2 = words(m, kc), words(m, nb * bs), words(kc, k), words(nb * bs, k), words(m, k)
+    z2 = torch.empty_like(c2)
+    t_rows = timed(lambda: ctx.simm_share_masked(1, bs, idx, n_dev, n_blk, tm, e2, f2, a2, b2, c2, out=z2),
+                   reps=10)
+    t_plain = timed(lambda: ctx.simm_share(1, bs, idx, n_dev, n_blk, e2, f2, a2, b2, c2, out=z2), reps=10)
+    out["simm_row_sets_us"] = t_rows * 1e6
+    out["simm_union_of_masks_us"] = t_plain * 1e6
+    return out
+
+
 def micro(ctx, layer):
     """Per-kernel yardsticks on the same device (stderr + returned dict)."""
     import torch
@@ -213,6 +262,7 @@ def micro(ctx, layer):
     del m, idx
     t = timed(lambda: ctx.compact_mask(layer.mask, layer.idx, layer.n_dev), reps=50)
     out["compact_layer_mask_us"] = t * 1e6
+    out.update(general_forms(ctx, timed))
     macs = ctx.probe_mfma_i8(1024, 2000)
     t = timed(lambda: ctx.probe_mfma_i8(1024, 2000), reps=5)
     out["mfma_i8_issue_TOPs"] = 2.0 * macs / t / 1e12

@@ -8,7 +8,8 @@
 // unit, so one workgroup finds the same components by label propagation:
 //   * the mask is packed into one bit per edge (row-major bit words in LDS);
 //   * every token starts with its own number as label; a round gives every block the smallest
-//     label among its tokens and then every token the smallest label among its blocks; labels
+//     label among its tokens (pushed along the edges with LDS atomics) and then every token
+//     the smallest label among its blocks; labels
 //     only ever decrease, so the rounds end, with every node of a component carrying the
 //     component's smallest token;
 //   * components are numbered by that token (ascending), and the tokens and blocks that take
@@ -53,13 +54,33 @@ __global__ __launch_bounds__(CT) void components_kernel(const uint8_t* __restric
     __shared__ int changed, n_comp;
     const int wpr = (nb + 31) >> 5;
 
-    // edges -> bit words
+    // edges -> bit words; the 32 flags of a word are requested together (independent loads),
+    // as eight 4-byte words when every row starts on a 4-byte boundary
+    const bool rows4 = (reinterpret_cast<uintptr_t>(mask) & 3u) == 0 && (nb & 3) == 0;
     for (int i = threadIdx.x; i < n_tok * wpr; i += CT) {
         const int t = i / wpr, w = i - t * wpr;
         const uint8_t* src = mask + (size_t)t * nb + w * 32;
-        const int lim = nb - w * 32 < 32 ? nb - w * 32 : 32;
+        const int lim = nb - w * 32 < 32 ? nb - w * 32 : 32;          // flags of this word inside the row
         u32 v = 0;
-        for (int j = 0; j < lim; ++j) v |= (src[j] ? 1u : 0u) << j;
+        if (rows4) {
+            u32 q[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[j] = *reinterpret_cast<const u32*>(src + (4 * j < lim ? 4 * j : 0));
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (4 * j >= lim) continue;
+                v |= ((q[j] & 0x000000ffu) ? 1u : 0u) << (4 * j);
+                v |= ((q[j] & 0x0000ff00u) ? 2u : 0u) << (4 * j);
+                v |= ((q[j] & 0x00ff0000u) ? 4u : 0u) << (4 * j);
+                v |= ((q[j] & 0xff000000u) ? 8u : 0u) << (4 * j);
+            }
+        } else {
+            uint8_t q[32];
+#pragma unroll
+            for (int j = 0; j < 32; ++j) q[j] = src[j < lim ? j : 0];
+#pragma unroll
+            for (int j = 0; j < 32; ++j) v |= ((j < lim && q[j]) ? 1u : 0u) << j;
+        }
         bits[i] = v;
     }
     __syncthreads();
@@ -73,15 +94,22 @@ __global__ __launch_bounds__(CT) void components_kernel(const uint8_t* __restric
     // label propagation; a label is a token number and only decreases, so n_tok rounds suffice
     for (int round = 0; round <= n_tok; ++round) {
         if (threadIdx.x == 0) changed = 0;
-        for (int b = threadIdx.x; b < nb; b += CT) {
-            const int w = b >> 5;
-            const u32 bit = 1u << (b & 31);
-            int m = NONE;
-            for (int t = 0; t < n_tok; ++t)
-                if (bits[t * wpr + w] & bit) m = lr[t] < m ? lr[t] : m;
-            lb[b] = m;
+        // blocks take the smallest label among their tokens: every token pushes its label along
+        // its edges (work proportional to the number of edges, LDS atomics)
+        for (int b = threadIdx.x; b < nb; b += CT) lb[b] = NONE;
+        __syncthreads();
+        for (int t = threadIdx.x; t < n_tok; t += CT) {
+            const int mine = lr[t];
+            for (int w = 0; w < wpr; ++w) {
+                u32 v = bits[t * wpr + w];
+                while (v) {
+                    atomicMin(&lb[w * 32 + __builtin_ctz(v)], mine);
+                    v &= v - 1;
+                }
+            }
         }
         __syncthreads();
+        // tokens take the smallest label among their blocks
         for (int t = threadIdx.x; t < n_tok; t += CT) {
             int m = lr[t];
             for (int w = 0; w < wpr; ++w) {

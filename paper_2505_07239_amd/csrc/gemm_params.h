@@ -34,6 +34,9 @@ struct GemmParams {
     const int* row_comp;      // SOMM blocks: component number of each listed row
     const int* blk_comp;      // SOMM blocks: component number of each listed block
     const int* n_row_dev;     // SOMM blocks: number of listed rows (device), or null
+    int* tile_list;           // SOMM blocks: output tiles that touch a result block, [0] = their count
+    const int* tile_sel;      // SOMM blocks: which of two tile shapes runs (device), or null
+    int tile_sel_want;        //              the value this launch answers to
     const unsigned char* tmask;   // SIMM masked: m x tmask_nb bytes, token r uses block b
     long tmask_nb;
 #ifdef EXP_TRACE

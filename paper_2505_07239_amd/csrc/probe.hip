@@ -4,7 +4,7 @@
 #include "common.h"
 
 size_t comet_compact_workspace_bytes(int64_t n_tok, int64_t nb);
-size_t comet_gemm_workspace_bytes(int64_t m, int64_t kc_cap);
+size_t comet_gemm_workspace_bytes(int64_t m, int64_t kc_cap, int64_t n_cap);
 
 namespace {
 
@@ -111,7 +111,7 @@ size_t comet_workspace_bytes(int op, int64_t m, int64_t k, int64_t n, int bs) {
     switch (op) {
         case COMET_OP_COMPACT: return comet_compact_workspace_bytes(m, n);
         case COMET_OP_SOMM:
-        case COMET_OP_SIMM: return comet_gemm_workspace_bytes(m, k);
+        case COMET_OP_SIMM: return comet_gemm_workspace_bytes(m, k, n);
         default: return 0;
     }
 }

@@ -212,6 +212,60 @@ __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
 }
 
 // ---------------------------------------------------------------------------
+// result blocks (Protocol 2 in general form): which output tiles are computed
+// ---------------------------------------------------------------------------
+// Rows and columns are listed component by component, so a tile touches a result block exactly
+// when the component ranges of its rows and of its columns overlap.  One workgroup writes the
+// numbers of those tiles, in the order the GEMM enumerates tiles (tile = tn * tiles_m + tm),
+// to list[1 ..] and their count to list[0]; the GEMM then deals out work over that list only.
+// For tall operands two shapes are listed (128 x 64 and 64 x 64) and the choice between them is
+// made here, on the device, from the area each would compute: both GEMM kernels are launched
+// and the one that was not chosen returns at once, so the host never waits for the counts.
+__global__ __launch_bounds__(GT) void tile_list_kernel(GemmParams p, int BM, int BN, int* list,
+                                                        const int* other, int other_area, int* sel) {
+    __shared__ int wave_tot[GT / 64];
+    __shared__ int base;
+    const int nblk = n_blocks(p);
+    const int m_eff = n_rows(p), n_eff = nblk * p.bs;
+    const int tiles_m = (m_eff + BM - 1) / BM, tiles_n = (n_eff + BN - 1) / BN;
+    const int tiles = tiles_m * tiles_n;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) base = 0;
+    __syncthreads();
+    for (int t0 = 0; t0 < tiles; t0 += GT) {
+        const int tile = t0 + threadIdx.x;
+        bool on = false;
+        if (tile < tiles) {
+            const int tm = tile % tiles_m, tn = tile / tiles_m;
+            const int r_hi = (tm + 1) * BM < m_eff ? (tm + 1) * BM - 1 : m_eff - 1;
+            const int c_hi = (tn + 1) * BN < n_eff ? (tn + 1) * BN - 1 : n_eff - 1;
+            const int rc0 = p.row_comp[tm * BM], rc1 = p.row_comp[r_hi];
+            const int cc0 = p.blk_comp[tn * BN / p.bs], cc1 = p.blk_comp[c_hi / p.bs];
+            on = !(rc1 < cc0 || cc1 < rc0);
+        }
+        const unsigned long long bal = __ballot(on);
+        if (lane == 0) wave_tot[wave] = __builtin_popcountll(bal);
+        __syncthreads();
+        int pos = base + __builtin_popcountll(bal & ((1ull << lane) - 1));
+        for (int w = 0; w < wave; ++w) pos += wave_tot[w];
+        if (on) list[1 + pos] = tile;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int s = 0;
+            for (int w = 0; w < GT / 64; ++w) s += wave_tot[w];
+            base += s;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        list[0] = base;
+        // second of two shapes: this one runs when it computes at most 80 % of the other's area
+        // (smaller tiles follow the block structure more closely but reuse operands less)
+        if (sel) *sel = (5l * base * BM * BN < 4l * other[0] * other_area) ? 1 : 0;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // gemm
 // ---------------------------------------------------------------------------
 template <int WAVES_M, int WAVES_N, int WM, int WN>
@@ -573,6 +627,7 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
     __shared__ __align__(16) unsigned char xs2[T::XBYTES];
     __shared__ __align__(16) unsigned char wsm[T::WSTAGES * T::WBYTES];
 
+    if (p.tile_sel && *p.tile_sel != p.tile_sel_want) return;   // the other tile shape was chosen
     const int nblk = n_blocks(p);
     const int n_eff = KIND == KIND_SOMM ? nblk * p.bs : p.n_cap;
     const int kc = KIND == KIND_SOMM ? p.kc_cap : nblk * p.bs;
@@ -581,7 +636,9 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
     const int m_eff = n_rows(p);
     const int tiles_m = (m_eff + T::BM - 1) / T::BM;
     const int tiles_n = (n_eff + T::BN - 1) / T::BN;
-    const long units = (long)tiles_m * tiles_n * KT;
+    // with result blocks only the listed tiles are computed
+    const int tiles = p.row_comp ? p.tile_list[0] : tiles_m * tiles_n;
+    const long units = (long)tiles * KT;
     if (units == 0) return;
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one
@@ -606,8 +663,15 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
     // side therefore sweep the same slice of the contraction at the same time
     // (the activation planes of that slice stay hot in L2) and each XCD ends up
     // with whole slices, so a weight word is fetched from HBM by one XCD only.
-    const int CH = p.chunk;
-    const int tiles = tiles_m * tiles_n;
+    int CH = p.chunk;
+    if (p.row_comp) {
+        // the number of listed tiles is only known here: as many slices as workgroups per tile
+        int slices = (int)((G + tiles / 2) / tiles);
+        if (slices < 1) slices = 1;
+        CH = (KT + slices - 1) / slices;
+        if (CH > MAX_SEG) CH = MAX_SEG;
+        if (CH < 1) CH = 1;
+    }
     const long full_chunk_units = (long)tiles * CH;
     const int n_chunks = (KT + CH - 1) / CH;
     while (u < u_end) {
@@ -615,23 +679,13 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
         if (c > n_chunks - 1) c = n_chunks - 1;
         const long rem = u - (long)c * full_chunk_units;
         const int clen = (c == n_chunks - 1) ? KT - c * CH : CH;
-        const int tile = (int)(rem / clen);
-        const int ks0 = c * CH + (int)(rem - (long)tile * clen);
+        const int tile_pos = (int)(rem / clen);
+        const int ks0 = c * CH + (int)(rem - (long)tile_pos * clen);
+        const int tile = p.row_comp ? p.tile_list[1 + tile_pos] : tile_pos;
         long len = c * CH + clen - ks0;
         if (len > u_end - u) len = u_end - u;
         const int L = (int)len;
         const int tm = tile % tiles_m, tn = tile / tiles_m;
-
-        if (p.row_comp) {
-            // Result blocks (Protocol 2 in general form): rows and columns are listed component
-            // by component, so a tile touches a block exactly when the component ranges of its
-            // rows and of its columns overlap; the other tiles are not computed at all.
-            const int r_hi = (tm + 1) * T::BM < m_eff ? (tm + 1) * T::BM - 1 : m_eff - 1;
-            const int c_hi = (tn + 1) * T::BN < n_eff ? (tn + 1) * T::BN - 1 : n_eff - 1;
-            const int rc0 = p.row_comp[tm * T::BM], rc1 = p.row_comp[r_hi];
-            const int cc0 = p.blk_comp[tn * T::BN / p.bs], cc1 = p.blk_comp[c_hi / p.bs];
-            if (rc1 < cc0 || cc1 < rc0) { u += len; continue; }
-        }
 
         ld.setup(p, tm, tn, n_eff);
         v16i acc[WM][WN][8];
@@ -742,16 +796,26 @@ int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
 
 inline int round_up(int64_t v, int64_t to) { return (int)(((v + to - 1) / to) * to); }
 
-size_t gemm_ws_bytes(int64_t m, int64_t kc_cap) {
-    if (m < 1 || kc_cap < 0 || m > COMET_DIM_MAX || kc_cap > COMET_DIM_MAX) return 0;
+// digit planes of [E | A'] (the few-row path keeps its k-major copy there instead)
+size_t planes_bytes(int64_t m, int64_t kc_cap) {
     const size_t mpad = (size_t)round_up(m, 128);
     const size_t ks_cap = (size_t)((kc_cap + KSTEP - 1) / KSTEP);
     const size_t bytes = mpad * 2 * ks_cap * 256;
     return bytes ? bytes : 256;
 }
 
+// followed by the list of output tiles that touch a result block (general form of Protocol 2):
+// a selector, then twice (two tile shapes) one count plus one entry per tile of the smallest
+// tile shape, 64 x 64
+size_t gemm_ws_bytes(int64_t m, int64_t kc_cap, int64_t n_cap) {
+    if (m < 1 || kc_cap < 0 || n_cap < 0 || m > COMET_DIM_MAX || kc_cap > COMET_DIM_MAX || n_cap > COMET_DIM_MAX)
+        return 0;
+    const size_t tiles = (size_t)((m + 63) / 64) * (size_t)((n_cap + 63) / 64);
+    return planes_bytes(m, kc_cap) + (((2 * (tiles + 1) + 1) * sizeof(int) + 255) & ~(size_t)255);
+}
+
 int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t ws_bytes) {
-    const size_t need = gemm_ws_bytes(p.m, p.kc_cap);
+    const size_t need = gemm_ws_bytes(p.m, p.kc_cap, p.n_cap);
     if (!ws || ws_bytes < need)
         return comet_fail(ctx, COMET_EWORKSPACE, "%s: workspace of %zu bytes required", what, need);
     if (reinterpret_cast<uintptr_t>(ws) & 255u)
@@ -760,6 +824,7 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     if (!guard.ok) return comet_fail(ctx, COMET_EDEVICE, "%s: cannot select device", what);
 
     p.xp = static_cast<unsigned char*>(ws);
+    p.tile_list = reinterpret_cast<int*>(p.xp + planes_bytes(p.m, p.kc_cap));
     p.mpad = round_up(p.m, 128);
     p.ks_cap = (p.kc_cap + KSTEP - 1) / KSTEP;
     p.bs_shift = -1;
@@ -780,6 +845,38 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         COMET_LAUNCH_CHECK(ctx, what);
     }
     if (p.ks_cap == 0) return COMET_OK;
+    if (p.row_comp) {
+        // result blocks: list the tiles that are computed (see tile_list_kernel)
+        int* sel = p.tile_list;
+        int* list_a = sel + 1;
+        int* list_b = list_a + 1 + (size_t)((p.m + 63) / 64) * (size_t)((p.n_cap + 63) / 64);
+        p.tile_list = list_a;
+        if (ctx->gemm_tile == 2 || (p.m > 32 && p.m <= 64)) {
+            hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, 64, 64, list_a,
+                               (const int*)nullptr, 0, (int*)nullptr);
+            COMET_LAUNCH_CHECK(ctx, what);
+            return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+        }
+        if (p.m <= 32) {
+            hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, 32, 256, list_a,
+                               (const int*)nullptr, 0, (int*)nullptr);
+            COMET_LAUNCH_CHECK(ctx, what);
+            return launch_gemm<1, 4, 1, 2>(ctx, what, p);
+        }
+        hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, 128, 64, list_a,
+                           (const int*)nullptr, 0, (int*)nullptr);
+        COMET_LAUNCH_CHECK(ctx, what);
+        hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, 64, 64, list_b,
+                           (const int*)list_a, 128 * 64, sel);
+        COMET_LAUNCH_CHECK(ctx, what);
+        p.tile_sel = sel;
+        p.tile_sel_want = 0;
+        int rc = launch_gemm<2, 2, 2, 1>(ctx, what, p);
+        if (rc) return rc;
+        p.tile_list = list_b;
+        p.tile_sel_want = 1;
+        return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+    }
     if (ctx->gemm_tile == 2) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
     if (p.m <= 32) return launch_gemm<1, 4, 1, 2>(ctx, what, p);
     if (p.m <= 64) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
@@ -856,7 +953,9 @@ int simm_params(comet_ctx* ctx, const char* what, GemmParams& p, int party, int6
 
 }  // namespace
 
-size_t comet_gemm_workspace_bytes(int64_t m, int64_t kc_cap) { return gemm_ws_bytes(m, kc_cap); }
+size_t comet_gemm_workspace_bytes(int64_t m, int64_t kc_cap, int64_t n_cap) {
+    return gemm_ws_bytes(m, kc_cap, n_cap);
+}
 
 extern "C" {
 

@@ -114,3 +114,22 @@ def stress_mask_device(seed: int, n_flags: int, device, density: float = 0.15,
     delta.index_add_(0, starts, one)
     delta.index_add_(0, ends, -one)
     return (torch.cumsum(delta[:n_flags], 0, dtype=torch.int32) > 0).to(torch.uint8)
+
+
+def grouped_token_masks(seed: int, stream_base: int, n_tok: int, nb: int, groups: int,
+                        density: float, mean_run: float = 4.0) -> np.ndarray:
+    """Per-token masks whose (token, block) graph has several connected components.
+
+    Token ``t`` belongs to group ``t * groups // n_tok`` (think of a batch that holds ``groups``
+    unrelated requests); a group owns the block range ``[g * nb // groups, (g + 1) * nb // groups)``
+    and each of its tokens draws an independent clustered mask inside that range with
+    ``density * groups`` of the range active, i.e. ``density`` of all blocks.  Tokens of a group
+    overlap, tokens of different groups never do: the setting in which Protocol 2's grouping
+    into result blocks saves computation over the union of all masks.  Shape ``[n_tok, nb]``."""
+    out = np.zeros((n_tok, nb), dtype=np.uint8)
+    for t in range(n_tok):
+        g = t * groups // n_tok
+        lo, hi = g * nb // groups, (g + 1) * nb // groups
+        d = min(1.0, density * groups)
+        out[t, lo:hi] = clustered_block_mask(seed, stream_base + t, hi - lo, d, mean_run)
+    return out
