@@ -218,3 +218,33 @@ def beaver_share_sparse_input(party: int, e, f, a_i, b_i, c_i, s) -> np.ndarray:
     lib().co_beaver_share_sparse_input(party, _p(e), _p(f), _p(a_i), _p(b_i), _p(c_i), _p(s), _p(z),
                                        m, k, n)
     return z
+
+
+# ---- oblivious shuffle steps, merge to full width, share-local rescaling ----
+
+def permute_mask(src, perm, mask, axis: int, sign: int) -> np.ndarray:
+    """dst = perm(src) +/- mask along columns (axis 0) or rows (axis 1); p(x)_j = x[p[j]]."""
+    src, mask = _u64(src), _u64(mask)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    rows, cols = src.shape
+    assert mask.shape == src.shape and len(perm) == (cols if axis == 0 else rows)
+    dst = np.empty_like(src)
+    lib().co_permute_mask(_p(src), _p(perm), _p(mask), _p(dst), rows, cols, axis, sign)
+    return dst
+
+
+def scatter_cols(compact, idx, bs: int, n_full: int) -> np.ndarray:
+    compact = _u64(compact)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    m = compact.shape[0]
+    assert compact.shape[1] == len(idx) * bs
+    full = np.empty((m, n_full), dtype=np.uint64)
+    lib().co_scatter_cols(_p(compact), _p(idx), len(idx), bs, _p(full), m, n_full)
+    return full
+
+
+def truncate_share(party: int, z, frac_bits: int = 16) -> np.ndarray:
+    z = _u64(z)
+    out = np.empty_like(z)
+    lib().co_truncate_share(party, _p(z), _p(out), z.size, frac_bits)
+    return out

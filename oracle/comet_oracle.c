@@ -230,3 +230,49 @@ void co_beaver_share_sparse_input(int party, const u64* E, const u64* F, const u
         }
     }
 }
+
+/* ---- oblivious shuffle, the two local steps of the online stage (Protocol 1) ----
+ * A permutation p acts on a vector as p(x) = [x_{p_1}, x_{p_2}, ...], i.e.
+ * p(x)_j = x[p[j]] (0-based here).  On a matrix it acts along one axis:
+ * axis 0 (columns): out(r, j) = in(r, p[j]);  axis 1 (rows): out(j, c) = in(p[j], c).
+ * step 1:  y_i = tau_i(x_i) + a_i        (sign = +1)
+ * step 2:  z_i = rho_i(y_other) - b_i    (sign = -1)
+ * src, dst: rows x cols;  mask in the order of dst. */
+void co_permute_mask(const u64* src, const int32_t* perm, const u64* mask, u64* dst, int rows,
+                     int cols, int axis, int sign) {
+    for (int r = 0; r < rows; ++r)
+        for (int c = 0; c < cols; ++c) {
+            const u64 v = axis == 0 ? src[(size_t)r * cols + perm[c]] : src[(size_t)perm[r] * cols + c];
+            const u64 mk = mask[(size_t)r * cols + c];
+            dst[(size_t)r * cols + c] = sign > 0 ? v + mk : v - mk;
+        }
+}
+
+/* ---- Merge of Protocol 2 back to the full width ("reshaped to origin size") ----
+ * full (m x n_full) := 0, then the kept column blocks of compact (m x n_blk*bs)
+ * are written to their neurons: full(r, idx[t]*bs + j) = compact(r, t*bs + j). */
+void co_scatter_cols(const u64* compact, const int32_t* idx, int n_blk, int bs, u64* full, int m,
+                     int n_full) {
+    const int ld = n_blk * bs;
+    for (size_t i = 0; i < (size_t)m * n_full; ++i) full[i] = 0;
+    for (int r = 0; r < m; ++r)
+        for (int t = 0; t < n_blk; ++t)
+            for (int j = 0; j < bs; ++j)
+                full[(size_t)r * n_full + (size_t)idx[t] * bs + j] = compact[(size_t)r * ld + (size_t)t * bs + j];
+}
+
+/* ---- share-local rescaling after a fixed-point product ----
+ * The product of two values with f fractional bits carries 2f; each party
+ * divides its own share by 2^f without talking to the other:
+ *   party 0:  z_0' =   floor( z_0 / 2^f )          (z_0 read as signed)
+ *   party 1:  z_1' = - floor( (-z_1) / 2^f )
+ * The reconstruction differs from the exact quotient by at most one unit in the
+ * last place, except when the shares wrap (probability about |z| / 2^63 over
+ * the sharing randomness).  The paper does not state its rescaling; this is the
+ * usual two-party rule of the fixed-point framework it builds on. */
+void co_truncate_share(int party, const u64* z, u64* out, size_t n, int f) {
+    for (size_t i = 0; i < n; ++i) {
+        if (party == 0) out[i] = (u64)((int64_t)z[i] >> f);
+        else out[i] = (u64)0 - (u64)((int64_t)((u64)0 - z[i]) >> f);
+    }
+}

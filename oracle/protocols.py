@@ -325,3 +325,59 @@ def simm_general(x, y, s, a, b, a_split, b_split, c_split_cols) -> GeneralCase:
     e, f = co.open_(d[0], d[1]), co.open_(g[0], g[1])
     z = tuple(co.beaver_share_sparse_input(i, e, f, a_sh[i], b_sh[i], c_sh[i], s) for i in (0, 1))
     return GeneralCase("simm", s, a_sh, b_sh, tuple(c_sh), e, f, z)
+
+
+# ---------------------------------------------------------------------------
+# Protocol 1: oblivious shuffle
+# ---------------------------------------------------------------------------
+
+@dataclass
+class ShuffleMaterial:
+    """What the trusted third party hands out at the offline stage (0-based parties)."""
+    pi: np.ndarray
+    rho: Tuple[np.ndarray, np.ndarray]
+    tau: Tuple[np.ndarray, np.ndarray]
+    a: Tuple[np.ndarray, np.ndarray]
+    b: Tuple[np.ndarray, np.ndarray]
+
+
+def compose(f: np.ndarray, g: np.ndarray) -> np.ndarray:
+    """Index array of f o g (apply g first): (f o g)(x)_j = g(x)[f[j]] = x[g[f[j]]]."""
+    return np.asarray(g)[np.asarray(f)].astype(np.int32)
+
+
+def inverse(p: np.ndarray) -> np.ndarray:
+    inv = np.empty(len(p), dtype=np.int32)
+    inv[np.asarray(p)] = np.arange(len(p), dtype=np.int32)
+    return inv
+
+
+def shuffle_offline(pi, tau1, tau2, a1, a2, c, axis: int) -> ShuffleMaterial:
+    """Offline stage of Protocol 1 from given randomness: rho_1 = pi o tau_2^-1,
+    rho_2 = pi o tau_1^-1, b_1 = rho_1(a_2) + c, b_2 = rho_2(a_1) - c."""
+    pi, tau1, tau2 = (np.asarray(v, dtype=np.int32) for v in (pi, tau1, tau2))
+    rho1, rho2 = compose(pi, inverse(tau2)), compose(pi, inverse(tau1))
+    zero = np.zeros_like(a1)
+    b1 = co.permute_mask(a2, rho1, zero, axis, +1) + c
+    b2 = co.permute_mask(a1, rho2, zero, axis, +1) - c
+    return ShuffleMaterial(pi, (rho1, rho2), (tau1, tau2), (a1, a2), (b1, b2))
+
+
+def shuffle_online(x: Sequence[np.ndarray], mat: ShuffleMaterial, axis: int):
+    """Online stage: y_i = tau_i(x_i) + a_i is sent to the other party, which computes
+    z = rho(y) - b.  Returns (z_0, z_1) and the exchanged (y_0, y_1)."""
+    y = [co.permute_mask(x[i], mat.tau[i], mat.a[i], axis, +1) for i in (0, 1)]
+    z = tuple(co.permute_mask(y[1 - i], mat.rho[i], mat.b[i], axis, -1) for i in (0, 1))
+    return z, tuple(y)
+
+
+def unshuffle_material(mat: ShuffleMaterial, a1, a2, c, axis: int) -> ShuffleMaterial:
+    """Material of the shuffle that restores the original order ("unshuffle"): every party
+    inverts its own sub-permutations locally, tau_i' = rho_i^-1 and rho_i' = tau_i^-1, so that
+    rho_i' o tau_other' = tau_i^-1 o rho_other^-1 = (rho_other o tau_i)^-1 = pi^-1; fresh masks."""
+    tau = (inverse(mat.rho[0]), inverse(mat.rho[1]))
+    rho = (inverse(mat.tau[0]), inverse(mat.tau[1]))
+    zero = np.zeros_like(a1)
+    b1 = co.permute_mask(a2, rho[0], zero, axis, +1) + c
+    b2 = co.permute_mask(a1, rho[1], zero, axis, +1) - c
+    return ShuffleMaterial(inverse(mat.pi), rho, tau, (a1, a2), (b1, b2))
