@@ -223,6 +223,37 @@ def general_forms(ctx, timed):
     return out
 
 
+def glue_steps(ctx, timed):
+    """Shuffle steps, merge to full width and rescaling on a 4096 x 11008 matrix of words (the
+    activations of 4096 tokens at the FFN width): achieved GB/s of algorithmic bytes."""
+    import torch
+    import paper_2505_07239_amd as comet
+    rows, cols, bs = 4096, 11008, 32
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(78)
+    words = lambda *shape: torch.randint(-(2 ** 63), 2 ** 63 - 1, shape, dtype=torch.int64, device=dev,
+                                         generator=gen)
+    x, mk, o = words(rows, cols), words(rows, cols), torch.empty((rows, cols), dtype=torch.int64, device=dev)
+    pc = torch.randperm(cols, device=dev, generator=gen).to(torch.int32)
+    pr = torch.randperm(rows, device=dev, generator=gen).to(torch.int32)
+    n = rows * cols
+    out = {}
+    t = timed(lambda: ctx.permute_mask(x, pc, mk, comet.AXIS_COLS, +1, out=o), reps=10)
+    out["shuffle_cols_GBs"] = 24.0 * n / t / 1e9
+    t = timed(lambda: ctx.permute_mask(x, pr, mk, comet.AXIS_ROWS, -1, out=o), reps=10)
+    out["shuffle_rows_GBs"] = 24.0 * n / t / 1e9
+    t = timed(lambda: ctx.truncate_share(1, x, 16, out=o), reps=10)
+    out["truncate_GBs"] = 16.0 * n / t / 1e9
+    keep = 52
+    idx = (torch.arange(keep, device=dev, dtype=torch.int32) * 6).contiguous()
+    nd = torch.tensor([keep], dtype=torch.int32, device=dev)
+    c = words(rows, keep * bs)
+    t = timed(lambda: ctx.scatter_cols(c, bs, idx, nd, keep, cols, out=o), reps=10)
+    out["scatter_GBs"] = (8.0 * n + 16.0 * rows * keep * bs) / t / 1e9   # zero fill + kept blocks read and written
+    return out
+
+
 def micro(ctx, layer):
     """Per-kernel yardsticks on the same device (stderr + returned dict)."""
     import torch
@@ -263,6 +294,7 @@ def micro(ctx, layer):
     t = timed(lambda: ctx.compact_mask(layer.mask, layer.idx, layer.n_dev), reps=50)
     out["compact_layer_mask_us"] = t * 1e6
     out.update(general_forms(ctx, timed))
+    out.update(glue_steps(ctx, timed))
     macs = ctx.probe_mfma_i8(1024, 2000)
     t = timed(lambda: ctx.probe_mfma_i8(1024, 2000), reps=5)
     out["mfma_i8_issue_TOPs"] = 2.0 * macs / t / 1e12

@@ -217,6 +217,40 @@ int comet_simm_share_masked(comet_ctx* ctx, int party, int64_t m, int64_t k_full
                             const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i,
                             void* ws, size_t ws_bytes);
 
+/* ---- (5) local steps around the products ------------------------------- */
+
+/* One local step of the oblivious shuffle's online stage (Protocol 1):
+ *     dst = perm(src) + mask   (sign = +1:  y_i = tau_i(x_i) + a_i)
+ *     dst = perm(src) - mask   (sign = -1:  z_i = rho_i(y_other) - b_i)
+ * A permutation acts as perm(x)_j = x[perm[j]] (the paper's pi = [2,1,3] gives
+ * [x_2, x_1, x_3]), along the columns (COMET_AXIS_COLS: dst(r, j) = src(r, perm[j]),
+ * perm has cols entries) or the rows (COMET_AXIS_ROWS: dst(j, c) = src(perm[j], c),
+ * rows entries) of a rows x cols matrix; mask is in the order of dst.  dst must
+ * not alias src.  An entry of perm outside the axis is read as 0 (never a
+ * fault; the output is then meaningless).  rows, cols < 2^24. */
+int comet_permute_mask(comet_ctx* ctx, const uint64_t* src, const int32_t* perm,
+                       const uint64_t* mask, uint64_t* dst, int64_t rows, int64_t cols, int axis,
+                       int sign);
+
+/* Merge of a compact result back to the full width ("reshaped to origin size";
+ * Protocol 2's Merge for whole column blocks): full (m x n_full) is set to zero
+ * and column block t of compact (m x n_blk_cap*bs) is written to neurons
+ * blk_idx[t]*bs .. +bs, for t < *n_blk_dev (or n_blk_cap when null).  Applied to
+ * each party's share separately it yields shares of the scattered secret.  A
+ * block id that does not fit n_full is dropped. */
+int comet_scatter_cols(comet_ctx* ctx, const uint64_t* compact, int64_t m, int bs,
+                       const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap,
+                       uint64_t* full, int64_t n_full);
+
+/* Share-local rescaling of a fixed-point product by 2^frac_bits:
+ *   party 0: out = floor(z / 2^f) on the signed word;  party 1: out = -floor(-z / 2^f).
+ * The reconstruction is within one unit of the exact quotient unless the shares
+ * wrap around 2^64 (probability about |secret| / 2^63 over the sharing
+ * randomness).  The paper does not state its rescaling rule; this is the usual
+ * two-party one.  out may alias z. */
+int comet_truncate_share(comet_ctx* ctx, int party, const uint64_t* z, uint64_t* out,
+                         size_t n_elems, int frac_bits);
+
 /* ---- measurement aids (roofline probes; not part of the protocol) ------- */
 
 /* Launch-shape overrides for sweeps and for tests that must reach a particular

@@ -27,6 +27,7 @@ EXPORTS = [
     "comet_workspace_bytes", "comet_mask_share", "comet_mask_share_gather", "comet_open",
     "comet_compact_mask", "comet_somm_share", "comet_simm_share",
     "comet_components", "comet_somm_share_blocks", "comet_simm_share_masked",
+    "comet_permute_mask", "comet_scatter_cols", "comet_truncate_share",
     "comet_set_tuning", "comet_timing_begin", "comet_timing_end", "comet_probe_mfma_i8", "comet_probe_valu_mac64", "comet_probe_copy",
 ]
 
@@ -69,6 +70,9 @@ def load_library() -> ctypes.CDLL:
                                             vp, vp, vp, vp, vp, vp, vp, sz]
     lib.comet_simm_share_masked.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, i32, i32, vp, i64,
                                             vp, vp, vp, vp, vp, vp, vp, sz]
+    lib.comet_permute_mask.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32]
+    lib.comet_scatter_cols.argtypes = [vp, vp, i64, i32, vp, vp, i32, vp, i64]
+    lib.comet_truncate_share.argtypes = [vp, i32, vp, vp, sz, i32]
     lib.comet_probe_mfma_i8.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
     lib.comet_probe_valu_mac64.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
     lib.comet_probe_copy.argtypes = [vp, vp, vp, sz]
@@ -270,6 +274,39 @@ class Context:
             self.h, party, m, k_full, n, bs, _ptr(blk_idx), _ptr(n_blk_dev), n_blk_cap, flags,
             _ptr(token_mask), token_mask.shape[1], _ptr(e), _ptr(f), _ptr(a_i), _ptr(b_i), _ptr(c_i),
             _ptr(out), _ptr(ws), need))
+        return out
+
+    # ---- (5) local steps around the products ----
+    def permute_mask(self, src, perm, mask, axis, sign, out=None):
+        _words(src, "src"), _words(mask, "mask")
+        if perm.dtype != torch.int32 or not perm.is_cuda or not perm.is_contiguous():
+            raise TypeError("perm must be a contiguous int32 tensor on the GPU")
+        rows, cols = src.shape
+        if mask.shape != src.shape or perm.numel() != (cols if axis == AXIS_COLS else rows):
+            raise ValueError("mask must have the shape of src and perm one entry per index of the axis")
+        out = torch.empty_like(src) if out is None else _words(out, "out")
+        self._sync_stream()
+        self._check(self.lib.comet_permute_mask(self.h, _ptr(src), _ptr(perm), _ptr(mask), _ptr(out),
+                                                rows, cols, axis, sign))
+        return out
+
+    def scatter_cols(self, compact, bs, blk_idx, n_blk_dev, n_blk_cap, n_full, out=None):
+        _words(compact, "compact")
+        m = compact.shape[0]
+        if compact.shape[1] != n_blk_cap * bs:
+            raise ValueError("compact must be m x n_blk_cap*bs")
+        out = torch.empty((m, n_full), dtype=torch.int64, device=compact.device) if out is None \
+            else _words(out, "out")
+        self._sync_stream()
+        self._check(self.lib.comet_scatter_cols(self.h, _ptr(compact), m, bs, _ptr(blk_idx),
+                                                _ptr(n_blk_dev), n_blk_cap, _ptr(out), n_full))
+        return out
+
+    def truncate_share(self, party, z, frac_bits=16, out=None):
+        _words(z, "z")
+        out = torch.empty_like(z) if out is None else _words(out, "out")
+        self._sync_stream()
+        self._check(self.lib.comet_truncate_share(self.h, party, _ptr(z), _ptr(out), z.numel(), frac_bits))
         return out
 
     # ---- probes ----
