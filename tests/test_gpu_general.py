@@ -233,3 +233,60 @@ def test_somm_result_blocks_matrix_path_for_few_rows(ctx):
         _somm_blocks_case(ctx, 470, 12, 64, 18, 16, 3, 2)
     finally:
         ctx.set_tuning(comet.TUNE_SKINNY, 0)
+
+
+# ---------------------------------------------------------------------------
+# MHA-shaped workload: head-granular sparsity (block = one attention head)
+# ---------------------------------------------------------------------------
+
+def test_mha_sparse_qkv_and_output_layers(ctx):
+    """Sparse QKV layer with merged cache-refill rows (Protocol 2, result blocks) and sparse
+    output layer (Protocol 3, per-token head sets) at the LLaMA-2-7B attention shape.  Operands are
+    uniform random words (shares and opened values are uniform anyway; the C shares are not
+    tied to A B, the per-party share is checked for exactly the C that is passed in).  The QKV
+    share is compared on sampled rows, the output layer in full."""
+    cfg = configs.mha_config()
+    qkv_mask, out_mask = configs.mha_head_masks(cfg)
+    d, h, bs = cfg.d_model, cfg.n_heads, cfg.head_dim
+    seed = 600
+
+    # --- sparse QKV: rows = current tokens + refill rows, 96 column blocks of 128 ---
+    comp = check_components(ctx, qkv_mask)
+    comps, row_idx, row_comp, blk_idx, blk_comp = flat_components(qkv_mask)
+    n_row, n_blk = len(row_idx), len(blk_idx)
+    n_act = n_blk * bs
+    say("mha qkv: %d rows, %d of %d blocks, %d components" % (n_row, n_blk, 3 * h, len(comps)))
+    e, a = u64(seed, 1, n_row, d), u64(seed, 2, n_row, d)
+    f, b = u64(seed, 3, d, n_act), u64(seed, 4, d, 3 * h * bs)
+    c = u64(seed, 5, n_row, n_act)
+    z = ctx.somm_share_blocks(1, bs, comp["blk_idx"], comp["blk_comp"], comp["n_blk"], n_blk,
+                              comp["row_comp"], comp["n_row"], up(e), up(f), up(a), up(b), up(c))
+    torch.cuda.synchronize()
+    got = down(z)
+    cols = (blk_idx.astype(np.int64)[:, None] * bs + np.arange(bs)[None, :]).ravel()
+    b_sel = np.ascontiguousarray(b[:, cols])
+    col_comp = np.repeat(blk_comp, bs)
+    sample = sorted({0, 1, cfg.tokens - 1, cfg.tokens, n_row // 2, n_row - 1})
+    want = co.beaver_share_blocks(1, e[sample], f, a[sample], b_sel, c[sample], row_comp[sample], col_comp)
+    assert np.array_equal(got[sample], want)
+    # rows that were not sampled: the zero pattern between the blocks must hold everywhere
+    on = row_comp[:, None] == col_comp[None, :]
+    assert not got[~on].any()
+
+    # --- sparse output layer: contraction over the heads each token activated ---
+    idx_np = co.compact_mask(out_mask)
+    t = len(idx_np)
+    idx, n_dev = ctx.compact_mask(torch.from_numpy(out_mask).cuda())
+    m = cfg.tokens
+    kc = t * bs
+    say("mha output layer: %d tokens, %d of %d heads in the union" % (m, t, h))
+    e2, a2 = u64(seed, 11, m, kc), u64(seed, 12, m, h * bs)
+    f2, b2 = u64(seed, 13, kc, d), u64(seed, 14, h * bs, d)
+    c2 = u64(seed, 15, m, d)
+    tm = torch.from_numpy(out_mask).cuda()
+    z2 = ctx.simm_share_masked(1, bs, idx, n_dev, t, tm, up(e2), up(f2), up(a2), up(b2), up(c2))
+    torch.cuda.synchronize()
+    s_el = np.repeat(out_mask[:, idx_np], bs, axis=1)
+    want2 = co.beaver_share_sparse_input(1, e2, f2, co.index_cols(a2, idx_np, bs),
+                                         co.index_rows(b2, idx_np, bs), c2, s_el)
+    assert np.array_equal(down(z2), want2)

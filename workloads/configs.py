@@ -131,3 +131,66 @@ def raw_inputs(cfg: Config, mm: MatMul, seed: int = rng.BASE_SEED,
 def c_split(cfg: Config, mm: MatMul, rows: int, cols: int, seed: int = rng.BASE_SEED) -> np.ndarray:
     """Uniform uint64 randomness that splits the triple's C into two shares."""
     return rng.uniform_u64(seed, stream_id(cfg, mm.index, R_CSPLIT), rows * cols).reshape(rows, cols)
+
+
+# ---------------------------------------------------------------------------
+# MHA-shaped workload (Sec. 3.1 workflow, Sec. 6): head-granular sparsity
+# ---------------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class MhaConfig:
+    """Sparse QKV layer (Protocol 2) and sparse output layer (Protocol 3) of one attention
+    module with head-granular sparsity: a block is one attention head (``bs = head_dim``).
+
+    Rows of the QKV product are the tokens of the current step plus the merged cache-refill
+    requests of Sec. 6.1 (one row per token whose keys / values are missing for some heads), so
+    every row carries its own set of heads.  The fused QKV weight has ``3 * n_heads`` column
+    blocks (Q heads, then K heads, then V heads); a head that is active for a row keeps its
+    three blocks."""
+    name: str
+    d_model: int
+    n_heads: int
+    head_dim: int
+    tokens: int          # tokens of the current step (every activated head: Q, K and V)
+    refill_rows: int     # merged cache-miss rows (K and V of the heads they miss)
+    head_density: float  # fraction of heads a token activates ("more than 50 % inactive", Sec. 2.3)
+
+    @property
+    def rows(self) -> int:
+        return self.tokens + self.refill_rows
+
+
+def mha_config() -> MhaConfig:
+    """LLaMA-2-7B attention shape: 32 heads of 128, decode batch of 8 with 56 refill rows."""
+    return MhaConfig("llama7b_mha", 4096, 32, 128, 8, 56, 0.5)
+
+
+def mha_head_masks(cfg: MhaConfig, seed: int = rng.BASE_SEED):
+    """(qkv_mask [rows, 3 * n_heads], out_mask [tokens, n_heads]) as uint8.
+
+    Current tokens activate ``head_density`` of the heads, chosen uniformly per token (heads show
+    no spatial locality); a refill row misses between one and four of the heads that the current
+    step uses, and asks for their K and V blocks only."""
+    h = cfg.n_heads
+    out_mask = np.stack([masks.uniform_block_mask(seed, 6000 + t, h, cfg.head_density)
+                         for t in range(cfg.tokens)])
+    used = np.nonzero(out_mask.max(axis=0))[0]
+    qkv = np.zeros((cfg.rows, 3 * h), dtype=np.uint8)
+    qkv[:cfg.tokens, 0:h] = out_mask
+    qkv[:cfg.tokens, h:2 * h] = out_mask
+    qkv[:cfg.tokens, 2 * h:3 * h] = out_mask
+    draws = rng.uniform_u64(seed, 6500, cfg.refill_rows * 5).reshape(cfg.refill_rows, 5)
+    for r in range(cfg.refill_rows):
+        n_miss = 1 + int(draws[r, 0] % np.uint64(4))
+        for j in range(n_miss):
+            head = int(used[int(draws[r, 1 + j] % np.uint64(len(used)))])
+            qkv[cfg.tokens + r, h + head] = 1          # K of that head
+            qkv[cfg.tokens + r, 2 * h + head] = 1      # V of that head
+    return qkv, out_mask
+
+
+def prefetch_pays_off(l1: int, l2: int, head_weight_words: int, token_words: int) -> bool:
+    """Cost-benefit rule of Sec. 6.2 for prefetching a not-activated head: with ``l2`` cache
+    misses for it and ``l1`` for the activated heads, prefetch iff
+    ``l2 > w / x + max(0, l2 - l1)`` (w: size of the head's weight matrix, x: token vector size)."""
+    return l2 > head_weight_words / token_words + max(0, l2 - l1)
