@@ -768,7 +768,7 @@ int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
     // a chip-sized grid, shrunk when there is too little work to share out
     long grid = (ctx->num_cu / 8) * 8 * (WM * WN == 1 ? 2 : 1);
     if (grid < 8) grid = 8;
-    const long want = (units_cap + 3) / 4;
+    const long want = (units_cap + 1) / 2;      // at least two contraction steps per workgroup
     if (want < grid) grid = want < 8 ? (want < 1 ? 1 : want) : (want / 8) * 8;
     if (ctx->gemm_grid > 0) grid = ctx->gemm_grid;
     // Slice length: as many slices as there are workgroups per tile, so that a workgroup's
@@ -880,6 +880,10 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     if (ctx->gemm_tile == 2) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
     if (p.m <= 32) return launch_gemm<1, 4, 1, 2>(ctx, what, p);
     if (p.m <= 64) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+    // a small product (a handful of 128 x 64 tiles) is bound by the fixed cost per workgroup:
+    // the 64 x 64 tile doubles the number of independent tiles
+    const long big_tiles = (long)((p.m + 127) / 128) * ((p.n_cap + 63) / 64);
+    if (big_tiles * 8 <= ctx->num_cu) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
     return launch_gemm<2, 2, 2, 1>(ctx, what, p);
 }
 
