@@ -439,6 +439,10 @@ struct Loader {
             // (Left to the compiler, the wait would not count the LDS-DMA transfers issued in
             // between and would stall every step until those have landed.)  The register is
             // an in/out operand of the wait, so nothing that uses the word can move above it.
+            // Invariant this relies on: a register with a request in flight stays live until its
+            // wait -- every request is consumed by the next step's wait here, and a segment
+            // ends with a wait for everything -- because the compiler would otherwise be free to
+            // reuse a register that the memory system is still going to write.
             asm volatile("s_waitcnt vmcnt(%1)" : "+v"(wn[J][E]) : "n"(T::VM_PER_STEP - 1) : "memory");
             wa[J][E] = to_digits(wn[J][E]);
         }
