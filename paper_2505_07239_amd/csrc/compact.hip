@@ -271,7 +271,7 @@ __global__ __launch_bounds__(CT) void compact_emit_kernel(const unsigned short* 
         typedef int int4v __attribute__((ext_vector_type(4)));
         int4v* out4 = reinterpret_cast<int4v*>(out - ph);     // 16-byte aligned by construction
         const int4v* st4 = reinterpret_cast<const int4v*>(stage);
-        for (int q = q0 + threadIdx.x; q < q1; q += CT) out4[q] = st4[q];
+        for (int q = q0 + threadIdx.x; q < q1; q += CT) __builtin_nontemporal_store(st4[q], out4 + q);
         // ragged head (before the first whole quad) and tail (after the last)
         const int head_end = q0 * 4 < end ? q0 * 4 : end;
         if ((int)threadIdx.x >= ph && (int)threadIdx.x < head_end) out[threadIdx.x - ph] = stage[threadIdx.x];
