@@ -357,7 +357,7 @@ struct Loader {
             if (KIND == KIND_SOMM && p.b_full) {
                 const int blk = col / p.bs;
                 const long st = block_start(p, blk);
-                bcol = st < 0 ? 0 : st + (col - blk * p.bs);
+                bcol = (st < 0 ? 0 : st) + (col - blk * p.bs);
             }
             wb[j] = p.B + bcol;
             wf[j] = p.F + col;
