@@ -92,3 +92,54 @@ def test_block_ids_outside_the_axis_read_block_zero(ctx, m):
     torch.cuda.synchronize()
     want = co.beaver_share(1, e, f, a, co.index_cols(b, as_read, bs), c)
     assert np.array_equal(down(z), want)
+
+
+@pytest.mark.parametrize("m,bs", [(8, 8), (70, 8), (70, 6), (40, 16)])
+@pytest.mark.parametrize("full", [True, False])
+def test_simm_block_ids_outside_the_axis_read_block_zero(ctx, m, bs, full):
+    """Same rule on the contraction axis: the rows of B_i and the columns of A_i of a block whose id
+    does not fit are those of block 0 (few-row kernel, power-of-two and general block sizes)."""
+    nb, n = 7, 40
+    k_full = nb * bs
+    bad = np.array([2, -1, 1 << 18, 5], dtype=np.int32)
+    as_read = np.array([2, 0, 0, 5], dtype=np.int32)
+    t = len(bad)
+    seed = 730 + m + bs
+    e, a = u64(seed, 1, m, t * bs), u64(seed, 2, m, k_full)
+    f, b = u64(seed, 3, t * bs, n), u64(seed, 4, k_full, n)
+    c = u64(seed, 5, m, n)
+    say("bad block ids (simm) m=%d bs=%d full=%s" % (m, bs, full))
+    idx = torch.from_numpy(bad).cuda()
+    a_sel, b_sel = co.index_cols(a, as_read, bs), co.index_rows(b, as_read, bs)
+    if full:
+        z = ctx.simm_share(1, bs, idx, None, t, up(e), up(f), up(a), up(b), up(c))
+    else:                                     # already indexed operands: the list is not consulted
+        z = ctx.simm_share(1, bs, idx, None, t, up(e), up(f), up(a_sel), up(b_sel), up(c),
+                           a_full=False, b_full=False)
+    torch.cuda.synchronize()
+    assert np.array_equal(down(z), co.beaver_share(1, e, f, a_sel, b_sel, c))
+
+
+@pytest.mark.parametrize("axis", [0, 1])
+def test_indexed_masking_skips_blocks_that_do_not_fit(ctx, axis):
+    """comet_mask_share_gather leaves the outputs of a block whose id does not fit untouched."""
+    import paper_2505_07239_amd as comet
+    rows, cols, bs = (9, 48, 8) if axis == 0 else (48, 9, 8)
+    bad = np.array([1, 999, -3, 4], dtype=np.int32)
+    t = len(bad)
+    w, b = u64(750 + axis, 1, rows, cols), u64(750 + axis, 2, rows, cols)
+    shape = (rows, t * bs) if axis == 0 else (t * bs, cols)
+    out = torch.full(shape, -5, dtype=torch.int64, device="cuda")
+    say("indexed masking with ids that do not fit, axis %d" % axis)
+    ctx.mask_share_gather(up(w), up(b), axis, bs, torch.from_numpy(bad).cuda(), None, t, out=out)
+    torch.cuda.synchronize()
+    got = down(out)
+    d = w - b
+    for pos, blk in enumerate(bad):
+        sl = slice(pos * bs, (pos + 1) * bs)
+        piece = got[:, sl] if axis == 0 else got[sl, :]
+        if 0 <= blk and (blk + 1) * bs <= (cols if axis == 0 else rows):
+            want = d[:, blk * bs:(blk + 1) * bs] if axis == 0 else d[blk * bs:(blk + 1) * bs, :]
+            assert np.array_equal(piece, want)
+        else:
+            assert np.all(piece.view(np.int64) == -5)
