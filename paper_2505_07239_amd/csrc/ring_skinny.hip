@@ -81,13 +81,13 @@ struct WVec;
 template <>
 struct WVec<1> {
     u64 v[1];
-    __device__ __forceinline__ void load(const u64* q) { v[0] = *q; }
+    __device__ __forceinline__ void load(const u64* q) { v[0] = __builtin_nontemporal_load(q); }
 };
 template <>
 struct WVec<2> {
     u64 v[2];
     __device__ __forceinline__ void load(const u64* q) {
-        const u64x2 t = *reinterpret_cast<const u64x2*>(q);
+        const u64x2 t = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(q));   // read once
         v[0] = t.x; v[1] = t.y;
     }
 };
@@ -232,9 +232,9 @@ int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p) {
     const bool vec2 = (p.ldb & 1) == 0 && (p.ldf & 1) == 0 && (p.n_cap & 1) == 0 && (p.bs & 1) == 0;
     const int cols = vec2 ? 128 : 64;
     const long tiles = (p.n_cap + cols - 1) / cols;
-    // about eight workgroups per compute unit, each wavefront with at least one full batch of
+    // about sixteen workgroups per compute unit, each wavefront with at least one full batch of
     // rows in flight
-    long slices = (8l * ctx->num_cu + tiles - 1) / tiles;
+    long slices = (16l * ctx->num_cu + tiles - 1) / tiles;
     const long max_slices = (2l * p.kc_cap) / (SW * UNROLL);
     if (slices > max_slices) slices = max_slices;
     if (ctx->skinny_slices > 0) slices = ctx->skinny_slices;
