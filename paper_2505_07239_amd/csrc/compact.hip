@@ -38,6 +38,9 @@ __device__ __forceinline__ u32 nz_bits4(u32 w, int shift) {
 }
 
 // OR over tokens of flags [c0, c0+16) -> 16-bit word.  Flags at or beyond nb read as 0.
+// rows_aligned: every token row starts on a 16-byte boundary (one 16-byte load per token);
+// otherwise the sixteen flags of a token are sixteen independent byte loads (index clamped to
+// the row, surplus masked afterwards), so that a token costs one memory round trip, not sixteen.
 __device__ __forceinline__ u32 or_flags16(const uint8_t* __restrict__ mask, long n_tok, long nb,
                                           long c0, bool rows_aligned) {
     if (c0 >= nb) return 0;
@@ -47,13 +50,18 @@ __device__ __forceinline__ u32 or_flags16(const uint8_t* __restrict__ mask, long
             acc |= __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(mask + t * nb + c0));
         return nz_bits4(acc.x, 0) | nz_bits4(acc.y, 4) | nz_bits4(acc.z, 8) | nz_bits4(acc.w, 12);
     }
-    u32 bits = 0;
     const int lim = (int)((nb - c0) < FL ? (nb - c0) : FL);
-    for (int j = 0; j < lim; ++j) {
-        u32 any = 0;
-        for (long t = 0; t < n_tok; ++t) any |= mask[t * nb + c0 + j];
-        bits |= (any ? 1u : 0u) << j;
+    u32 any[FL];
+#pragma unroll
+    for (int j = 0; j < FL; ++j) any[j] = 0;
+    const uint8_t* src = mask + c0;
+    for (long t = 0; t < n_tok; ++t, src += nb) {
+#pragma unroll
+        for (int j = 0; j < FL; ++j) any[j] |= src[j < lim ? j : 0];
     }
+    u32 bits = 0;
+#pragma unroll
+    for (int j = 0; j < FL; ++j) bits |= ((j < lim && any[j]) ? 1u : 0u) << j;
     return bits;
 }
 
