@@ -888,6 +888,9 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     // the 64 x 64 tile doubles the number of independent tiles
     const long big_tiles = (long)((p.m + 127) / 128) * ((p.n_cap + 63) / 64);
     if (big_tiles * 8 <= ctx->num_cu) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+    // a ragged last row tile: 64-row tiles when they pad the rows by clearly less (the smaller
+    // tile is about 5 % slower per product)
+    if ((long)round_up(p.m, 64) * 110 < (long)round_up(p.m, 128) * 100) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
     return launch_gemm<2, 2, 2, 1>(ctx, what, p);
 }
 
