@@ -302,10 +302,11 @@ __device__ __forceinline__ void wait_and_barrier() {
 //
 // A contraction step issues 36 * WM * WN matrix instructions.  Everything else
 // a step has to do -- start the LDS-DMA of the activation planes two steps
-// ahead, load the weight words two steps ahead, turn the weight words of the
-// next step into digit planes and store them to LDS -- is cut into pieces of a
-// handful of instructions, and gemm_step() places one or two pieces behind
-// each matrix instruction so that they execute in its shadow.
+// ahead, request the weight words of the step after next, turn the weight
+// words of the next step (requested a step ago) into digit planes and store
+// them to LDS -- is cut into pieces of a handful of instructions, and
+// gemm_step() places a piece behind every second or third matrix instruction
+// so that they execute in its shadow.
 //
 // Activation side: the packed digit planes go from global memory straight into
 // LDS (global_load_lds_dwordx4: every lane supplies its own global address, the
@@ -313,8 +314,9 @@ __device__ __forceinline__ void wait_and_barrier() {
 // so they occupy no registers and need no LDS store.
 //
 // Weight side: raw uint64 words into registers; one step later each word is
-// split into digits and its register immediately reused for the next request.  Every load is unconditional: out-of-range rows and columns are clamped
-// to a valid address instead of being predicated off.  That is exact because
+// split into digits and its register immediately reused for the next request.
+// Every load is unconditional: out-of-range rows and columns are clamped to a
+// valid address instead of being predicated off.  That is exact because
 // (a) a weight column only feeds its own output column, and columns at or
 // beyond the kept width are never written back, and (b) the packed activation
 // planes hold zeros beyond the contraction length, so whatever the weight side
