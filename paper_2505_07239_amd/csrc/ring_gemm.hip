@@ -156,8 +156,13 @@ __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
     } else if (wide) {
         const u64* e = p.E + (size_t)row * p.lde + k0;
         u64x2 ev[8];
+        if (h == 0 || p.party) {                       // party 0's A' is A_i itself
 #pragma unroll
-        for (int j = 0; j < 8; ++j) ev[j] = *reinterpret_cast<const u64x2*>(e + 2 * j);
+            for (int j = 0; j < 8; ++j) ev[j] = *reinterpret_cast<const u64x2*>(e + 2 * j);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ev[j] = u64x2{0, 0};
+        }
         if (h == 0) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) { w[2 * j] = ev[j].x; w[2 * j + 1] = ev[j].y; }
