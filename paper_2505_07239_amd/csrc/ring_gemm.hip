@@ -439,20 +439,12 @@ struct Loader {
     // stacked contraction and the row gather are selects on wave-uniform values.
     template <int J, int E, bool SPLIT>
     __device__ __forceinline__ void load_piece(const GemmParams& p, int kc) {
-        if (SPLIT) {
-            // The word was requested one step ago.  Like the LDS-DMA, the request is issued from
-            // inline assembly, so the wait is written here by hand: everything but the
-            // VM_PER_STEP - 1 vector-memory operations issued after it may still be in flight.
-            // (Left to the compiler, the wait would not count the LDS-DMA transfers issued in
-            // between and would stall every step until those have landed.)  The register is
-            // an in/out operand of the wait, so nothing that uses the word can move above it.
-            // Invariant this relies on: a register with a request in flight stays live until its
-            // wait -- every request is consumed by the next step's wait here, and a segment
-            // ends with a wait for everything -- because the compiler would otherwise be free to
-            // reuse a register that the memory system is still going to write.
-            asm volatile("s_waitcnt vmcnt(%1)" : "+v"(wn[J][E]) : "n"(T::VM_PER_STEP - 1) : "memory");
-            wa[J][E] = to_digits(wn[J][E]);
-        }
+        // The compiler's wait for this word (requested a step ago) does not know about the LDS-DMA
+        // transfers issued since, which sit between the two in the in-order load queue, so it also
+        // waits for those.  Measured, that costs nothing: the kernel is bound by power, and a
+        // hand-written, exact wait (which needs the request in inline assembly, outside the
+        // compiler's view of the register) gave the same time per step.
+        if (SPLIT) wa[J][E] = to_digits(wn[J][E]);
         // octet index is the same for all lanes of a wavefront
         const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * J) / T::BN));
         const int k0 = s2 * KSTEP + oct * 8;
@@ -470,7 +462,7 @@ struct Loader {
         }
         // every operand holds fewer than 2^31 words (host check), so the word offset fits 32 bits
         const unsigned off = (unsigned)row * (unsigned)ld2;
-        asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(wn[J][E]) : "v"(src + off) : "memory");
+        wn[J][E] = src[off];
     }
 
     // quarter Q of the byte transpose of task J: Q = 0: low digits of words 0..3,
