@@ -38,6 +38,12 @@ struct GemmParams {
     const int* tile_sel;      // SOMM blocks: which of two tile shapes runs (device), or null
     int tile_sel_want;        //              the value this launch answers to
     const unsigned char* tmask;   // SIMM masked: m x tmask_nb bytes, token r uses block b
+    // SIMM masked, matrix-core kernel: per row tile the contraction steps that some token of
+    // the tile takes part in.  step_cnt[tm] steps, listed ascending at step_list[tm * ks_cap ..];
+    // step_off[tm] = number of listed steps of the row tiles before tm.
+    int* step_cnt;
+    int* step_off;
+    int* step_list;
     long tmask_nb;
 #ifdef EXP_TRACE
     u64* trace;

@@ -271,6 +271,89 @@ __global__ __launch_bounds__(GT) void tile_list_kernel(GemmParams p, int BM, int
 }
 
 // ---------------------------------------------------------------------------
+// per-token row sets (Protocol 3 in general form): which contraction steps a row tile computes
+// ---------------------------------------------------------------------------
+// Protocol 3 multiplies column j of X only on its row set R_j.  At tile granularity: a row tile
+// needs contraction step s (32 consecutive kept neurons) only if one of its tokens uses one of
+// the blocks the step touches; for all other steps the tile's activation digits are zero.  One
+// workgroup per row tile lists its steps in ascending order (grid.x = row tiles); a second,
+// one-workgroup kernel turns the counts into offsets.  The GEMM then deals out work over the
+// listed steps only.
+__global__ __launch_bounds__(GT) void step_list_kernel(GemmParams p, int BM) {
+    __shared__ int wave_tot[GT / 64];
+    __shared__ int base;
+    const int nblk = n_blocks(p);
+    const int m_eff = n_rows(p);
+    const int kc = nblk * p.bs;
+    const int KS = (kc + KSTEP - 1) / KSTEP;
+    const int tm = blockIdx.x;
+    const int r0 = tm * BM, r1 = (tm + 1) * BM < m_eff ? (tm + 1) * BM : m_eff;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int* list = p.step_list + (size_t)tm * p.ks_cap;
+    if (threadIdx.x == 0) base = 0;
+    __syncthreads();
+    for (int s0 = 0; s0 < KS; s0 += GT) {
+        const int st = s0 + threadIdx.x;
+        bool on = false;
+        if (st < KS && r0 < r1) {
+            const int t0 = st * KSTEP / p.bs;
+            int t1 = (st * KSTEP + KSTEP - 1) / p.bs;
+            t1 = t1 < nblk - 1 ? t1 : nblk - 1;
+            for (int t = t0; t <= t1 && !on; ++t)
+                for (int r = r0; r < r1 && !on; ++r) on = token_uses(p, r, t);
+        }
+        const unsigned long long bal = __ballot(on);
+        if (lane == 0) wave_tot[wave] = __builtin_popcountll(bal);
+        __syncthreads();
+        int pos = base + __builtin_popcountll(bal & ((1ull << lane) - 1));
+        for (int w = 0; w < wave; ++w) pos += wave_tot[w];
+        if (on) list[pos] = st;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int sum = 0;
+            for (int w = 0; w < GT / 64; ++w) sum += wave_tot[w];
+            base += sum;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) p.step_cnt[tm] = base;
+}
+
+// step_off[t] = step_cnt[0] + ... + step_cnt[t - 1] for t = 0 .. tiles (one workgroup)
+__global__ __launch_bounds__(GT) void step_offsets_kernel(GemmParams p, int BM) {
+    __shared__ int wave_tot[GT / 64];
+    __shared__ int base;
+    const int m_eff = n_rows(p);
+    const int tiles = (m_eff + BM - 1) / BM;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) base = 0;
+    __syncthreads();
+    for (int t0 = 0; t0 < tiles; t0 += GT) {
+        const int t = t0 + threadIdx.x;
+        const int v = t < tiles ? p.step_cnt[t] : 0;
+        int inc = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += o;
+        }
+        if (lane == 63) wave_tot[wave] = inc;
+        __syncthreads();
+        int pre = base + inc - v;
+        for (int w = 0; w < wave; ++w) pre += wave_tot[w];
+        if (t < tiles) p.step_off[t] = pre;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int sum = 0;
+            for (int w = 0; w < GT / 64; ++w) sum += wave_tot[w];
+            base += sum;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) p.step_off[tiles] = base;
+}
+
+// ---------------------------------------------------------------------------
 // gemm
 // ---------------------------------------------------------------------------
 template <int WAVES_M, int WAVES_N, int WM, int WN>
@@ -342,6 +425,7 @@ struct Loader {
     size_t xstride;            // bytes between the 16-byte units one thread moves per step
     int g0[W];                 // GATHER_POW2: first gathered row of this task's octet
     int gpend[W];              // GATHER_POW2: block id requested for the step after this one
+    const int* steps;          // listed contraction steps of this row tile, or null (all steps)
 
     static constexpr int XGRP_PER_PASS = GT / T::BM;         // groups covered by one pass of the block
     static_assert(GT % T::BM == 0, "tile rows must divide the block");
@@ -369,16 +453,27 @@ struct Loader {
             wb[j] = p.B + bcol;
             wf[j] = p.F + col;
         }
+        steps = nullptr;
         const int grp = threadIdx.x / T::BM, within = threadIdx.x % T::BM;
         xsrc = p.xp + ((size_t)grp * p.mpad + (size_t)tm * T::BM + within) * 16;
         xstride = (size_t)XGRP_PER_PASS * p.mpad * 16;
     }
 
     // block id that holds compact row octet (step ks, task j); GATHER_POW2 only
+    // A position ks in [0, 2 KS) of the stacked contraction of this tile -> half h and step s.
+    // Without a step list the positions are the steps themselves; with one (per-token row sets)
+    // a half has KS listed steps and position q stands for step steps[q].
+    __device__ __forceinline__ void resolve(int ks, int KS, int& h, int& s) const {
+        h = ks >= KS ? 1 : 0;
+        s = ks - h * KS;
+        if (steps) s = steps[s];
+    }
+
     __device__ __forceinline__ int gather_id(const GemmParams& p, int ks, int KS, int kc, int j) {
-        const int h = ks >= KS ? 1 : 0;
+        int h, s;
+        resolve(ks, KS, h, s);
         const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * j) / T::BN));
-        const int k0 = (ks - h * KS) * KSTEP + oct * 8;
+        const int k0 = s * KSTEP + oct * 8;
         const int kb = k0 <= kc - 8 ? k0 : kc - 8;
         return p.blk_idx[h ? 0 : (kb >> p.bs_shift)];
     }
@@ -397,8 +492,7 @@ struct Loader {
     // load returns long before the next call consumes it, so consuming it never
     // stalls on the LDS reads that share its counter.
     __device__ __forceinline__ void begin(const GemmParams& p, int ks, int KS, int kc, int ks_limit) {
-        h2 = ks >= KS ? 1 : 0;
-        s2 = ks - h2 * KS;
+        resolve(ks, KS, h2, s2);
         ld2 = (int)(h2 ? p.ldf : p.ldb);
         xs2 = xsrc + (size_t)(h2 * p.ks_cap + s2) * 16 * p.mpad * 16;
         if (GMODE == GATHER_POW2) {
@@ -641,7 +735,9 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
     const int tiles_n = (n_eff + T::BN - 1) / T::BN;
     // with result blocks only the listed tiles are computed
     const int tiles = p.row_comp ? p.tile_list[0] : tiles_m * tiles_n;
-    const long units = (long)tiles * KT;
+    // with per-token row sets only the listed steps of each row tile are computed
+    const bool listed = p.step_list != nullptr;
+    const long units = listed ? (long)tiles_n * 2 * p.step_off[tiles_m] : (long)tiles * KT;
     if (units == 0) return;
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one
@@ -678,19 +774,42 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
     const long full_chunk_units = (long)tiles * CH;
     const int n_chunks = (KT + CH - 1) / CH;
     while (u < u_end) {
-        int c = (int)(u / full_chunk_units);
-        if (c > n_chunks - 1) c = n_chunks - 1;
-        const long rem = u - (long)c * full_chunk_units;
-        const int clen = (c == n_chunks - 1) ? KT - c * CH : CH;
-        const int tile_pos = (int)(rem / clen);
-        const int ks0 = c * CH + (int)(rem - (long)tile_pos * clen);
-        const int tile = p.row_comp ? p.tile_list[1 + tile_pos] : tile_pos;
-        long len = c * CH + clen - ks0;
+        int tm, tn, ks0, KSt = KS;
+        long len;
+        const int* listed_steps = nullptr;
+        if (listed) {
+            // units are ordered row tile by row tile, inside a row tile column tile by column
+            // tile, inside a tile along its listed steps (E B_i half, then A' F half)
+            int lo = 0, hi = tiles_m;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if ((long)tiles_n * 2 * p.step_off[mid] <= u) lo = mid; else hi = mid;
+            }
+            tm = lo;
+            KSt = p.step_cnt[tm];
+            const long rem = u - (long)tiles_n * 2 * p.step_off[tm];
+            tn = (int)(rem / (2 * KSt));
+            ks0 = (int)(rem - (long)tn * 2 * KSt);
+            len = 2 * KSt - ks0;
+            if (len > MAX_SEG) len = MAX_SEG;
+            listed_steps = p.step_list + (size_t)tm * p.ks_cap;
+        } else {
+            int c = (int)(u / full_chunk_units);
+            if (c > n_chunks - 1) c = n_chunks - 1;
+            const long rem = u - (long)c * full_chunk_units;
+            const int clen = (c == n_chunks - 1) ? KT - c * CH : CH;
+            const int tile_pos = (int)(rem / clen);
+            ks0 = c * CH + (int)(rem - (long)tile_pos * clen);
+            const int tile = p.row_comp ? p.tile_list[1 + tile_pos] : tile_pos;
+            len = c * CH + clen - ks0;
+            tm = tile % tiles_m;
+            tn = tile / tiles_m;
+        }
         if (len > u_end - u) len = u_end - u;
         const int L = (int)len;
-        const int tm = tile % tiles_m, tn = tile / tiles_m;
 
         ld.setup(p, tm, tn, n_eff);
+        ld.steps = listed_steps;
         v16i acc[WM][WN][8];
 #pragma unroll
         for (int i = 0; i < WM; ++i)
@@ -705,10 +824,10 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
         const int ks_last = ks0 + L - 1;
         {
             using LD = Loader<T, KIND, GMODE>;
-            ld.prime(p, ks0, KS, kc);
-            ld.begin(p, ks0, KS, kc, ks_last);
+            ld.prime(p, ks0, KSt, kc);
+            ld.begin(p, ks0, KSt, kc, ks_last);
             ld.template pieces<LD::P_DMA, false>(std::make_integer_sequence<int, LD::P_END - LD::P_DMA>{}, p, kc, xs0, wsm);
-            ld.begin(p, ks0 + 1 < ks_last ? ks0 + 1 : ks_last, KS, kc, ks_last);
+            ld.begin(p, ks0 + 1 < ks_last ? ks0 + 1 : ks_last, KSt, kc, ks_last);
             ld.template pieces<LD::P_DMA, true>(std::make_integer_sequence<int, LD::P_END - LD::P_DMA>{}, p, kc, xs1, wsm);
         }
         wait_and_barrier<0>();
@@ -717,15 +836,15 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
             const int k2 = ks0 + i + 2;
             gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs0, wsm + (i & 1) * T::WBYTES,
                                               wsm + ((i + 1) & 1) * T::WBYTES, xs2, a_off, b_off,
-                                              k2 < ks_last ? k2 : ks_last, ks_last, KS, kc);
+                                              k2 < ks_last ? k2 : ks_last, ks_last, KSt, kc);
             if (i + 1 < L)
                 gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs1, wsm + ((i + 1) & 1) * T::WBYTES,
                                                   wsm + (i & 1) * T::WBYTES, xs0, a_off, b_off,
-                                                  k2 + 1 < ks_last ? k2 + 1 : ks_last, ks_last, KS, kc);
+                                                  k2 + 1 < ks_last ? k2 + 1 : ks_last, ks_last, KSt, kc);
             if (i + 2 < L)
                 gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs2, wsm + (i & 1) * T::WBYTES,
                                                   wsm + ((i + 1) & 1) * T::WBYTES, xs1, a_off, b_off,
-                                                  k2 + 2 < ks_last ? k2 + 2 : ks_last, ks_last, KS, kc);
+                                                  k2 + 2 < ks_last ? k2 + 2 : ks_last, ks_last, KSt, kc);
         }
         // the look-ahead transfers of the last steps are redundant; let them land before the
         // stages are reused
@@ -807,6 +926,14 @@ size_t planes_bytes(int64_t m, int64_t kc_cap) {
     return bytes ? bytes : 256;
 }
 
+// step lists of Protocol 3 with per-token row sets: per row tile of the smallest tile height (32)
+// a count, an offset and up to ks_cap listed steps
+size_t step_ws_bytes(int64_t m, int64_t kc_cap) {
+    const size_t tiles = (size_t)((m + 31) / 32);
+    const size_t ks_cap = (size_t)((kc_cap + KSTEP - 1) / KSTEP);
+    return ((tiles * (ks_cap + 2) + 1) * sizeof(int) + 255) & ~(size_t)255;
+}
+
 // followed by the list of output tiles that touch a result block (general form of Protocol 2):
 // a selector, then twice (two tile shapes) one count plus one entry per tile of the smallest
 // tile shape, 64 x 64
@@ -814,7 +941,8 @@ size_t gemm_ws_bytes(int64_t m, int64_t kc_cap, int64_t n_cap) {
     if (m < 1 || kc_cap < 0 || n_cap < 0 || m > COMET_DIM_MAX || kc_cap > COMET_DIM_MAX || n_cap > COMET_DIM_MAX)
         return 0;
     const size_t tiles = (size_t)((m + 63) / 64) * (size_t)((n_cap + 63) / 64);
-    return planes_bytes(m, kc_cap) + (((2 * (tiles + 1) + 1) * sizeof(int) + 255) & ~(size_t)255);
+    return planes_bytes(m, kc_cap) + (((2 * (tiles + 1) + 1) * sizeof(int) + 255) & ~(size_t)255) +
+           step_ws_bytes(m, kc_cap);
 }
 
 int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t ws_bytes) {
@@ -880,16 +1008,37 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         p.tile_sel_want = 1;
         return launch_gemm<2, 2, 1, 1>(ctx, what, p);
     }
-    if (ctx->gemm_tile == 2) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
-    if (p.m <= 32) return launch_gemm<1, 4, 1, 2>(ctx, what, p);
-    if (p.m <= 64) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+    // tile shape: rows per workgroup tile 128, 64 or 32
+    int bm = 128;
+    const long big_tiles = (long)((p.m + 127) / 128) * ((p.n_cap + 63) / 64);
+    if (ctx->gemm_tile == 2) bm = 64;
+    else if (p.m <= 32) bm = 32;
+    else if (p.m <= 64) bm = 64;
     // a small product (a handful of 128 x 64 tiles) is bound by the fixed cost per workgroup:
     // the 64 x 64 tile doubles the number of independent tiles
-    const long big_tiles = (long)((p.m + 127) / 128) * ((p.n_cap + 63) / 64);
-    if (big_tiles * 8 <= ctx->num_cu) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+    else if (big_tiles * 8 <= ctx->num_cu) bm = 64;
     // a ragged last row tile: 64-row tiles when they pad the rows by clearly less (the smaller
     // tile is about 5 % slower per product)
-    if ((long)round_up(p.m, 64) * 110 < (long)round_up(p.m, 128) * 100) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+    else if ((long)round_up(p.m, 64) * 110 < (long)round_up(p.m, 128) * 100) bm = 64;
+    // per-token row sets: 64-row tiles follow the row sets more closely
+    else if (p.tmask) bm = 64;
+    if (p.tmask) {
+        // list, per row tile, the contraction steps some token of the tile takes part in
+        const size_t tiles64 = (size_t)((p.m + 63) / 64) * (size_t)((p.n_cap + 63) / 64);
+        const size_t tl_bytes = ((2 * (tiles64 + 1) + 1) * sizeof(int) + 255) & ~(size_t)255;
+        const size_t t32 = (size_t)((p.m + 31) / 32);
+        int* base = reinterpret_cast<int*>(p.xp + planes_bytes(p.m, p.kc_cap) + tl_bytes);
+        p.step_cnt = base;
+        p.step_off = base + t32;
+        p.step_list = base + 2 * t32 + 1;
+        const unsigned tiles_m = (unsigned)((p.m + bm - 1) / bm);
+        hipLaunchKernelGGL(step_list_kernel, dim3(tiles_m), dim3(GT), 0, ctx->stream, p, bm);
+        COMET_LAUNCH_CHECK(ctx, what);
+        hipLaunchKernelGGL(step_offsets_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, bm);
+        COMET_LAUNCH_CHECK(ctx, what);
+    }
+    if (bm == 32) return launch_gemm<1, 4, 1, 2>(ctx, what, p);
+    if (bm == 64) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
     return launch_gemm<2, 2, 2, 1>(ctx, what, p);
 }
 

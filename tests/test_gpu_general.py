@@ -130,7 +130,11 @@ def test_components_rejects_oversize(ctx):
 
 @pytest.mark.parametrize("m,nb,bs,n,groups,per_tok", [(3, 12, 8, 40, 2, 2), (8, 24, 16, 96, 3, 3),
                                                       (13, 10, 3, 33, 2, 2), (40, 20, 32, 70, 4, 2),
-                                                      (130, 16, 16, 200, 3, 4), (70, 9, 5, 64, 1, 3)])
+                                                      (130, 16, 16, 200, 3, 4), (70, 9, 5, 64, 1, 3),
+                                                      # several row tiles with different step lists
+                                                      (300, 40, 32, 96, 5, 3), (200, 30, 64, 70, 4, 2),
+                                                      # more listed steps than one accumulation segment holds
+                                                      (100, 300, 32, 64, 1, 290)])
 @pytest.mark.parametrize("compact_triples", [False, True])
 def test_simm_per_token_row_sets(ctx, m, nb, bs, n, groups, per_tok, compact_triples):
     seed = 300 + m
