@@ -69,9 +69,9 @@ __global__ __launch_bounds__(EW_THREADS) void gather_cols_kernel(
         const size_t src = r * (size_t)cols + (size_t)start + (c - blk * bs);
         const size_t dst = r * (size_t)ld + c;
         if (VEC == 2) {
-            const u64x2 x = *reinterpret_cast<const u64x2*>(w + src);
-            const u64x2 y = *reinterpret_cast<const u64x2*>(b + src);
-            *reinterpret_cast<u64x2*>(g + dst) = x - y;
+            const u64x2 x = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(w + src));
+            const u64x2 y = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(b + src));
+            __builtin_nontemporal_store(x - y, reinterpret_cast<u64x2*>(g + dst));
         } else {
             g[dst] = w[src] - b[src];
         }
@@ -94,9 +94,9 @@ __global__ __launch_bounds__(EW_THREADS) void gather_rows_kernel(
     for (int c = (blockIdx.y * EW_THREADS + threadIdx.x) * VEC; c < cols;
          c += gridDim.y * EW_THREADS * VEC) {
         if (VEC == 2) {
-            const u64x2 x = *reinterpret_cast<const u64x2*>(w + src + c);
-            const u64x2 y = *reinterpret_cast<const u64x2*>(b + src + c);
-            *reinterpret_cast<u64x2*>(g + dst + c) = x - y;
+            const u64x2 x = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(w + src + c));
+            const u64x2 y = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(b + src + c));
+            __builtin_nontemporal_store(x - y, reinterpret_cast<u64x2*>(g + dst + c));
         } else {
             g[dst + c] = w[src + c] - b[src + c];
         }
