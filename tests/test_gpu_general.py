@@ -294,3 +294,49 @@ def test_mha_sparse_qkv_and_output_layers(ctx):
     want2 = co.beaver_share_sparse_input(1, e2, f2, co.index_cols(a2, idx_np, bs),
                                          co.index_rows(b2, idx_np, bs), c2, s_el)
     assert np.array_equal(down(z2), want2)
+
+
+# ---------------------------------------------------------------------------
+# seeded sweep over both general forms
+# ---------------------------------------------------------------------------
+
+def _draw_general(case):
+    r = rng.uniform_u64(4343, case, 10)
+    pick = lambda i, lo, hi: lo + int(r[i] % np.uint64(hi - lo + 1))
+    m = [2, 9, 16, 17, 40, 64, 100, 129, 260][pick(0, 0, 8)]
+    bs = [2, 3, 8, 16, 32, 64][pick(1, 0, 5)]
+    nb = pick(2, 3, max(3, min(36, 576 // bs)))
+    groups = pick(3, 1, min(5, nb))
+    per_tok = pick(4, 1, 4)
+    other = pick(5, 8, 200)
+    return m, bs, nb, groups, per_tok, other
+
+
+@pytest.mark.parametrize("case", range(20))
+def test_general_forms_sweep(ctx, case):
+    m, bs, nb, groups, per_tok, other = _draw_general(case)
+    say("sweep %d: m=%d bs=%d nb=%d groups=%d per_tok=%d other=%d" % (case, m, bs, nb, groups, per_tok, other))
+    # Protocol 2 with result blocks (other = contraction length)
+    _somm_blocks_case(ctx, 6000 + case, m, other, nb, bs, groups, per_tok, spare_rows=case % 3,
+                      spare_blocks=0, b_full=bool(case & 1))
+    # Protocol 3 with per-token row sets (other = output width)
+    seed = 6500 + case
+    k = nb * bs
+    mask_blk = grouped_mask(seed, m, nb, groups, per_tok)
+    if not mask_blk.any():
+        return
+    s = np.repeat(mask_blk, bs, axis=1)
+    idx_np = co.compact_mask(mask_blk)
+    t = len(idx_np)
+    # the one-pass oracle on operands drawn directly (its agreement with the literal protocol is
+    # pinned in the CPU suite); entries outside the sparsity distribution hold junk
+    e, a = u64(seed, 1, m, t * bs), u64(seed, 2, m, k)
+    f, b = u64(seed, 3, t * bs, other), u64(seed, 4, k, other)
+    c = u64(seed, 5, m, other)
+    idx, n_dev = ctx.compact_mask(torch.from_numpy(mask_blk).cuda())
+    z = ctx.simm_share_masked(1, bs, idx, n_dev, t, torch.from_numpy(mask_blk).cuda(), up(e), up(f), up(a),
+                              up(b), up(c))
+    torch.cuda.synchronize()
+    want = co.beaver_share_sparse_input(1, e, f, co.index_cols(a, idx_np, bs), co.index_rows(b, idx_np, bs), c,
+                                        np.ascontiguousarray(s[:, np.repeat(idx_np, bs) * bs + np.tile(np.arange(bs), t)]))
+    assert np.array_equal(down(z), want)
