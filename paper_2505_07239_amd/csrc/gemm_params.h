@@ -45,9 +45,6 @@ struct GemmParams {
     int* step_off;
     int* step_list;
     long tmask_nb;
-#ifdef EXP_TRACE
-    u64* trace;
-#endif
 };
 
 static __device__ __forceinline__ int n_blocks(const GemmParams& p) {
