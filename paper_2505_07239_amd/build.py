@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcomet_ring.so")
 SOURCES = ["ctx.hip", "elementwise.hip", "compact.hip", "ring_gemm.hip", "ring_skinny.hip", "components.hip", "glue.hip", "probe.hip"]
-FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=default",
+FLAGS = ["-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-fvisibility=default",
          # the LDS-DMA helper names M0 as clobbered, which clang flags as a reserved register
          "-Wno-inline-asm",
          # packed-FP32 instruction selection is switched off for every device pass
