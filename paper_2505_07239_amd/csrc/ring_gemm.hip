@@ -860,9 +860,15 @@ __global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(G
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int row = tm * T::BM + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                    u64 z = 0;
-#pragma unroll
-                    for (int s = 0; s < 8; ++s) z += (u64)(long long)acc[i][j][s][e] << (8 * s);
+                    // sum_s sext64(S_s) << 8s: the four low planes as 32 x 32 -> 64 bit signed
+                    // multiply-adds, the four high planes only reach the upper word
+                    long long lo = (long long)acc[i][j][0][e];
+                    lo += (long long)acc[i][j][1][e] * (1 << 8);
+                    lo += (long long)acc[i][j][2][e] * (1 << 16);
+                    lo += (long long)acc[i][j][3][e] * (1 << 24);
+                    const u32 hi = (u32)acc[i][j][4][e] + ((u32)acc[i][j][5][e] << 8) +
+                                   ((u32)acc[i][j][6][e] << 16) + ((u32)acc[i][j][7][e] << 24);
+                    const u64 z = (u64)lo + ((u64)hi << 32);
                     bool live = row < m_eff && col < n_eff;
                     if (live && p.row_comp) live = p.row_comp[row] == ccomp;   // on a result block
                     if (live) atomicAdd(p.Z + (size_t)row * p.ldz + col, z);
