@@ -142,6 +142,7 @@ def cpu_baseline(layer, budget_s=20.0):
     cores = co.num_threads()
     per_proj = budget_s / len(layer.mm)
     total_ops, total_s, ok, notes = 0.0, 0.0, True, []
+    one_ops, one_s = 0.0, 0.0                 # the one-row trials: one output row, so one thread
     for b in layer.mm:
         mm = b["mm"]
         e, f = host(b["e"]), host(b["f"])
@@ -160,6 +161,8 @@ def cpu_baseline(layer, budget_s=20.0):
         t0 = time.perf_counter()
         co.beaver_share_rows(0, e, f, a_sel[0], b_sel[0], c[0], 0, 1)
         t_row = max(time.perf_counter() - t0, 1e-6)
+        one_ops += 2 * (2.0 * k_eff * n_eff)                       # party 0: two products, 2 ops/MAC
+        one_s += t_row
         rows = int(max(1, min(mm.m, per_proj / (2.0 * t_row) * min(cores, 8))))
         t0 = time.perf_counter()
         z = [co.beaver_share_rows(i, e, f, a_sel[i], b_sel[i], c[i], 0, rows) for i in (0, 1)]
@@ -169,6 +172,7 @@ def cpu_baseline(layer, budget_s=20.0):
         total_s += dt
         notes.append("%s rows 0..%d of %d" % (mm.name, rows, mm.m))
     return {"value": total_ops / total_s / 1e9, "unit": "Gop/s", "cores": cores, "kind": "oracle",
+            "value_1core": one_ops / one_s / 1e9,
             "sample": "both parties' shares, %s; oracle's 3-product Eq. 1 loops counted as the "
                       "2-product minimum; %.1f s of CPU time" % ("; ".join(notes), total_s),
             "matches_gpu": bool(ok)}
