@@ -101,6 +101,76 @@ class Layer:
             self.mm.append(b)
         self.ring_ops_per_step = sum(2 * 2 * b["macs_per_launch"] for b in self.mm)   # 2 parties, 2 ops/MAC
 
+    # ---- the same step with the bandwidth-bound kernels and the ring GEMMs on two streams ----
+    def enable_overlap(self, ctx_stream_kernels):
+        """Second set of the buffers a step writes (index list, masked and opened operands,
+        output shares), two streams of default priority and the events that order them.  The
+        masking / opening / compaction kernels of one step then run beside the GEMMs of the
+        previous projection or the previous step: consecutive steps alternate between the sets."""
+        import torch
+        self.ctx_ew = ctx_stream_kernels
+        self.s_ew, self.s_gemm = torch.cuda.Stream(), torch.cuda.Stream()
+        dev = self.idx.device
+        self.sets = []
+        for q in (0, 1):
+            st = {"idx": self.idx if q == 0 else torch.zeros_like(self.idx),
+                  "n_dev": self.n_dev if q == 0 else torch.zeros_like(self.n_dev), "mm": []}
+            for b in self.mm:
+                if q == 0:
+                    st["mm"].append(b)
+                else:
+                    c2 = dict(b)
+                    for key in ("d", "g", "z"):
+                        c2[key] = [torch.empty_like(t) for t in b[key]]
+                    for key in ("e", "f"):
+                        c2[key] = torch.empty_like(b[key])
+                    st["mm"].append(c2)
+            st["ew_done"] = [torch.cuda.Event() for _ in self.mm]
+            st["gemm_done"] = torch.cuda.Event()
+            st["gemm_done"].record(torch.cuda.current_stream())
+            self.sets.append(st)
+        self.parity = 0
+        del dev
+
+    def step_overlapped(self):
+        import torch
+        import paper_2505_07239_amd as comet
+        cfg = self.cfg
+        st = self.sets[self.parity]
+        self.parity ^= 1
+        with torch.cuda.stream(self.s_ew):
+            self.s_ew.wait_event(st["gemm_done"])          # the GEMMs that last read this set are done
+            ctx = self.ctx_ew
+            ctx.compact_mask(self.mask, st["idx"], st["n_dev"])
+            for j, b in enumerate(st["mm"]):
+                mm = b["mm"]
+                for i in (0, 1):
+                    if mm.kind == "somm":
+                        ctx.mask_share(b["x"][i], b["a"][i], out=b["d"][i])
+                        ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_COLS, cfg.bs, st["idx"],
+                                              st["n_dev"], self.n_blk, out=b["g"][i])
+                    else:
+                        ctx.mask_share_gather(b["x"][i], b["a"][i], comet.AXIS_COLS, cfg.bs, st["idx"],
+                                              st["n_dev"], self.n_blk, out=b["d"][i])
+                        ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_ROWS, cfg.bs, st["idx"],
+                                              st["n_dev"], self.n_blk, out=b["g"][i])
+                ctx.open(b["d"][0], b["d"][1], out=b["e"])
+                ctx.open(b["g"][0], b["g"][1], out=b["f"])
+                st["ew_done"][j].record(self.s_ew)
+        with torch.cuda.stream(self.s_gemm):
+            ctx = self.ctx
+            for j, b in enumerate(st["mm"]):
+                mm = b["mm"]
+                self.s_gemm.wait_event(st["ew_done"][j])
+                for i in (0, 1):
+                    if mm.kind == "somm":
+                        ctx.somm_share(i, cfg.bs, st["idx"], st["n_dev"], self.n_blk, b["e"], b["f"],
+                                       b["a"][i], b["b"][i], b["c"][i], out=b["z"][i])
+                    else:
+                        ctx.simm_share(i, cfg.bs, st["idx"], st["n_dev"], self.n_blk, b["e"], b["f"],
+                                       b["a"][i], b["b"][i], b["c"][i], out=b["z"][i])
+            st["gemm_done"].record(self.s_gemm)
+
     def step(self):
         import paper_2505_07239_amd as comet
         ctx, cfg = self.ctx, self.cfg
@@ -323,6 +393,8 @@ def main():
                     help="c1..c4, c5_d100 / c5_d050 / c5_d025 / c5_d010 / c5_d005")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run the bandwidth-bound kernels and the ring GEMMs on two streams")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of one step captured in a HIP graph instead of eager calls")
     ap.add_argument("--gemm-chunk", type=int, default=0, help="tuning sweep: scheduling slice length")
@@ -358,8 +430,13 @@ def main():
         (wname, cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs, layer.n_blk, cfg.nb,
          layer.n_act, layer.ring_ops_per_step / 1e9))
 
+    run_step = layer.step
+    if args.overlap:
+        ctx_ew = comet.Context(0)
+        layer.enable_overlap(ctx_ew)
+        run_step = layer.step_overlapped
     for _ in range(args.warmup):
-        layer.step()
+        run_step()
     torch.cuda.synchronize()
     launches = 2 * len(layer.mm) * args.steps
     if args.graph:
@@ -385,7 +462,7 @@ def main():
         ctx.timing_begin(launches)
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            layer.step()
+            run_step()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         gemm_ms, n_timed = ctx.timing_end()
@@ -406,7 +483,8 @@ def main():
                                 "+".join(m.name for m in cfg.matmuls)),
                    "ring_ops_per_step": layer.ring_ops_per_step,
                    "launches_per_step": 2 * len(layer.mm),
-                   "submission": "hip graph replay" if args.graph else "eager"},
+                   "submission": "hip graph replay" if args.graph else
+                                 ("eager, two streams" if args.overlap else "eager")},
         "roofline": {"bound": "mfma", "kernel": "ring_gemm_kernel",
                      "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": achieved / PEAK_INT8_TOPS,
