@@ -326,3 +326,85 @@ def test_simm_one_pass_ignores_entries_outside_s():
     junk_a = np.where(s != 0, gen.a[1], u64(45, 51, m, k))
     assert np.array_equal(co.beaver_share_sparse_input(1, junk_e, gen.f, junk_a, gen.b[1], gen.c[1], s),
                           gen.z[1])
+
+
+# ---------------------------------------------------------------------------
+# Optimality appendix: the grouping Protocol 2 uses, and the work of Protocol 3
+# ---------------------------------------------------------------------------
+
+def _set_partitions(items):
+    """Every partition of a list into non-empty groups."""
+    if not items:
+        yield []
+        return
+    head, rest = items[0], items[1:]
+    for part in _set_partitions(rest):
+        for i in range(len(part)):
+            yield part[:i] + [[head] + part[i]] + part[i + 1:]
+        yield [[head]] + part
+
+
+def test_components_are_the_optimal_grouping_by_brute_force():
+    """Theorem 1: over every way of splitting the requested outputs (edges)
+    into disjoint result blocks, the split into connected components has the
+    smallest total node count S1 and, among the splits that reach it, the
+    smallest total of |X_i| |Y_i|.  Checked by listing all partitions of the
+    edge set of tiny graphs (at most 7 edges, 877 partitions)."""
+    checked = 0
+    for seed in range(40):
+        m, n = 2 + seed % 3, 2 + seed % 4
+        s = (u64(seed, 31, m, n) % np.uint64(3) == 0).astype(np.uint8)
+        edges = [(i, j) for i in range(m) for j in range(n) if s[i, j]]
+        if not 2 <= len(edges) <= 7:
+            continue
+        comps = protocols.components(s)
+        s1_comp = sum(len(r) + len(c) for r, c in comps)
+        s2_comp = sum(len(r) * len(c) for r, c in comps)
+        best_s1, best_s2 = None, None
+        for part in _set_partitions(edges):
+            s1 = sum(len({i for i, _ in g}) + len({j for _, j in g}) for g in part)
+            s2 = sum(len({i for i, _ in g}) * len({j for _, j in g}) for g in part)
+            if best_s1 is None or s1 < best_s1:
+                best_s1, best_s2 = s1, s2
+            elif s1 == best_s1 and s2 < best_s2:
+                best_s2 = s2
+        assert (s1_comp, s2_comp) == (best_s1, best_s2), (seed, s.tolist())
+        # the minimum of S1 is the number of nodes that take part at all
+        assert s1_comp == int(s.any(axis=1).sum() + s.any(axis=0).sum())
+        checked += 1
+    assert checked >= 15
+
+
+def test_somm_literal_counts_the_cost_of_its_components():
+    """The counters of Protocol 2 on a general mask are the appendix's sums
+    over the components: C1 = 2 sum(|X_i| + |Y_i|), C2 = 3 sum |X_i| |Y_i|."""
+    m, k, n = 6, 5, 9
+    s = (u64(27, 1, m, n) % np.uint64(4) == 0).astype(np.uint8)
+    xq, yq = small_q(27, 2, m, k), small_q(27, 3, k, n)
+    cost = protocols.Cost()
+    protocols.somm_literal(co.share(xq, u64(27, 4, m, k)), co.share(yq, u64(27, 5, k, n)), s,
+                           u64(27, 6, m, k), u64(27, 7, k, n), u64(27, 8, m, k), u64(27, 9, k, n),
+                           u64(27, 10, m, n), cost)
+    comps = protocols.components(s)
+    assert cost.calls == len(comps)
+    assert cost.vectors == 2 * sum(len(r) + len(c) for r, c in comps)
+    assert cost.dot_products == 3 * sum(len(r) * len(c) for r, c in comps)
+
+
+def test_simm_literal_does_n_times_p_multiplications_per_product():
+    """Theorem 2: the column-by-row form spends p scalar multiplications per
+    non-zero of X, N p in all (times the three local products of Pi_MatMul),
+    and opens each non-zero of X once plus each used row of Y once."""
+    m, k, p = 5, 7, 4
+    s = (u64(28, 1, m, k) % np.uint64(3) == 0).astype(np.uint8)
+    s[:, 2] = 0                                      # a column nobody uses: its row of Y is never sent
+    xq, yq = small_q(28, 2, m, k), small_q(28, 3, k, p)
+    cost = protocols.Cost()
+    protocols.simm_literal(co.share(xq, u64(28, 4, m, k)), co.share(yq, u64(28, 5, k, p)), s,
+                           u64(28, 6, m, k), u64(28, 7, k, p), u64(28, 8, m, k), u64(28, 9, k, p),
+                           [u64(28, 100 + j, m, p) for j in range(k)], cost)
+    nnz = int(s.sum())
+    used_cols = int(s.any(axis=0).sum())
+    assert cost.scalar_mults == 3 * nnz * p
+    assert cost.opened_elems == nnz + used_cols * p
+    assert cost.calls == used_cols
