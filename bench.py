@@ -244,7 +244,8 @@ def cpu_baseline(layer, budget_s=20.0):
     return {"value": total_ops / total_s / 1e9, "unit": "Gop/s", "cores": cores, "kind": "oracle",
             "value_1core": one_ops / one_s / 1e9,
             "sample": "both parties' shares, %s; oracle's 3-product Eq. 1 loops counted as the "
-                      "2-product minimum; %.1f s of CPU time" % ("; ".join(notes), total_s),
+                      "2-product minimum; %.1f s of wall time on %d threads (%.0f thread-seconds)" %
+                      ("; ".join(notes), total_s, cores, total_s * cores),
             "matches_gpu": bool(ok)}
 
 
