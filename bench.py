@@ -298,6 +298,39 @@ def general_forms(ctx, timed):
     return out
 
 
+def weight_layouts(ctx, timed):
+    """SOMM of the LLaMA-7B gate projection (256 tokens, 52 of 344 blocks) with the weight side
+    stored row-major (d x f, kept neurons are 256-byte segments of every row) and neuron-major
+    (f x d, a kept neuron is one contiguous row): the indexed masking of the weights and the
+    share call, each with the full-size triple part indexed in the kernel."""
+    import torch
+    import paper_2505_07239_amd as comet
+    from workloads import masks, rng
+    m, k, nb, bs = 256, 4096, 344, 32
+    dev = torch.device("cuda:0")
+    mask = masks.clustered_block_mask(rng.BASE_SEED, 9100, nb, 0.15, 4.0)[None, :]
+    idx, n_dev = ctx.compact_mask(torch.from_numpy(mask).to(dev))
+    t_blk = int(n_dev.item())
+    n_act = t_blk * bs
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(79)
+    words = lambda *shape: torch.randint(-(2 ** 63), 2 ** 63 - 1, shape, dtype=torch.int64, device=dev,
+                                         generator=gen)
+    e, a, c = words(m, k), words(m, k), words(m, n_act)
+    z = torch.empty_like(c)
+    out = {}
+    for name, tr in (("row_major", False), ("neuron_major", True)):
+        y, b = (words(nb * bs, k), words(nb * bs, k)) if tr else (words(k, nb * bs), words(k, nb * bs))
+        g = torch.empty((n_act, k) if tr else (k, n_act), dtype=torch.int64, device=dev)
+        axis = comet.AXIS_ROWS if tr else comet.AXIS_COLS
+        t = timed(lambda: ctx.mask_share_gather(y, b, axis, bs, idx, n_dev, t_blk, out=g), reps=20)
+        out["somm_weights_%s_mask_GBs" % name] = 24.0 * k * n_act / t / 1e9
+        t = timed(lambda: ctx.somm_share(1, bs, idx, n_dev, t_blk, e, g, a, b, c, neuron_major=tr, out=z),
+                  reps=10)
+        out["somm_weights_%s_share_us" % name] = t * 1e6
+    return out
+
+
 def glue_steps(ctx, timed):
     """Shuffle steps, merge to full width and rescaling on a 4096 x 11008 matrix of words (the
     activations of 4096 tokens at the FFN width): achieved GB/s of algorithmic bytes."""
@@ -370,6 +403,7 @@ def micro(ctx, layer):
     out["compact_layer_mask_us"] = t * 1e6
     out.update(general_forms(ctx, timed))
     out.update(glue_steps(ctx, timed))
+    out.update(weight_layouts(ctx, timed))
     macs = ctx.probe_mfma_i8(1024, 2000)
     t = timed(lambda: ctx.probe_mfma_i8(1024, 2000), reps=5)
     out["mfma_i8_issue_TOPs"] = 2.0 * macs / t / 1e12

@@ -57,9 +57,15 @@ enum { COMET_AXIS_COLS = 0, COMET_AXIS_ROWS = 1 };
 /* operations known to comet_workspace_bytes() */
 enum { COMET_OP_COMPACT = 0, COMET_OP_SOMM = 1, COMET_OP_SIMM = 2 };
 
-/* flags of the share calls: the named triple share is passed at FULL size and
- * is indexed by blk_idx inside the kernel (otherwise it is already compact) */
-enum { COMET_FULL_A = 1, COMET_FULL_B = 2 };
+/* flags of the share calls.
+ * COMET_FULL_A / COMET_FULL_B: the named triple share is passed at FULL size
+ * and is indexed by blk_idx inside the kernel (otherwise it is already compact).
+ * COMET_WEIGHTS_NEURON_MAJOR (SOMM calls): the weight-side operands B_i and F
+ * are stored one ROW per neuron (n x k, the transpose of the k x n form), the
+ * layout in which a kept neuron is one contiguous run of k words in both
+ * projections of an FFN (the weights are permuted and stored once, offline,
+ * Sec. 4.2, so their layout is free to choose).  The result is the same. */
+enum { COMET_FULL_A = 1, COMET_FULL_B = 2, COMET_WEIGHTS_NEURON_MAJOR = 4 };
 
 /* ---- context ---------------------------------------------------------- */
 
@@ -130,6 +136,10 @@ int comet_compact_mask(comet_ctx* ctx, const uint8_t* mask, int64_t n_tok, int64
  *   B_i    : k x n_full when flags & COMET_FULL_B (kept columns are indexed in
  *            the kernel), else k x ld
  *   C_i,Z_i: m x ld   (compact; C = A B on the kept columns)
+ * With flags & COMET_WEIGHTS_NEURON_MAJOR, F is ld x k and B_i is n_full x k
+ * (COMET_FULL_B: kept rows are indexed in the kernel) or ld x k; k must then
+ * be even (COMET_EINVAL otherwise).  Calls with m <= 16 take the matrix-core
+ * kernel in this layout (the few-row kernel reads row-major weights).
  * ld = n_blk_cap * bs; column c of a compact operand is neuron
  * blk_idx[c / bs] * bs + c % bs.  Z_i must not alias any input.  A block id
  * that does not fit n_full is read as block 0 (the outputs it feeds are then

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libcomet_ring.so")
 
 AXIS_COLS, AXIS_ROWS = 0, 1
 OP_COMPACT, OP_SOMM, OP_SIMM = 0, 1, 2
-FULL_A, FULL_B = 1, 2
+FULL_A, FULL_B, WEIGHTS_NEURON_MAJOR = 1, 2, 4
 TUNE_GEMM_GRID, TUNE_GEMM_CHUNK, TUNE_GEMM_TILE, TUNE_SKINNY, TUNE_SKINNY_SLICES = 0, 1, 2, 3, 4
 
 EXPORTS = [
@@ -184,18 +184,20 @@ class Context:
 
     # ---- (3) output share ----
     def somm_share(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, e, f, a_i, b_i, c_i,
-                   b_full=True, out=None):
+                   b_full=True, neuron_major=False, out=None):
+        """``neuron_major``: ``f`` and ``b_i`` are stored one row per neuron (n x k)."""
         for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
             _words(t, nm)
         m, k = e.shape
-        n_full = b_i.shape[1] if b_full else 0
+        n_full = b_i.shape[0 if neuron_major else 1] if b_full else 0
         ld = n_blk_cap * bs
         out = torch.empty((m, ld), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
         need = workspace_bytes(OP_SOMM, m, k, ld, bs)
         ws = self.workspace(need)
         self._sync_stream()
+        flags = (FULL_B if b_full else 0) | (WEIGHTS_NEURON_MAJOR if neuron_major else 0)
         self._check(self.lib.comet_somm_share(self.h, party, m, k, n_full, bs, _ptr(blk_idx),
-                                              _ptr(n_blk_dev), n_blk_cap, FULL_B if b_full else 0,
+                                              _ptr(n_blk_dev), n_blk_cap, flags,
                                               _ptr(e), _ptr(f), _ptr(a_i), _ptr(b_i), _ptr(c_i),
                                               _ptr(out), _ptr(ws), need))
         return out
@@ -237,11 +239,11 @@ class Context:
         return out
 
     def somm_share_blocks(self, party, bs, blk_idx, blk_comp, n_blk_dev, n_blk_cap, row_comp, n_row_dev,
-                          e, f, a_i, b_i, c_i, b_full=True, out=None):
+                          e, f, a_i, b_i, c_i, b_full=True, neuron_major=False, out=None):
         for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
             _words(t, nm)
         m, k = e.shape
-        n_full = b_i.shape[1] if b_full else 0
+        n_full = b_i.shape[0 if neuron_major else 1] if b_full else 0
         ld = n_blk_cap * bs
         out = torch.empty((m, ld), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
         need = workspace_bytes(OP_SOMM, m, k, ld, bs)
@@ -249,7 +251,8 @@ class Context:
         self._sync_stream()
         self._check(self.lib.comet_somm_share_blocks(
             self.h, party, m, k, n_full, bs, _ptr(blk_idx), _ptr(blk_comp), _ptr(n_blk_dev), n_blk_cap,
-            _ptr(row_comp), _ptr(n_row_dev), FULL_B if b_full else 0, _ptr(e), _ptr(f), _ptr(a_i),
+            _ptr(row_comp), _ptr(n_row_dev),
+            (FULL_B if b_full else 0) | (WEIGHTS_NEURON_MAJOR if neuron_major else 0), _ptr(e), _ptr(f), _ptr(a_i),
             _ptr(b_i), _ptr(c_i), _ptr(out), _ptr(ws), need))
         return out
 

@@ -60,6 +60,8 @@ constexpr u64 DIGIT_BIAS = 0x0080808080808080ull;
 constexpr int GATHER_NONE = 0;   // rows are the compact contraction index
 constexpr int GATHER_POW2 = 1;   // block gather, bs a power of two >= 8
 constexpr int GATHER_ANY = 2;    // block gather, any bs
+// SOMM with neuron-major weights: B_i and F hold one row of k contiguous words per output column
+constexpr int WEIGHTS_TR = 3;
 
 __device__ __forceinline__ u64 to_digits(u64 x) { return (x + DIGIT_BIAS) ^ DIGIT_BIAS; }
 
@@ -368,7 +370,10 @@ struct Tile {
     static constexpr int SMEM = XSTAGES * XBYTES + WSTAGES * WBYTES;
     static constexpr int XVEC = XBYTES / 16 / GT;    // 16-byte units per thread per stage
     static constexpr int WTASK = BN * 4 / GT;        // (column, octet) tasks per thread per stage
-    static constexpr int VM_PER_STEP = XVEC + 8 * WTASK;   // vector-memory loads a thread issues per step
+    // vector-memory loads a thread issues per step: the LDS-DMA units plus, per weight task,
+    // eight 8-byte loads (or four 16-byte loads when the weights are neuron-major)
+    static constexpr int vm_per_step(bool pairs) { return XVEC + (pairs ? 4 : 8) * WTASK; }
+    static constexpr int VM_PER_STEP = vm_per_step(false);
     static_assert(WAVES_M * WAVES_N * 64 == GT, "four wavefronts per workgroup");
     static_assert(XVEC >= 1 && WTASK >= 1, "tile too small for the loader");
     static_assert(VM_PER_STEP < 63, "outstanding-load counter has 6 bits");
@@ -450,8 +455,14 @@ struct Loader {
                 const long st = block_start(p, blk);
                 bcol = (st < 0 ? 0 : st) + (col - blk * p.bs);
             }
-            wb[j] = p.B + bcol;
-            wf[j] = p.F + col;
+            if (GMODE == WEIGHTS_TR) {
+                // the column's own row of k words; the contraction index is then the word offset
+                wb[j] = p.B + bcol * p.ldb;
+                wf[j] = p.F + (long)col * p.ldf;
+            } else {
+                wb[j] = p.B + bcol;
+                wf[j] = p.F + col;
+            }
         }
         steps = nullptr;
         const int grp = threadIdx.x / T::BM, within = threadIdx.x % T::BM;
@@ -493,7 +504,7 @@ struct Loader {
     // stalls on the LDS reads that share its counter.
     __device__ __forceinline__ void begin(const GemmParams& p, int ks, int KS, int kc, int ks_limit) {
         resolve(ks, KS, h2, s2);
-        ld2 = (int)(h2 ? p.ldf : p.ldb);
+        ld2 = GMODE == WEIGHTS_TR ? 1 : (int)(h2 ? p.ldf : p.ldb);
         xs2 = xsrc + (size_t)(h2 * p.ks_cap + s2) * 16 * p.mpad * 16;
         if (GMODE == GATHER_POW2) {
             const int ksn = ks + 1 < ks_limit ? ks + 1 : ks_limit;
@@ -543,6 +554,19 @@ struct Loader {
         const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * J) / T::BN));
         const int k0 = s2 * KSTEP + oct * 8;
         const u64* src = h2 ? wf[J] : wb[J];
+        if constexpr (GMODE == WEIGHTS_TR) {
+            // Words E - 1 and E of the octet are neighbours in memory: one 16-byte load behind the
+            // split of the second (k is even and the rows are 16-byte aligned, host check).  Past
+            // the end of the contraction any valid pair will do: its activation digits are zero.
+            if constexpr ((E & 1) == 1) {
+                typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+                const int kp = (k0 + E) < kc ? (k0 + E - 1) : kc - 2;
+                const u64x2 v = *reinterpret_cast<const u64x2*>(src + kp);
+                wn[J][E - 1] = v.x;
+                wn[J][E] = v.y;
+            }
+            return;
+        }
         const int kk = (k0 + E) < kc ? (k0 + E) : kc - 1;
         int row = kk;
         if (GMODE == GATHER_POW2) {
@@ -699,7 +723,7 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
         ...);
     // The activation planes of the next step were requested one step ago; only the loads
     // issued during this step may still be in flight past this point.
-    wait_and_barrier<T::VM_PER_STEP>();
+    wait_and_barrier<T::vm_per_step(GMODE == WEIGHTS_TR)>();
 }
 
 template <class T, int KIND, int GMODE, int WM, int WN>
@@ -882,6 +906,7 @@ template <int WAVES_M, int WAVES_N, int WM, int WN>
 int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     void (*kern)(GemmParams) = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, GATHER_NONE>;
+    if (p.kind == KIND_SOMM && p.w_tr) kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, WEIGHTS_TR>;
     if (p.kind == KIND_SIMM) {
         if (!p.b_full)
             kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_NONE>;
@@ -969,7 +994,8 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         if (p.bs == (1 << sh)) p.bs_shift = sh;
 
     if (p.n_cap == 0) return COMET_OK;
-    if (p.m <= COMET_SKINNY_MAX_ROWS && ctx->skinny_mode != 1) return comet_launch_skinny(ctx, what, p);
+    // (the few-row kernel reads the weights along the output columns: row-major weights only)
+    if (p.m <= COMET_SKINNY_MAX_ROWS && ctx->skinny_mode != 1 && !p.w_tr) return comet_launch_skinny(ctx, what, p);
     // digit planes of [E | A'] and Z := C, one launch
     {
         unsigned gx = (unsigned)((p.ks_cap * 2 + 3) / 4);
@@ -1052,7 +1078,8 @@ int check_common(comet_ctx* ctx, const char* what, int party, int64_t m, int bs,
                  int flags, const void* const* ptrs, int n_ptrs, const int32_t* blk_idx) {
     if (party != 0 && party != 1) return comet_fail(ctx, COMET_EINVAL, "%s: party must be 0 or 1", what);
     if (m < 1 || bs < 1 || n_blk_cap < 0) return comet_fail(ctx, COMET_EINVAL, "%s: bad size", what);
-    if (flags & ~(COMET_FULL_A | COMET_FULL_B)) return comet_fail(ctx, COMET_EINVAL, "%s: unknown flag", what);
+    if (flags & ~(COMET_FULL_A | COMET_FULL_B | COMET_WEIGHTS_NEURON_MAJOR))
+        return comet_fail(ctx, COMET_EINVAL, "%s: unknown flag", what);
     for (int i = 0; i < n_ptrs; ++i) {
         if (!ptrs[i]) return comet_fail(ctx, COMET_EINVAL, "%s: null pointer (operand %d)", what, i);
         if (!comet_aligned16(ptrs[i]))
@@ -1087,6 +1114,11 @@ int somm_params(comet_ctx* ctx, const char* what, GemmParams& p, int party, int6
     p.A = (const u64*)A_i; p.lda = k; p.a_full = 0;
     p.B = (const u64*)B_i; p.b_full = (flags & COMET_FULL_B) ? 1 : 0; p.ldb = p.b_full ? n_full : ld;
     p.F = (const u64*)F; p.ldf = ld;
+    if (flags & COMET_WEIGHTS_NEURON_MAJOR) {
+        // B_i: n_full x k or ld x k, F: ld x k; the kernel reads pairs of contraction words
+        if (k & 1) return comet_fail(ctx, COMET_EINVAL, "%s: neuron-major weights need an even k", what);
+        p.w_tr = 1; p.ldb = k; p.ldf = k;
+    }
     p.C = (const u64*)C_i; p.Z = (u64*)Z_i; p.ldz = ld;
     return COMET_OK;
 }
@@ -1099,6 +1131,8 @@ int simm_params(comet_ctx* ctx, const char* what, GemmParams& p, int party, int6
     int rc = check_common(ctx, what, party, m, bs, n_blk_cap, flags, ptrs, 6, blk_idx);
     if (rc) return rc;
     if (n < 1 || k_full < 0) return comet_fail(ctx, COMET_EINVAL, "%s: bad size", what);
+    if (flags & COMET_WEIGHTS_NEURON_MAJOR)
+        return comet_fail(ctx, COMET_EINVAL, "%s: B_i and F of SIMM are neuron-major as they are (one row per neuron)", what);
     if (n > COMET_DIM_MAX || k_full > COMET_DIM_MAX) return comet_fail(ctx, COMET_ECAP, "%s: dimension beyond 2^24", what);
     const int64_t ld = (int64_t)n_blk_cap * bs;
     if ((flags & (COMET_FULL_A | COMET_FULL_B)) && ld > k_full)

@@ -48,10 +48,12 @@ def test_workspace_query_is_host_only(lib):
                                           ctypes.c_int64, ctypes.c_int]
     # SOMM, m = 256 (already a multiple of 128), k = 4096: 256 * 2 * 128 steps * 256 bytes of
     # digit planes, then the tile lists of the result-block form: a selector and twice
-    # (count + 4 x 26 tiles of 64 x 64) int32, rounded up to 256 bytes
+    # (count + 4 x 26 tiles of 64 x 64) int32, rounded up to 256 bytes, then the step lists of
+    # the row-set form: per 32-row tile a count, an offset and up to 128 steps, plus one offset
     planes = 256 * 2 * 128 * 256
     lists = ((2 * (4 * 26 + 1) + 1) * 4 + 255) // 256 * 256
-    assert lib.comet_workspace_bytes(1, 256, 4096, 1664, 32) == planes + lists
+    steps = ((8 * (128 + 2) + 1) * 4 + 255) // 256 * 256
+    assert lib.comet_workspace_bytes(1, 256, 4096, 1664, 32) == planes + lists + steps
     # small masks need no scratch, large ones do
     assert lib.comet_workspace_bytes(0, 1, 0, 344, 0) == 0
     assert lib.comet_workspace_bytes(0, 1, 0, 1 << 20, 0) > 0

@@ -260,6 +260,42 @@ def test_share_few_rows(ctx, kind, m, k, n, bs, keep, path):
         ctx.set_tuning(comet.TUNE_SKINNY, 0)
 
 
+@pytest.mark.parametrize("m,k,n,bs,keep", [
+    (1, 2, 4, 4, 1), (37, 70, 96, 3, 5), (130, 46, 200, 8, 9), (65, 34, 64, 32, 1),
+    (200, 300, 512, 16, 20), (9, 520, 600, 20, 17), (16, 778, 384, 32, 5), (256, 768, 3072, 32, 10)])
+@pytest.mark.parametrize("b_full", [True, False])
+def test_somm_neuron_major_weights(ctx, m, k, n, bs, keep, b_full):
+    """B_i and F stored one row per neuron (the transposes of the row-major operands) give
+    the same share, with B_i at full size (kept rows indexed in the kernel) or compact."""
+    case = _random_case("somm", m, k, n, bs, keep, 240 + m)
+    t = len(case.idx)
+    gi = torch.zeros(max(t, 1), dtype=torch.int32, device="cuda")
+    gi[:t] = torch.from_numpy(case.idx).cuda()
+    n_dev = torch.tensor([t], dtype=torch.int32, device="cuda")
+    f_t = np.ascontiguousarray(case.f.T)
+    for party in (0, 1):
+        say("neuron-major somm m=%d k=%d n=%d bs=%d b_full=%s party %d" % (m, k, n, bs, b_full, party))
+        b_i = case.b[party] if b_full else co.index_cols(case.b[party], case.idx, bs)
+        z = ctx.somm_share(party, bs, gi, n_dev, t, up(case.e), up(f_t), up(case.a[party]),
+                           up(np.ascontiguousarray(b_i.T)), up(case.c[party]), b_full=b_full,
+                           neuron_major=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(down(z), case.z[party])
+
+
+def test_somm_neuron_major_rejects_odd_k_and_simm(ctx):
+    import paper_2505_07239_amd as comet
+    case = _random_case("somm", 4, 7, 16, 4, 2, 260)
+    t = len(case.idx)
+    gi = torch.from_numpy(case.idx).cuda()
+    n_dev = torch.tensor([t], dtype=torch.int32, device="cuda")
+    with pytest.raises(comet.CometError) as ei:
+        ctx.somm_share(0, 4, gi, n_dev, t, up(case.e), up(np.ascontiguousarray(case.f.T)),
+                       up(case.a[0]), up(np.ascontiguousarray(case.b[0].T)), up(case.c[0]),
+                       neuron_major=True)
+    assert ei.value.code == -1
+
+
 @pytest.mark.parametrize("slices", [1, 3, 64, 5000])
 @pytest.mark.parametrize("kind", ["somm", "simm"])
 def test_share_few_rows_any_split(ctx, kind, slices):
