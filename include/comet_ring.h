@@ -203,6 +203,7 @@ int comet_components(comet_ctx* ctx, const uint8_t* mask, int64_t n_tok, int64_t
  * block are skipped.
  *   E, A_i : m_cap x k   (rows at or beyond *n_row_dev are ignored)
  *   F      : k x ld;  B_i: k x n_full when flags & COMET_FULL_B, else k x ld
+ *            (transposed, as in comet_somm_share, with COMET_WEIGHTS_NEURON_MAJOR)
  *   C_i,Z_i: m_cap x ld, ld = n_blk_cap * bs
  * n_row_dev may be null (then all m_cap rows take part).  Limits as for
  * comet_somm_share. */

@@ -167,7 +167,8 @@ def test_simm_per_token_row_sets(ctx, m, nb, bs, n, groups, per_tok, compact_tri
 # Protocol 2 with result blocks
 # ---------------------------------------------------------------------------
 
-def _somm_blocks_case(ctx, seed, m, k, nb, bs, groups, per_tok, spare_rows=0, spare_blocks=0, b_full=True):
+def _somm_blocks_case(ctx, seed, m, k, nb, bs, groups, per_tok, spare_rows=0, spare_blocks=0, b_full=True,
+                      neuron_major=False):
     n_full = nb * bs
     mask_blk = grouped_mask(seed, m, nb, groups, per_tok)
     s = np.repeat(mask_blk, bs, axis=1)
@@ -197,9 +198,12 @@ def _somm_blocks_case(ctx, seed, m, k, nb, bs, groups, per_tok, spare_rows=0, sp
         a_p = rows_padded(gen.a[party])
         c_p = cols_padded(rows_padded(gen.c[party]))
         b_arg = gen.b[party] if b_full else cols_padded(gen.b[party])
+        f_arg = f_c
+        if neuron_major:                      # the same weights stored one row per neuron
+            b_arg, f_arg = np.ascontiguousarray(b_arg.T), np.ascontiguousarray(f_c.T)
         z = ctx.somm_share_blocks(party, bs, comp["blk_idx"], comp["blk_comp"], comp["n_blk"], cap,
-                                  comp["row_comp"], comp["n_row"], up(e_p), up(f_c), up(a_p), up(b_arg),
-                                  up(c_p), b_full=b_full)
+                                  comp["row_comp"], comp["n_row"], up(e_p), up(f_arg), up(a_p), up(b_arg),
+                                  up(c_p), b_full=b_full, neuron_major=neuron_major)
         torch.cuda.synchronize()
         zz = down(z)
         want = gen.z[party][np.ix_(row_idx, cols)] if n_row and n_blk else np.zeros((n_row, n_blk * bs), np.uint64)
@@ -220,6 +224,17 @@ def _somm_blocks_case(ctx, seed, m, k, nb, bs, groups, per_tok, spare_rows=0, sp
 def test_somm_result_blocks(ctx, m, k, nb, bs, groups, per_tok):
     say("somm blocks m=%d k=%d nb=%d bs=%d groups=%d" % (m, k, nb, bs, groups))
     n_comp = _somm_blocks_case(ctx, 400 + m, m, k, nb, bs, groups, per_tok)
+    assert n_comp >= 1
+
+
+@pytest.mark.parametrize("m,k,nb,bs,groups,per_tok,b_full", [(8, 64, 24, 16, 3, 3, True),
+                                                             (40, 70, 20, 32, 4, 2, False),
+                                                             (200, 130, 16, 16, 3, 3, True),
+                                                             (300, 64, 40, 32, 5, 2, False)])
+def test_somm_result_blocks_neuron_major_weights(ctx, m, k, nb, bs, groups, per_tok, b_full):
+    say("somm blocks, neuron-major weights m=%d k=%d nb=%d bs=%d groups=%d" % (m, k, nb, bs, groups))
+    n_comp = _somm_blocks_case(ctx, 430 + m, m, k, nb, bs, groups, per_tok, spare_rows=3,
+                               spare_blocks=0 if b_full else 1, b_full=b_full, neuron_major=True)
     assert n_comp >= 1
 
 
