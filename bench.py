@@ -435,8 +435,8 @@ def main():
     ap.add_argument("--gemm-chunk", type=int, default=0, help="tuning sweep: scheduling slice length")
     ap.add_argument("--gemm-grid", type=int, default=0, help="tuning sweep: workgroups per launch")
     ap.add_argument("--gemm-tile", type=int, default=0, help="tuning sweep: 2 = 64x64 tile")
-    ap.add_argument("--skinny", type=int, default=0, help="tuning sweep: 1 = matrix cores even for m <= 16")
-    ap.add_argument("--skinny-slices", type=int, default=0, help="tuning sweep: contraction slices of the m <= 16 kernel")
+    ap.add_argument("--skinny", type=int, default=0, help="tuning sweep: 1 = matrix cores even for m <= 8")
+    ap.add_argument("--skinny-slices", type=int, default=0, help="tuning sweep: contraction slices of the m <= 8 kernel")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (both parties are simulated on it); "
@@ -530,7 +530,7 @@ def main():
                      "note": "algorithmic int8 ops: 36 digit products x 2 ops per ring MAC, two "
                              "products per party (2*m*k*n_act ring MACs per launch)"},
     }
-    if cfg.tokens <= 16 and not args.skinny:
+    if cfg.tokens <= 8 and not args.skinny:
         # a few activation rows: the share calls take the vector-ALU kernel, bound by reading the
         # two weight-side operands (B_i and F, kc x n words each) once per launch
         wbytes = sum(b["macs_per_launch"] for b in layer.mm) / len(layer.mm) / cfg.tokens * 8.0

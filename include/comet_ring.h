@@ -138,7 +138,7 @@ int comet_compact_mask(comet_ctx* ctx, const uint8_t* mask, int64_t n_tok, int64
  *   C_i,Z_i: m x ld   (compact; C = A B on the kept columns)
  * With flags & COMET_WEIGHTS_NEURON_MAJOR, F is ld x k and B_i is n_full x k
  * (COMET_FULL_B: kept rows are indexed in the kernel) or ld x k; k must then
- * be even (COMET_EINVAL otherwise).  Calls with m <= 16 take the matrix-core
+ * be even (COMET_EINVAL otherwise).  Calls with m <= 8 take the matrix-core
  * kernel in this layout (the few-row kernel reads row-major weights).
  * ld = n_blk_cap * bs; column c of a compact operand is neuron
  * blk_idx[c / bs] * bs + c % bs.  Z_i must not alias any input.  A block id
@@ -272,7 +272,7 @@ int comet_truncate_share(comet_ctx* ctx, int party, const uint64_t* z, uint64_t*
  *                         clamped to 256
  *   COMET_TUNE_GEMM_TILE: 2 forces the 64 x 64 output tile (two workgroups per
  *                         compute unit) whatever m is
- *   COMET_TUNE_SKINNY:    calls with m <= 16 normally take a vector-ALU kernel
+ *   COMET_TUNE_SKINNY:    calls with m <= 8 normally take a vector-ALU kernel
  *                         bound by reading the weights once; 1 sends them to the
  *                         matrix-core kernel like any other call
  *   COMET_TUNE_SKINNY_SLICES: pieces the stacked contraction is cut into by

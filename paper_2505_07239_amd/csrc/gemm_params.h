@@ -83,6 +83,8 @@ static __device__ __forceinline__ long block_start(const GemmParams& p, int blk)
 
 // Vector-ALU path for at most COMET_SKINNY_MAX_ROWS activation rows (decoding): computes the
 // whole share, Z := C included.  p.xp is the workspace of the matrix-core path, which is
-// always large enough.
-static const int COMET_SKINNY_MAX_ROWS = 16;
+// always large enough.  Up to 8 rows it reads the weights at the rate of a device copy; from 9
+// rows on its multiply-adds (three per row and weight word) take longer than the memory
+// traffic and the matrix-core kernel's 32-row tile is faster.
+static const int COMET_SKINNY_MAX_ROWS = 8;
 int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p);

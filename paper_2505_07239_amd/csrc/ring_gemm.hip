@@ -372,8 +372,13 @@ struct Tile {
     static constexpr int WTASK = BN * 4 / GT;        // (column, octet) tasks per thread per stage
     // vector-memory loads a thread issues per step: the LDS-DMA units plus, per weight task,
     // eight 8-byte loads (or four 16-byte loads when the weights are neuron-major)
-    static constexpr int vm_per_step(bool pairs) { return XVEC + (pairs ? 4 : 8) * WTASK; }
-    static constexpr int VM_PER_STEP = vm_per_step(false);
+    // and one load of a block id with the power-of-two row gather
+    static constexpr int vm_per_step(int gmode) {
+        return XVEC + (gmode == WEIGHTS_TR ? 4 : 8) * WTASK + (gmode == GATHER_POW2 ? WTASK : 0);
+    }
+    static constexpr int VM_PER_STEP = vm_per_step(GATHER_POW2);   // the largest
+    // two workgroups share a compute unit when one needs at most half of its registers and LDS
+    static constexpr int WG_PER_CU = (WM * WN == 1 && SMEM <= 80 * 1024) ? 2 : 1;
     static_assert(WAVES_M * WAVES_N * 64 == GT, "four wavefronts per workgroup");
     static_assert(XVEC >= 1 && WTASK >= 1, "tile too small for the loader");
     static_assert(VM_PER_STEP < 63, "outstanding-load counter has 6 bits");
@@ -417,8 +422,17 @@ __device__ __forceinline__ void wait_and_barrier() {
 template <class T, int KIND, int GMODE>
 struct Loader {
     static constexpr int W = T::WTASK;
-    const u64* wb[W];          // B_i at (row 0, this task's column), gather applied (SOMM)
-    const u64* wf[W];          // F   at (row 0, this task's column)
+    // Where this task's weight words are.  Without a row gather: pointers to (row 0, the task's
+    // column) of B_i (column gather applied for SOMM) and of F; neuron-major weights: to the
+    // column's own row of k words.  With a row gather (SIMM, full-size B_i): the byte offset of
+    // the column inside a row; the row is wave-uniform, so a load is "scalar row address +
+    // 32-bit lane offset" and the compiler has no per-load 64-bit vector addresses to keep
+    // (it would form all of a step's addresses ahead of time and run out of registers on the
+    // 32 x 256 tile).
+    static constexpr bool ROW_GATHER = GMODE == GATHER_POW2 || GMODE == GATHER_ANY;
+    unsigned cb[W], cf[W];
+    const u64* wb[W];
+    const u64* wf[W];
     const unsigned char* xsrc; // this thread's first 16-byte unit of step (h = 0, s = 0)
     u64 wn[W][8];              // weight words in flight (requested one step before they are split)
     u64 wa[W][8];              // digits of the weight words being staged for the next step
@@ -459,6 +473,9 @@ struct Loader {
                 // the column's own row of k words; the contraction index is then the word offset
                 wb[j] = p.B + bcol * p.ldb;
                 wf[j] = p.F + (long)col * p.ldf;
+            } else if (ROW_GATHER) {
+                cb[j] = (unsigned)bcol * 8u;      // columns stay below 2^24 (host check)
+                cf[j] = (unsigned)col * 8u;
             } else {
                 wb[j] = p.B + bcol;
                 wf[j] = p.F + col;
@@ -486,7 +503,13 @@ struct Loader {
         const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * j) / T::BN));
         const int k0 = s * KSTEP + oct * 8;
         const int kb = k0 <= kc - 8 ? k0 : kc - 8;
-        return p.blk_idx[h ? 0 : (kb >> p.bs_shift)];
+        // The index is the same for all lanes, but it is made a vector value on purpose (a zero
+        // the compiler cannot see through): the id then arrives through the vector-memory queue,
+        // in order with the weight words, instead of through a scalar load, whose counter is
+        // shared with the LDS reads -- every fragment read of the step would wait for it.
+        int lane_zero = 0;
+        asm volatile("" : "+v"(lane_zero));
+        return p.blk_idx[(h ? 0 : (kb >> p.bs_shift)) + lane_zero];
     }
 
     // first step of a segment: nothing has been requested ahead yet
@@ -553,8 +576,8 @@ struct Loader {
         // octet index is the same for all lanes of a wavefront
         const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * J) / T::BN));
         const int k0 = s2 * KSTEP + oct * 8;
-        const u64* src = h2 ? wf[J] : wb[J];
         if constexpr (GMODE == WEIGHTS_TR) {
+            const u64* src = h2 ? wf[J] : wb[J];
             // Words E - 1 and E of the octet are neighbours in memory: one 16-byte load behind the
             // split of the second (k is even and the rows are 16-byte aligned, host check).  Past
             // the end of the contraction any valid pair will do: its activation digits are zero.
@@ -578,9 +601,16 @@ struct Loader {
             const long st = block_start(p, blk);
             row = h2 ? kk : (int)(st < 0 ? 0 : st) + (kk - blk * p.bs);
         }
-        // every operand holds fewer than 2^31 words (host check), so the word offset fits 32 bits
-        const unsigned off = (unsigned)row * (unsigned)ld2;
-        wn[J][E] = src[off];
+        if constexpr (ROW_GATHER) {
+            // wave-uniform start of the row, then this lane's column
+            const char* rowp = reinterpret_cast<const char*>((h2 ? p.F : p.B) + (size_t)row * (size_t)ld2);
+            wn[J][E] = *reinterpret_cast<const u64*>(rowp + (h2 ? cf[J] : cb[J]));
+        } else {
+            // every operand holds fewer than 2^31 words (host check), so the word offset fits 32 bits
+            const u64* src = h2 ? wf[J] : wb[J];
+            const unsigned off = (unsigned)row * (unsigned)ld2;
+            wn[J][E] = src[off];
+        }
     }
 
     // quarter Q of the byte transpose of task J: Q = 0: low digits of words 0..3,
@@ -631,37 +661,53 @@ __device__ __forceinline__ v4i lds_frag(const unsigned char* p) {
     return *reinterpret_cast<const v4i*>(p);
 }
 
-// position of matrix instruction M inside a step: digit plane t of the activation side,
-// weight digit uu, wave sub-tiles (ii, j)
+// Position of matrix instruction M inside a step: activation digit t, weight digit uu, wave
+// sub-tiles (ii, j); the accumulator plane is t + uu <= 7.  The 36 digit pairs are walked with
+// the digit of the side that has MORE fragments per digit in the outer loop, so that this side's
+// fragments are live for one group of instructions only and the other side's are held for the
+// step: activation digit outermost for WM >= WN, weight digit outermost for WN > WM (measured on
+// the 32 x 256 tile with a row gather: 262 against 330 us on a 938 MB weight side).
 template <int WM, int WN>
 struct SlotMap {
-    static constexpr int per_t(int t) { return (8 - t) * WM * WN; }
-    static constexpr int t_of(int m) {
-        int t = 0;
-        while (m >= per_t(t)) { m -= per_t(t); ++t; }
-        return t;
+    static constexpr bool W_OUTER = WN > WM;
+    static constexpr int per_outer(int o) { return (8 - o) * WM * WN; }
+    static constexpr int outer_of(int m) {
+        int o = 0;
+        while (m >= per_outer(o)) { m -= per_outer(o); ++o; }
+        return o;
     }
-    static constexpr int in_t(int m) {
-        int t = 0;
-        while (m >= per_t(t)) { m -= per_t(t); ++t; }
+    static constexpr int in_outer(int m) {
+        int o = 0;
+        while (m >= per_outer(o)) { m -= per_outer(o); ++o; }
         return m;
     }
+    static constexpr int inner_of(int m) { return in_outer(m) / (WM * WN); }
+    static constexpr int t_of(int m) { return W_OUTER ? inner_of(m) : outer_of(m); }
+    static constexpr int u_of(int m) { return W_OUTER ? outer_of(m) : inner_of(m); }
+    static constexpr int i_of(int m) { return (in_outer(m) / WN) % WM; }
+    static constexpr int j_of(int m) { return in_outer(m) % WN; }
 };
 
-// Fragment reads of a step in consumption order: a[0][*], then bf[*][0..7] (all first used
-// with digit plane 0 of the activation side), then a[1..7][*].  slot(R) is the matrix
-// instruction after which read R is issued, -1 for the reads issued before the first one.
+// Fragment reads of a step: read R < 8 WM is activation fragment a[R / WM][R % WM], the others
+// are weight fragments bf[j][uu] with (uu, j) = ((R - 8 WM) / WN, (R - 8 WM) % WN).  slot(R) is
+// the matrix instruction after which read R is issued, READ_LEAD instructions ahead of the
+// first one that uses it; -1 for the reads issued before the first instruction.
 template <int WM, int WN>
 struct ReadMap {
+    using SM = SlotMap<WM, WN>;
     static constexpr int NR = 8 * (WM + WN);
+    static constexpr int NM = 36 * WM * WN;
     static constexpr int READ_LEAD = 8;
+    static constexpr bool is_a(int r) { return r < 8 * WM; }
     static constexpr int need(int r) {
-        if (r < WM) return r * WN;
-        if (r < WM + 8 * WN) return ((r - WM) / WN) * WM * WN + (r - WM) % WN;
-        const int t = 1 + (r - WM - 8 * WN) / WM, ii = (r - WM - 8 * WN) % WM;
-        int start = 0;
-        for (int q = 0; q < t; ++q) start += (8 - q) * WM * WN;
-        return start + ii * WN;
+        for (int m = 0; m < NM; ++m) {
+            if (is_a(r)) {
+                if (SM::t_of(m) == r / WM && SM::i_of(m) == r % WM) return m;
+            } else {
+                if (SM::u_of(m) == (r - 8 * WM) / WN && SM::j_of(m) == (r - 8 * WM) % WN) return m;
+            }
+        }
+        return NM;
     }
     static constexpr int slot(int r) { return need(r) - READ_LEAD < 0 ? -1 : need(r) - READ_LEAD; }
 };
@@ -690,14 +736,12 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
     using RM = ReadMap<WM, WN>;
     auto read_frag = [&](auto rc) {
         constexpr int R = decltype(rc)::value;
-        if constexpr (R < WM) {
-            a[0][R] = lds_frag(xs + a_off + (R * 32) * 16);
-        } else if constexpr (R < WM + 8 * WN) {
-            constexpr int uu = (R - WM) / WN, j = (R - WM) % WN;
-            bf[j][uu] = lds_frag(ws + b_off + (uu * 2 * T::BN + j * 32) * 16);
-        } else {
-            constexpr int t = 1 + (R - WM - 8 * WN) / WM, ii = (R - WM - 8 * WN) % WM;
+        if constexpr (RM::is_a(R)) {
+            constexpr int t = R / WM, ii = R % WM;
             a[t][ii] = lds_frag(xs + a_off + (t * 2 * T::BM + ii * 32) * 16);
+        } else {
+            constexpr int uu = (R - 8 * WM) / WN, j = (R - 8 * WM) % WN;
+            bf[j][uu] = lds_frag(ws + b_off + (uu * 2 * T::BN + j * 32) * 16);
         }
     };
     auto reads_at = [&](auto slot) {
@@ -711,8 +755,7 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
     (
         [&] {
             constexpr int M = Ms;
-            constexpr int t = SM::t_of(M), r = SM::in_t(M);
-            constexpr int uu = r / (WM * WN), ii = (r / WN) % WM, j = r % WN;
+            constexpr int t = SM::t_of(M), uu = SM::u_of(M), ii = SM::i_of(M), j = SM::j_of(M);
             acc[ii][j][t + uu] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t][ii], bf[j][uu],
                                                                         acc[ii][j][t + uu], 0, 0, 0);
             reads_at(std::integral_constant<int, M>{});
@@ -723,7 +766,7 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
         ...);
     // The activation planes of the next step were requested one step ago; only the loads
     // issued during this step may still be in flight past this point.
-    wait_and_barrier<T::vm_per_step(GMODE == WEIGHTS_TR)>();
+    wait_and_barrier<T::vm_per_step(GMODE)>();
 }
 
 template <class T, int KIND, int GMODE, int WM, int WN>
@@ -738,7 +781,7 @@ __device__ __forceinline__ void gemm_step(const GemmParams& p, Loader<T, KIND, G
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE>
-__global__ __launch_bounds__(GT, (WM * WN == 1 ? 2 : 1)) void ring_gemm_kernel(GemmParams p) {
+__global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) void ring_gemm_kernel(GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     // Three activation stages filled by LDS-DMA two steps ahead, as separate
     // arrays so that the compiler can tell a stage being filled from the one
@@ -919,7 +962,7 @@ int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
     const long kt = 2l * p.ks_cap;
     const long units_cap = tiles * kt;
     // a chip-sized grid, shrunk when there is too little work to share out
-    long grid = (ctx->num_cu / 8) * 8 * (WM * WN == 1 ? 2 : 1);
+    long grid = (ctx->num_cu / 8) * 8 * T::WG_PER_CU;
     if (grid < 8) grid = 8;
     const long want = (units_cap + 1) / 2;      // at least two contraction steps per workgroup
     if (want < grid) grid = want < 8 ? (want < 1 ? 1 : want) : (want / 8) * 8;

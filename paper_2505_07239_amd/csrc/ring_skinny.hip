@@ -3,7 +3,7 @@
 //
 //     [Z]_i = [C]_i + [ E | A' ] . [ B_i ; F ],   A' = A_i + party * E      (mod 2^64)
 //
-// With m <= 16 rows every weight word is used m times and the product is bound by reading the
+// With m <= 8 rows every weight word is used m times and the product is bound by reading the
 // two weight operands once from memory, not by arithmetic: the matrix cores would spend most of
 // their 32-row tiles on padding, and the digit split they need costs more vector work per
 // weight word than the m multiply-adds themselves.  So this path multiplies directly in the
@@ -212,7 +212,7 @@ void (*pick_kernel(int kind))(GemmParams, const u64*, int) {
 int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p) {
     if (p.m < 1 || p.m > COMET_SKINNY_MAX_ROWS)
         return comet_fail(ctx, COMET_EINVAL, "%s: row count outside the vector-ALU path", what);
-    const int MR = p.m <= 8 ? 8 : 16;
+    constexpr int MR = COMET_SKINNY_MAX_ROWS;
     u64* xs = reinterpret_cast<u64*>(p.xp);
     // k-major activation words and Z := C (the workspace of the matrix-core path, 2048 bytes per
     // contraction index, always covers the 2 * MR * 8 bytes per index used here)
@@ -241,8 +241,7 @@ int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p) {
     if (slices > 65535) slices = 65535;
     if (slices < 1) slices = 1;
     void (*kern)(GemmParams, const u64*, int);
-    if (MR == 8) kern = vec2 ? pick_kernel<8, 2>(p.kind) : pick_kernel<8, 1>(p.kind);
-    else kern = vec2 ? pick_kernel<16, 2>(p.kind) : pick_kernel<16, 1>(p.kind);
+    kern = vec2 ? pick_kernel<MR, 2>(p.kind) : pick_kernel<MR, 1>(p.kind);
     const bool timed = ctx->ev && ctx->ev_used + 2 <= ctx->ev_cap;
     if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], ctx->stream);
     hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)slices), dim3(ST), 0, ctx->stream, p,

@@ -245,7 +245,7 @@ def test_somm_result_blocks_spare_capacity_and_compact_triples(ctx, m):
 
 
 def test_somm_result_blocks_matrix_path_for_few_rows(ctx):
-    """m <= 16 with the vector-ALU path switched off: the matrix-core kernel's 32-row tile."""
+    """m <= 8 with the vector-ALU path switched off: the matrix-core kernel's 32-row tile."""
     import paper_2505_07239_amd as comet
     ctx.set_tuning(comet.TUNE_SKINNY, 1)
     try:

@@ -243,7 +243,7 @@ def test_share_ragged_shapes(ctx, kind, m, k, n, bs, keep):
     ("simm", 16, 384, 777, 32, 5)])
 @pytest.mark.parametrize("path", ["vector", "matrix"])
 def test_share_few_rows(ctx, kind, m, k, n, bs, keep, path):
-    """m <= 16 takes the vector-ALU kernel by default; the matrix-core kernel must give the
+    """m <= 8 takes the vector-ALU kernel by default; the matrix-core kernel must give the
     same bits for the same call (odd widths and odd bs reach the one-column-per-lane variant)."""
     import paper_2505_07239_amd as comet
     case = _random_case(kind, m, k, n, bs, keep, 140 + m)
