@@ -419,7 +419,7 @@ __device__ __forceinline__ void wait_and_barrier() {
 // beyond the kept width are never written back, and (b) the packed activation
 // planes hold zeros beyond the contraction length, so whatever the weight side
 // reads there is multiplied by zero.
-template <class T, int KIND, int GMODE>
+template <class T, int KIND, int GMODE, bool LISTED>
 struct Loader {
     static constexpr int W = T::WTASK;
     // Where this task's weight words are.  Without a row gather: pointers to (row 0, the task's
@@ -431,6 +431,7 @@ struct Loader {
     // 32 x 256 tile).
     static constexpr bool ROW_GATHER = GMODE == GATHER_POW2 || GMODE == GATHER_ANY;
     unsigned cb[W], cf[W];
+    uintptr_t wbase;           // row gather: B_i or F, whichever half the look-ahead step is in
     const u64* wb[W];
     const u64* wf[W];
     const unsigned char* xsrc; // this thread's first 16-byte unit of step (h = 0, s = 0)
@@ -494,7 +495,7 @@ struct Loader {
     __device__ __forceinline__ void resolve(int ks, int KS, int& h, int& s) const {
         h = ks >= KS ? 1 : 0;
         s = ks - h * KS;
-        if (steps) s = steps[s];
+        if constexpr (LISTED) s = steps[s];
     }
 
     __device__ __forceinline__ int gather_id(const GemmParams& p, int ks, int KS, int kc, int j) {
@@ -509,7 +510,7 @@ struct Loader {
         // shared with the LDS reads -- every fragment read of the step would wait for it.
         int lane_zero = 0;
         asm volatile("" : "+v"(lane_zero));
-        return p.blk_idx[(h ? 0 : (kb >> p.bs_shift)) + lane_zero];
+        return p.blk_idx[((kb >> p.bs_shift) & (h - 1)) + lane_zero];
     }
 
     // first step of a segment: nothing has been requested ahead yet
@@ -527,7 +528,16 @@ struct Loader {
     // stalls on the LDS reads that share its counter.
     __device__ __forceinline__ void begin(const GemmParams& p, int ks, int KS, int kc, int ks_limit) {
         resolve(ks, KS, h2, s2);
+        h2 = __builtin_amdgcn_readfirstlane(h2);
+        s2 = __builtin_amdgcn_readfirstlane(s2);
         ld2 = GMODE == WEIGHTS_TR ? 1 : (int)(h2 ? p.ldf : p.ldb);
+        if (ROW_GATHER) {
+            // both halves as one expression without control flow (h2 is 0 or 1): a branch inside a
+            // step makes the compiler lose track of which loads are still in flight, and it then
+            // waits for all of the previous step's at the first use
+            const uintptr_t b = reinterpret_cast<uintptr_t>(p.B), f = reinterpret_cast<uintptr_t>(p.F);
+            wbase = b + ((f - b) & (uintptr_t)0 - (uintptr_t)h2);
+        }
         xs2 = xsrc + (size_t)(h2 * p.ks_cap + s2) * 16 * p.mpad * 16;
         if (GMODE == GATHER_POW2) {
             const int ksn = ks + 1 < ks_limit ? ks + 1 : ks_limit;
@@ -540,7 +550,8 @@ struct Loader {
                 const int oct = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * j) / T::BN));
                 const int k0 = s2 * KSTEP + oct * 8;
                 const int kb = k0 <= kc - 8 ? k0 : kc - 8;
-                g0[j] = (int)((st < 0 || st + p.bs > p.full_extent) ? 0 : st) + (kb & (p.bs - 1));
+                const long ok = ((st < 0) | (st + p.bs > p.full_extent)) ? 0l : -1l;
+                g0[j] = (int)(st & ok) + (kb & (p.bs - 1));
                 gpend[j] = gather_id(p, ksn, KS, kc, j);
             }
         }
@@ -594,8 +605,9 @@ struct Loader {
         int row = kk;
         if (GMODE == GATHER_POW2) {
             // B_i rows are the kept neurons; bs is a power of two >= 8, so an octet of compact
-            // rows lies inside one block (g0 is its first row, set by begin())
-            row = h2 ? kk : g0[J] + E;
+            // rows lies inside one block (g0 is its first row, set by begin()); F rows are compact
+            const int rg = g0[J] + E;
+            row = rg + ((kk - rg) & -h2);
         } else if (GMODE == GATHER_ANY) {
             const int blk = kk / p.bs;
             const long st = block_start(p, blk);
@@ -603,8 +615,9 @@ struct Loader {
         }
         if constexpr (ROW_GATHER) {
             // wave-uniform start of the row, then this lane's column
-            const char* rowp = reinterpret_cast<const char*>((h2 ? p.F : p.B) + (size_t)row * (size_t)ld2);
-            wn[J][E] = *reinterpret_cast<const u64*>(rowp + (h2 ? cf[J] : cb[J]));
+            const char* rowp = reinterpret_cast<const char*>(wbase + (size_t)row * (size_t)ld2 * 8u);
+            const unsigned c = cb[J] + ((cf[J] - cb[J]) & (0u - (unsigned)h2));
+            wn[J][E] = *reinterpret_cast<const u64*>(rowp + c);
         } else {
             // every operand holds fewer than 2^31 words (host check), so the word offset fits 32 bits
             const u64* src = h2 ? wf[J] : wb[J];
@@ -717,13 +730,13 @@ struct ReadMap {
 // share of the look-ahead pieces (see Loader).  The scheduling fences keep the
 // compiler from regrouping them.  ks_next2 is clamped by the caller: past the
 // end of a segment the look-ahead work is redundant but harmless.
-template <class T, int KIND, int GMODE, int WM, int WN, int... Ms>
+template <class T, int KIND, int GMODE, bool LISTED, int WM, int WN, int... Ms>
 __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>, const GemmParams& p,
-                                               Loader<T, KIND, GMODE>& ld, v16i (&acc)[WM][WN][8],
+                                               Loader<T, KIND, GMODE, LISTED>& ld, v16i (&acc)[WM][WN][8],
                                                const unsigned char* xs, const unsigned char* ws,
                                                unsigned char* ws_next, unsigned char* xs_next2,
                                                int a_off, int b_off, int ks_next2, int ks_limit, int KS, int kc) {
-    using L = Loader<T, KIND, GMODE>;
+    using L = Loader<T, KIND, GMODE, LISTED>;
     using SM = SlotMap<WM, WN>;
     constexpr int NM = 36 * WM * WN;
     v4i bf[WN][8];
@@ -769,18 +782,18 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
     wait_and_barrier<T::vm_per_step(GMODE)>();
 }
 
-template <class T, int KIND, int GMODE, int WM, int WN>
-__device__ __forceinline__ void gemm_step(const GemmParams& p, Loader<T, KIND, GMODE>& ld,
+template <class T, int KIND, int GMODE, bool LISTED, int WM, int WN>
+__device__ __forceinline__ void gemm_step(const GemmParams& p, Loader<T, KIND, GMODE, LISTED>& ld,
                                           v16i (&acc)[WM][WN][8], const unsigned char* xs,
                                           const unsigned char* ws, unsigned char* ws_next,
                                           unsigned char* xs_next2, int a_off, int b_off,
                                           int ks_next2, int ks_limit, int KS, int kc) {
-    gemm_step_impl<T, KIND, GMODE, WM, WN>(std::make_integer_sequence<int, 36 * WM * WN>{}, p, ld, acc,
+    gemm_step_impl<T, KIND, GMODE, LISTED, WM, WN>(std::make_integer_sequence<int, 36 * WM * WN>{}, p, ld, acc,
                                            xs, ws, ws_next, xs_next2, a_off, b_off, ks_next2, ks_limit,
                                            KS, kc);
 }
 
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE>
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool LISTED>
 __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) void ring_gemm_kernel(GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     // Three activation stages filled by LDS-DMA two steps ahead, as separate
@@ -803,7 +816,7 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) vo
     // with result blocks only the listed tiles are computed
     const int tiles = p.row_comp ? p.tile_list[0] : tiles_m * tiles_n;
     // with per-token row sets only the listed steps of each row tile are computed
-    const bool listed = p.step_list != nullptr;
+    constexpr bool listed = LISTED;
     const long units = listed ? (long)tiles_n * 2 * p.step_off[tiles_m] : (long)tiles * KT;
     if (units == 0) return;
 
@@ -822,7 +835,7 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) vo
     const int a_off = (g * T::BM + wm * WM * 32 + r) * 16;
     const int b_off = (g * T::BN + wn * WN * 32 + r) * 16;
 
-    Loader<T, KIND, GMODE> ld;
+    Loader<T, KIND, GMODE, LISTED> ld;
 
     // Work units are ordered chunk-major: all tiles for contraction steps
     // [0, CH), then all tiles for [CH, 2 CH), ...  Workgroups that run side by
@@ -890,7 +903,7 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) vo
         // prologue: step ks0 staged, step ks0+1 in flight
         const int ks_last = ks0 + L - 1;
         {
-            using LD = Loader<T, KIND, GMODE>;
+            using LD = Loader<T, KIND, GMODE, LISTED>;
             ld.prime(p, ks0, KSt, kc);
             ld.begin(p, ks0, KSt, kc, ks_last);
             ld.template pieces<LD::P_DMA, false>(std::make_integer_sequence<int, LD::P_END - LD::P_DMA>{}, p, kc, xs0, wsm);
@@ -901,15 +914,15 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) vo
 
         for (int i = 0; i < L; i += 3) {
             const int k2 = ks0 + i + 2;
-            gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs0, wsm + (i & 1) * T::WBYTES,
+            gemm_step<T, KIND, GMODE, LISTED, WM, WN>(p, ld, acc, xs0, wsm + (i & 1) * T::WBYTES,
                                               wsm + ((i + 1) & 1) * T::WBYTES, xs2, a_off, b_off,
                                               k2 < ks_last ? k2 : ks_last, ks_last, KSt, kc);
             if (i + 1 < L)
-                gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs1, wsm + ((i + 1) & 1) * T::WBYTES,
+                gemm_step<T, KIND, GMODE, LISTED, WM, WN>(p, ld, acc, xs1, wsm + ((i + 1) & 1) * T::WBYTES,
                                                   wsm + (i & 1) * T::WBYTES, xs0, a_off, b_off,
                                                   k2 + 1 < ks_last ? k2 + 1 : ks_last, ks_last, KSt, kc);
             if (i + 2 < L)
-                gemm_step<T, KIND, GMODE, WM, WN>(p, ld, acc, xs2, wsm + (i & 1) * T::WBYTES,
+                gemm_step<T, KIND, GMODE, LISTED, WM, WN>(p, ld, acc, xs2, wsm + (i & 1) * T::WBYTES,
                                                   wsm + ((i + 1) & 1) * T::WBYTES, xs1, a_off, b_off,
                                                   k2 + 2 < ks_last ? k2 + 2 : ks_last, ks_last, KSt, kc);
         }
@@ -948,15 +961,29 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) vo
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
-    void (*kern)(GemmParams) = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, GATHER_NONE>;
-    if (p.kind == KIND_SOMM && p.w_tr) kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, WEIGHTS_TR>;
+    void (*kern)(GemmParams) = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, GATHER_NONE, false>;
+    if (p.kind == KIND_SOMM && p.w_tr) kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, WEIGHTS_TR, false>;
     if (p.kind == KIND_SIMM) {
         if (!p.b_full)
-            kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_NONE>;
+            kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_NONE, false>;
         else if (p.bs_shift >= 3)
-            kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_POW2>;
+            kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_POW2, false>;
         else
-            kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_ANY>;
+            kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_ANY, false>;
+    }
+    if (p.step_list) {
+        // per-token row sets (SIMM): the variants that walk a step list; only the tile shapes the
+        // dispatch picks for them exist
+        if constexpr (WM * WN == 2 && WAVES_N == 2) {
+            return comet_fail(ctx, COMET_EINVAL, "%s: no step-list variant of this tile shape", what);
+        } else {
+            if (!p.b_full)
+                kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_NONE, true>;
+            else if (p.bs_shift >= 3)
+                kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_POW2, true>;
+            else
+                kern = ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_ANY, true>;
+        }
     }
     const long tiles = (long)((p.m + T::BM - 1) / T::BM) * ((p.n_cap + T::BN - 1) / T::BN);
     const long kt = 2l * p.ks_cap;
