@@ -431,7 +431,13 @@ struct Loader {
     // 32 x 256 tile).
     static constexpr bool ROW_GATHER = GMODE == GATHER_POW2 || GMODE == GATHER_ANY;
     unsigned cb[W], cf[W];
-    uintptr_t wbase;           // row gather: B_i or F, whichever half the look-ahead step is in
+    const char* wbase;         // row gather: B_i or F, whichever half the look-ahead step is in
+    // GATHER_POW2: the eight rows of a task's octet are consecutive, so a task keeps a running
+    // (wave-uniform) row address that moves on by one row pitch per load, and the lane's column
+    // offset of the half it is in: a load is two scalar additions and the load itself
+    const char* wcur[W];
+    size_t wpitch;
+    unsigned csel[W];
     const u64* wb[W];
     const u64* wf[W];
     const unsigned char* xsrc; // this thread's first 16-byte unit of step (h = 0, s = 0)
@@ -535,8 +541,9 @@ struct Loader {
             // both halves as one expression without control flow (h2 is 0 or 1): a branch inside a
             // step makes the compiler lose track of which loads are still in flight, and it then
             // waits for all of the previous step's at the first use
-            const uintptr_t b = reinterpret_cast<uintptr_t>(p.B), f = reinterpret_cast<uintptr_t>(p.F);
-            wbase = b + ((f - b) & (uintptr_t)0 - (uintptr_t)h2);
+            // (a select between two pointers keeps their address space; going through integers
+            // would turn the loads into flat loads, which also count against the LDS counter)
+            wbase = reinterpret_cast<const char*>(h2 ? p.F : p.B);
         }
         xs2 = xsrc + (size_t)(h2 * p.ks_cap + s2) * 16 * p.mpad * 16;
         if (GMODE == GATHER_POW2) {
@@ -552,6 +559,13 @@ struct Loader {
                 const int kb = k0 <= kc - 8 ? k0 : kc - 8;
                 const long ok = ((st < 0) | (st + p.bs > p.full_extent)) ? 0l : -1l;
                 g0[j] = (int)(st & ok) + (kb & (p.bs - 1));
+                // first row of the octet: gathered in the B_i half, compact (kb) in the F half;
+                // kc is a multiple of 8 here, so an octet lies inside the contraction as a whole
+                // or not at all, and kb keeps the latter in range (its activation digits are zero)
+                const int r0 = g0[j] + ((kb - g0[j]) & -h2);
+                wpitch = (size_t)ld2 * 8u;
+                wcur[j] = wbase + (size_t)r0 * wpitch;
+                csel[j] = cb[j] + ((cf[j] - cb[j]) & (0u - (unsigned)h2));
                 gpend[j] = gather_id(p, ksn, KS, kc, j);
             }
         }
@@ -601,6 +615,12 @@ struct Loader {
             }
             return;
         }
+        if constexpr (GMODE == GATHER_POW2) {
+            const char* rowp = wcur[J];
+            wcur[J] += wpitch;
+            wn[J][E] = *reinterpret_cast<const u64*>(rowp + csel[J]);
+            return;
+        }
         const int kk = (k0 + E) < kc ? (k0 + E) : kc - 1;
         int row = kk;
         if (GMODE == GATHER_POW2) {
@@ -615,7 +635,7 @@ struct Loader {
         }
         if constexpr (ROW_GATHER) {
             // wave-uniform start of the row, then this lane's column
-            const char* rowp = reinterpret_cast<const char*>(wbase + (size_t)row * (size_t)ld2 * 8u);
+            const char* rowp = wbase + (size_t)row * (size_t)ld2 * 8u;
             const unsigned c = cb[J] + ((cf[J] - cb[J]) & (0u - (unsigned)h2));
             wn[J][E] = *reinterpret_cast<const u64*>(rowp + c);
         } else {
