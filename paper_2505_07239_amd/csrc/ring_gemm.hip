@@ -748,26 +748,20 @@ struct ReadMap {
 // One contraction step of a workgroup: 36 * WM * WN matrix instructions on the
 // fragments of activation stage xs and weight stage ws, each followed by its
 // share of the look-ahead pieces (see Loader).  The scheduling fences keep the
-// compiler from regrouping them.  The look-ahead pieces work on the step fixed by the
-// previous call's begin(); once this step's last load piece is out, begin() fixes the step
-// the NEXT call's pieces work on (ks_after, clamped by the caller: past the end of a segment
-// the look-ahead work is redundant but harmless).  That address arithmetic then runs behind
-// the last matrix instructions of this step instead of in front of the first ones of the next.
+// compiler from regrouping them.  ks_next2 is clamped by the caller: past the
+// end of a segment the look-ahead work is redundant but harmless.
 template <class T, int KIND, int GMODE, bool LISTED, int WM, int WN, int... Ms>
 __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>, const GemmParams& p,
                                                Loader<T, KIND, GMODE, LISTED>& ld, v16i (&acc)[WM][WN][8],
                                                const unsigned char* xs, const unsigned char* ws,
                                                unsigned char* ws_next, unsigned char* xs_next2,
-                                               int a_off, int b_off, int ks_after, int ks_limit, int KS, int kc) {
+                                               int a_off, int b_off, int ks_next2, int ks_limit, int KS, int kc) {
     using L = Loader<T, KIND, GMODE, LISTED>;
     using SM = SlotMap<WM, WN>;
     constexpr int NM = 36 * WM * WN;
     v4i bf[WN][8];
     v4i a[8][WM];
-    // first matrix instruction behind which every load piece of this step has been issued
-    constexpr int LAST_LOAD = L::P_TASK + L::PER_TASK * (L::W - 1) + 7;
-    constexpr int M_LOADS_DONE = (int)(((long)(LAST_LOAD + 1) * NM + L::P_END - 1) / L::P_END);
-    constexpr int M_BEGIN = M_LOADS_DONE > NM - 12 ? (M_LOADS_DONE < NM - 1 ? M_LOADS_DONE : NM - 1) : NM - 12;
+    ld.begin(p, ks_next2, KS, kc, ks_limit);
     // Fragment reads are issued in the order the matrix instructions consume them, each
     // READ_LEAD instructions ahead of its first use: the first instruction of a step then waits
     // for a handful of reads instead of the whole step's, and a fragment of a late digit plane
@@ -800,7 +794,6 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
             reads_at(std::integral_constant<int, M>{});
             constexpr int p0 = (int)((long)M * L::P_END / NM), p1 = (int)((long)(M + 1) * L::P_END / NM);
             ld.template pieces<p0, true>(std::make_integer_sequence<int, p1 - p0>{}, p, kc, xs_next2, ws_next);
-            if constexpr (M == M_BEGIN) ld.begin(p, ks_after, KS, kc, ks_limit);
             __builtin_amdgcn_sched_barrier(0);
         }(),
         ...);
@@ -814,9 +807,9 @@ __device__ __forceinline__ void gemm_step(const GemmParams& p, Loader<T, KIND, G
                                           v16i (&acc)[WM][WN][8], const unsigned char* xs,
                                           const unsigned char* ws, unsigned char* ws_next,
                                           unsigned char* xs_next2, int a_off, int b_off,
-                                          int ks_after, int ks_limit, int KS, int kc) {
+                                          int ks_next2, int ks_limit, int KS, int kc) {
     gemm_step_impl<T, KIND, GMODE, LISTED, WM, WN>(std::make_integer_sequence<int, 36 * WM * WN>{}, p, ld, acc,
-                                           xs, ws, ws_next, xs_next2, a_off, b_off, ks_after, ks_limit,
+                                           xs, ws, ws_next, xs_next2, a_off, b_off, ks_next2, ks_limit,
                                            KS, kc);
 }
 
@@ -936,13 +929,11 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) vo
             ld.template pieces<LD::P_DMA, false>(std::make_integer_sequence<int, LD::P_END - LD::P_DMA>{}, p, kc, xs0, wsm);
             ld.begin(p, ks0 + 1 < ks_last ? ks0 + 1 : ks_last, KSt, kc, ks_last);
             ld.template pieces<LD::P_DMA, true>(std::make_integer_sequence<int, LD::P_END - LD::P_DMA>{}, p, kc, xs1, wsm);
-            // the pieces of the first step of the loop work on step ks0 + 2
-            ld.begin(p, ks0 + 2 < ks_last ? ks0 + 2 : ks_last, KSt, kc, ks_last);
         }
         wait_and_barrier<0>();
 
         for (int i = 0; i < L; i += 3) {
-            const int k2 = ks0 + i + 3;     // what the pieces of the step after the current one work on
+            const int k2 = ks0 + i + 2;
             gemm_step<T, KIND, GMODE, LISTED, WM, WN>(p, ld, acc, xs0, wsm + (i & 1) * T::WBYTES,
                                               wsm + ((i + 1) & 1) * T::WBYTES, xs2, a_off, b_off,
                                               k2 < ks_last ? k2 : ks_last, ks_last, KSt, kc);
