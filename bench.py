@@ -36,7 +36,7 @@ INT8_OPS_PER_RING_MAC = 72   # 36 digit products, 2 ops each
 # runs of this file: FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for
 # the copy probe of known size in the same run; the summaries are under profiles/.  None until
 # measured for that workload.
-GEMM_TRAFFIC_BYTES = {"c3": 199413607, "c4": 987125151}
+GEMM_TRAFFIC_BYTES = {"c3": 199303800, "c4": 987125342}
 
 
 def log(msg):
