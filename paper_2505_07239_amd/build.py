@@ -4,12 +4,16 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcomet_ring.so")
-SOURCES = ["ctx.hip", "elementwise.hip", "compact.hip", "ring_gemm.hip", "ring_skinny.hip", "components.hip", "glue.hip", "probe.hip"]
+# the variants of the matrix-core kernel come first: they take longest to compile
+SOURCES = ["ring_gemm_tile_32x256.hip", "ring_gemm_tile_32x256_listed.hip", "ring_gemm_tile_128x64.hip",
+           "ring_gemm_tile_64x64.hip", "ring_gemm_tile_64x64_listed.hip", "ring_gemm.hip",
+           "ring_skinny.hip", "ctx.hip", "elementwise.hip", "compact.hip", "components.hip", "glue.hip", "probe.hip"]
 FLAGS = ["-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-fvisibility=default",
          # the LDS-DMA helper names M0 as clobbered, which clang flags as a reserved register
          "-Wno-inline-asm",
@@ -20,10 +24,9 @@ FLAGS = ["-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-fvisibility=de
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objs = []
     build_dir = os.path.join(HERE, "_build")
     os.makedirs(build_dir, exist_ok=True)
-    for src in SOURCES:
+    def compile_one(src):
         obj = os.path.join(build_dir, src.replace(".hip", ".o"))
         cmd = [hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
@@ -34,7 +37,12 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError("hipcc failed on %s:\n%s" % (src, err))
         if err.strip() and verbose:
             print(err, file=sys.stderr)
-        objs.append(obj)
+        return obj
+
+    # translation units compile side by side (hipcc is a subprocess: threads are enough)
+    jobs = max(1, min(len(SOURCES), int(os.environ.get("MAX_JOBS", "0")) or (os.cpu_count() or 1), 8))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:

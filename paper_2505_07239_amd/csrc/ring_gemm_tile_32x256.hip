@@ -1,0 +1,5 @@
+// The 32 x 256 output tile of the int8 matrix-core kernel: the variants without a step list
+// (see ring_gemm_kernel.h).
+#include "ring_gemm_kernel.h"
+
+template comet_gemm::GemmKernel comet_gemm::gemm_kernel_for<1, 4, 1, 2, false>(const GemmParams&);
