@@ -242,9 +242,8 @@ struct Loader {
 
     // Fix the step the following dma / load pieces work on.  Steps are visited in
     // order (ks, then ks + 1 capped at ks_limit), which lets the block id of the
-    // next step be requested here, a whole step before it is needed: the scalar
-    // load returns long before the next call consumes it, so consuming it never
-    // stalls on the LDS reads that share its counter.
+    // next step be requested here, a whole step before it is needed (see gather_id()
+    // for why that request is a vector load).
     __device__ __forceinline__ void begin(const GemmParams& p, int ks, int KS, int kc, int ks_limit) {
         resolve(ks, KS, h2, s2);
         h2 = __builtin_amdgcn_readfirstlane(h2);
