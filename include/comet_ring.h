@@ -9,10 +9,12 @@
  *
  * Conventions that hold for every call unless stated otherwise
  *   - every matrix / vector pointer is a DEVICE pointer owned by the caller,
- *     16-byte aligned, dense row-major, elements are uint64_t taken mod 2^64;
+ *     16-byte aligned, dense row-major, elements are uint64_t taken mod 2^64
+ *     (int32 index lists and counts: 4-byte aligned; byte masks: any alignment);
  *   - the library never allocates or frees device memory and never frees or
  *     retains caller memory; scratch space comes in through (ws, ws_bytes),
- *     sized with comet_workspace_bytes(), and may be reused between calls;
+ *     sized with comet_workspace_bytes(), must be 256-byte aligned (COMET_EALIGN
+ *     otherwise) and may be reused between calls that do not overlap in time;
  *   - calls enqueue work on the context's stream and return without waiting;
  *     buffers must stay valid until that work has run;
  *   - the predicted sparsity distribution is a plaintext list of active
@@ -45,7 +47,7 @@ typedef struct comet_ctx comet_ctx;
 enum {
     COMET_OK = 0,
     COMET_EINVAL = -1,     /* null pointer, negative or inconsistent size, bad enum      */
-    COMET_EALIGN = -2,     /* a pointer is not 16-byte aligned                           */
+    COMET_EALIGN = -2,     /* an operand is not 16-byte, a workspace not 256-byte aligned */
     COMET_ECAP = -3,       /* size beyond what the kernels index (see each call)         */
     COMET_EDEVICE = -4,    /* no such device / wrong architecture / HIP runtime failure  */
     COMET_EWORKSPACE = -5  /* ws is NULL or smaller than comet_workspace_bytes() says    */
@@ -89,7 +91,8 @@ size_t comet_workspace_bytes(int op, int64_t m, int64_t k, int64_t n, int bs);
 /* ---- (1) mask and open shares: Sec. 2.1 multiplication, Sec. 5.1 -------- */
 
 /* [D]_i = [X]_i - [A]_i, elementwise over n_elems words: the masked share a
- * party sends to the other one.  d_i may alias x_i or a_i. */
+ * party sends to the other one.  d_i may be the same buffer as x_i or a_i
+ * (exactly the same address; partially overlapping buffers are not allowed). */
 int comet_mask_share(comet_ctx* ctx, const uint64_t* x_i, const uint64_t* a_i,
                      uint64_t* d_i, size_t n_elems);
 
@@ -109,7 +112,7 @@ int comet_mask_share_gather(comet_ctx* ctx, const uint64_t* w_i, const uint64_t*
 
 /* E = [D]_0 + [D]_1: reconstruction of the masked value after the exchange
  * (both parties live in one process here, so the exchange is this add).
- * e may alias d_0 or d_1. */
+ * e may be the same buffer as d_0 or d_1 (same address, no partial overlap). */
 int comet_open(comet_ctx* ctx, const uint64_t* d_0, const uint64_t* d_1, uint64_t* e,
                size_t n_elems);
 
@@ -144,8 +147,8 @@ int comet_compact_mask(comet_ctx* ctx, const uint8_t* mask, int64_t n_tok, int64
  * blk_idx[c / bs] * bs + c % bs.  Z_i must not alias any input.  A block id
  * that does not fit n_full is read as block 0 (the outputs it feeds are then
  * meaningless; no access ever leaves the operands).
- * Limits: 1 <= m, k, bs; m < 2^23; k, ld, n_full < 2^24; F and B_i hold fewer
- * than 2^31 words each. */
+ * Limits: 1 <= m, k, bs; m <= 2^22 - 128; k, ld, n_full < 2^24; F and B_i hold
+ * fewer than 2^31 words each (COMET_ECAP beyond them). */
 int comet_somm_share(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_full, int bs,
                      const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap, int flags,
                      const uint64_t* E, const uint64_t* F, const uint64_t* A_i,
@@ -163,8 +166,8 @@ int comet_somm_share(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_
  * ld = n_blk_cap * bs; only the first n_blk * bs columns of E / rows of F are
  * contracted.  Z_i must not alias any input.  A block id that does not fit
  * k_full is read as block 0 (see comet_somm_share).
- * Limits: 1 <= m, n, bs; m < 2^23; n, ld, k_full < 2^24; F and B_i hold fewer
- * than 2^31 words each. */
+ * Limits: 1 <= m, n, bs; m <= 2^22 - 128; n, ld, k_full < 2^24; F and B_i hold
+ * fewer than 2^31 words each (COMET_ECAP beyond them). */
 int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64_t n, int bs,
                      const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap, int flags,
                      const uint64_t* E, const uint64_t* F, const uint64_t* A_i,

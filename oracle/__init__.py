@@ -34,6 +34,29 @@ def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
         _lib = ctypes.CDLL(build())
+        vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        # every entry point with its C prototype, so that sizes travel at their declared width
+        protos = {
+            "co_encode": [vp, vp, sz, i], "co_decode": [vp, vp, sz, i],
+            "co_share": [vp, vp, vp, vp, sz], "co_reconstruct": [vp, vp, vp, sz],
+            "co_ring_matmul": [vp, vp, vp, i, i, i],
+            "co_ring_matmul_rows": [vp, vp, vp, i, i, i, i, i],
+            "co_mask_share": [vp, vp, vp, sz], "co_open": [vp, vp, vp, sz],
+            "co_compact_mask": [vp, i, i, vp],
+            "co_index_cols": [vp, i, i, vp, i, i, vp], "co_index_rows": [vp, i, i, vp, i, i, vp],
+            "co_beaver_share": [i, vp, vp, vp, vp, vp, vp, vp, i, i, i],
+            "co_beaver_share_rows": [i, vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i],
+            "co_beaver_share_at": [i, vp, vp, vp, vp, vp, i, i, i, i, i],
+            "co_beaver_share_blocks": [i, vp, vp, vp, vp, vp, vp, vp, vp, i, i, i],
+            "co_beaver_share_sparse_input": [i, vp, vp, vp, vp, vp, vp, vp, i, i, i],
+            "co_permute_mask": [vp, vp, vp, vp, i, i, i, i],
+            "co_scatter_cols": [vp, vp, i, i, vp, i, i],
+            "co_truncate_share": [i, vp, vp, sz, i],
+        }
+        for name, args in protos.items():
+            fn = getattr(_lib, name)
+            fn.argtypes = args
+            fn.restype = None
         _lib.co_compact_mask.restype = ctypes.c_int
         _lib.co_beaver_share_at.restype = ctypes.c_uint64
     return _lib

@@ -122,24 +122,33 @@ def components(s: np.ndarray) -> List[Tuple[np.ndarray, np.ndarray]]:
     return out
 
 
+def _rows(mat, idx):
+    return co.index_rows(mat, np.ascontiguousarray(idx, dtype=np.int32), 1)
+
+
+def _cols(mat, idx):
+    return co.index_cols(mat, np.ascontiguousarray(idx, dtype=np.int32), 1)
+
+
 def somm_literal(x, y, s, a, b, a_split, b_split, c_split, cost: Optional[Cost] = None):
-    """Protocol 2.  ``x``, ``y``: share pairs (``m x k``, ``k x n``); ``s``: 0/1
-    ``m x n``.  Triple material ``a`` (m x k), ``b`` (k x n) and the splitting
-    randomness are given at full shape; the component on rows ``I_x`` and
-    columns ``I_y`` uses their restriction to ``I_x`` / ``I_y`` with
-    ``C = A[I_x] B[:, I_y]``.  Returns full-size ``m x n`` shares that are
-    zero outside the computed blocks (Merge)."""
+    """Protocol 2 (Sec. 5.1).  ``x``, ``y``: share pairs (``m x k``, ``k x n``); ``s``: 0/1
+    ``m x n``, the sparsity distribution of ``X Y``.
+
+    The requested outputs are grouped by connected component of the bipartite graph of ``s``.
+    For a component with rows ``I_x`` and columns ``I_y`` the result block is
+    ``Z[I_x, I_y] = Pi_MatMul(X[I_x, :], Y[:, I_y])`` with a triple of its own; the output is zero
+    everywhere else.  Triple material ``a`` (m x k), ``b`` (k x n) and the splitting randomness
+    are given at full shape; a component's triple is their restriction to ``I_x`` / ``I_y`` with
+    ``C = A[I_x, :] B[:, I_y]``.  Returns the two parties' full-size ``m x n`` shares."""
     m, n = np.asarray(s).shape
     z = [np.zeros((m, n), dtype=np.uint64) for _ in (0, 1)]
-    for i_x, i_y in components(s):                                   # DFS, then one Pi_MatMul per component
-        xt = [co.index_rows(x[i], i_x, 1) for i in (0, 1)]            # IndexRows
-        yt = [co.index_cols(y[i], i_y, 1) for i in (0, 1)]            # IndexCols
-        t = ttp_triple(co.index_rows(a, i_x, 1), co.index_cols(b, i_y, 1),
-                       co.index_rows(a_split, i_x, 1), co.index_cols(b_split, i_y, 1),
-                       co.index_cols(co.index_rows(c_split, i_x, 1), i_y, 1))
-        r = pi_matmul(xt, yt, t, cost)                                # Pi_MatMul on the sub-matrices
-        for i in (0, 1):                                              # Merge
-            z[i][np.ix_(i_x, i_y)] = r[i]
+    for i_x, i_y in components(s):
+        triple = ttp_triple(_rows(a, i_x), _cols(b, i_y), _rows(a_split, i_x), _cols(b_split, i_y),
+                            _cols(_rows(c_split, i_x), i_y))
+        block = pi_matmul([_rows(x[i], i_x) for i in (0, 1)], [_cols(y[i], i_y) for i in (0, 1)],
+                          triple, cost)
+        for i in (0, 1):
+            z[i][np.ix_(i_x, i_y)] = block[i]
     return tuple(z)
 
 
@@ -148,30 +157,30 @@ def somm_literal(x, y, s, a, b, a_split, b_split, c_split, cost: Optional[Cost] 
 # ---------------------------------------------------------------------------
 
 def simm_literal(x, y, s, a, b, a_split, b_split, c_split_cols, cost: Optional[Cost] = None):
-    """Protocol 3.  ``x``: shares of the ``m x k`` sparse-input matrix, ``s``:
-    its 0/1 sparsity distribution, ``y``: shares of ``k x p``.
-    ``c_split_cols[j]`` is the ``m x p`` randomness splitting the triple of
-    column ``j`` (rows outside ``R_j`` unused).  Returns ``m x p`` shares."""
+    """Protocol 3 (Sec. 5.2).  ``x``: shares of the ``m x k`` sparse-input matrix, ``s``: its
+    0/1 sparsity distribution, ``y``: shares of ``k x p``.
+
+    Column by row: ``Z = sum_j X[:, j] Y[j, :]``, and column ``j`` of ``X`` is non-zero only on
+    its row set ``R_j = {r : s[r, j] != 0}``.  So every column with a non-empty ``R_j`` adds the
+    outer product ``Pi_MatMul(X[R_j, j], Y[j, :])`` (an ``|R_j| x 1`` by ``1 x p`` product with a
+    triple of its own) onto rows ``R_j`` of the output; a row of ``Y`` is masked once.
+    ``c_split_cols[j]`` is the ``m x p`` randomness that splits the triple of column ``j``
+    (rows outside ``R_j`` unused).  Returns the two parties' ``m x p`` shares."""
     s = np.asarray(s) != 0
     m, k = s.shape
     p = y[0].shape[1]
     z = [np.zeros((m, p), dtype=np.uint64) for _ in (0, 1)]
-    pairs = []                                                        # non-zero columns j and their row sets R_j
     for j in range(k):
-        r_j = np.nonzero(s[:, j])[0].astype(np.int32)
-        if len(r_j):
-            pairs.append((j, r_j))
-    for j, r_j in pairs:
-        jj = np.array([j], dtype=np.int32)
-        x2 = [co.index_rows(co.index_cols(x[i], jj, 1), r_j, 1) for i in (0, 1)]   # IndexCol, IndexRows
-        yj = [co.index_rows(y[i], jj, 1) for i in (0, 1)]                          # IndexRow
-        t = ttp_triple(co.index_rows(co.index_cols(a, jj, 1), r_j, 1), co.index_rows(b, jj, 1),
-                       co.index_rows(co.index_cols(a_split, jj, 1), r_j, 1),
-                       co.index_rows(b_split, jj, 1),
-                       co.index_rows(np.ascontiguousarray(c_split_cols[j]), r_j, 1))
-        r = pi_matmul(x2, yj, t, cost)                                # Pi_MatMul: an outer product
-        for i in (0, 1):                                              # Merge&Sum
-            z[i][r_j, :] += r[i]
+        r_j = np.nonzero(s[:, j])[0]
+        if not len(r_j):
+            continue
+        col = lambda mat: _rows(_cols(mat, [j]), r_j)          # mat[R_j, j] as |R_j| x 1
+        row = lambda mat: _rows(mat, [j])                      # mat[j, :]   as 1 x p
+        triple = ttp_triple(col(a), row(b), col(a_split), row(b_split),
+                            _rows(np.ascontiguousarray(c_split_cols[j]), r_j))
+        outer = pi_matmul([col(x[i]) for i in (0, 1)], [row(y[i]) for i in (0, 1)], triple, cost)
+        for i in (0, 1):
+            z[i][r_j, :] += outer[i]
     return tuple(z)
 
 

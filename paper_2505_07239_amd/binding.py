@@ -97,6 +97,29 @@ def _words(t: torch.Tensor, what: str) -> torch.Tensor:
     return t
 
 
+def _index_list(blk_idx, n_blk_dev, n_blk_cap: int, required: bool):
+    """The block list of a share / masking call: int32 on the GPU, at least n_blk_cap entries."""
+    if n_blk_cap < 0:
+        raise ValueError("n_blk_cap must not be negative")
+    if blk_idx is None:
+        if required:
+            raise ValueError("blk_idx is required when an operand is indexed inside the kernel")
+    else:
+        if blk_idx.dtype != torch.int32 or not blk_idx.is_cuda or not blk_idx.is_contiguous():
+            raise TypeError("blk_idx must be a contiguous int32 tensor on the GPU")
+        # with the count on the device only its first *n_blk_dev entries are read
+        if n_blk_dev is None and blk_idx.numel() < n_blk_cap:
+            raise ValueError("blk_idx holds %d entries, n_blk_cap is %d" % (blk_idx.numel(), n_blk_cap))
+    if n_blk_dev is not None:
+        if n_blk_dev.dtype != torch.int32 or not n_blk_dev.is_cuda or n_blk_dev.numel() < 1:
+            raise TypeError("n_blk_dev must be an int32 tensor on the GPU")
+
+
+def _shape(t: torch.Tensor, shape, what: str):
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (what, tuple(t.shape), tuple(shape)))
+
+
 class Context:
     """One library context on one device; calls run on torch's current stream."""
 
@@ -141,6 +164,8 @@ class Context:
     def mask_share(self, x_i, a_i, out=None):
         _words(x_i, "x_i"), _words(a_i, "a_i")
         out = torch.empty_like(x_i) if out is None else _words(out, "out")
+        if a_i.numel() != x_i.numel() or out.numel() != x_i.numel():
+            raise ValueError("x_i, a_i and out must hold the same number of words")
         self._sync_stream()
         self._check(self.lib.comet_mask_share(self.h, _ptr(x_i), _ptr(a_i), _ptr(out), x_i.numel()))
         return out
@@ -148,6 +173,8 @@ class Context:
     def open(self, d_0, d_1, out=None):
         _words(d_0, "d_0"), _words(d_1, "d_1")
         out = torch.empty_like(d_0) if out is None else _words(out, "out")
+        if d_1.numel() != d_0.numel() or out.numel() != d_0.numel():
+            raise ValueError("d_0, d_1 and out must hold the same number of words")
         self._sync_stream()
         self._check(self.lib.comet_open(self.h, _ptr(d_0), _ptr(d_1), _ptr(out), d_0.numel()))
         return out
@@ -158,6 +185,8 @@ class Context:
         ld = n_blk_cap * bs
         shape = (rows, ld) if axis == AXIS_COLS else (ld, cols)
         out = torch.empty(shape, dtype=torch.int64, device=w_i.device) if out is None else _words(out, "out")
+        _shape(b_i, (rows, cols), "b_i"), _shape(out, shape, "out")
+        _index_list(blk_idx, n_blk_dev, n_blk_cap, True)
         self._sync_stream()
         self._check(self.lib.comet_mask_share_gather(self.h, _ptr(w_i), _ptr(b_i), _ptr(out), rows,
                                                      cols, axis, bs, _ptr(blk_idx), _ptr(n_blk_dev),
@@ -192,6 +221,8 @@ class Context:
         n_full = b_i.shape[0 if neuron_major else 1] if b_full else 0
         ld = n_blk_cap * bs
         out = torch.empty((m, ld), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        self._somm_shapes(m, k, ld, n_full, f, a_i, b_i, c_i, out, b_full, neuron_major)
+        _index_list(blk_idx, n_blk_dev, n_blk_cap, b_full)
         need = workspace_bytes(OP_SOMM, m, k, ld, bs)
         ws = self.workspace(need)
         self._sync_stream()
@@ -202,6 +233,20 @@ class Context:
                                               _ptr(out), _ptr(ws), need))
         return out
 
+    @staticmethod
+    def _somm_shapes(m, k, ld, n_full, f, a_i, b_i, c_i, out, b_full, neuron_major):
+        tr = (lambda r, c: (c, r)) if neuron_major else (lambda r, c: (r, c))
+        _shape(f, tr(k, ld), "F"), _shape(a_i, (m, k), "A_i")
+        _shape(b_i, tr(k, n_full if b_full else ld), "B_i")
+        _shape(c_i, (m, ld), "C_i"), _shape(out, (m, ld), "out")
+
+    @staticmethod
+    def _simm_shapes(m, n, ld, k_full, e, f, a_i, b_i, c_i, out, a_full, b_full):
+        _shape(e, (m, ld), "E"), _shape(f, (ld, n), "F")
+        _shape(a_i, (m, k_full if a_full else ld), "A_i")
+        _shape(b_i, (k_full if b_full else ld, n), "B_i")
+        _shape(c_i, (m, n), "C_i"), _shape(out, (m, n), "out")
+
     def simm_share(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, e, f, a_i, b_i, c_i,
                    a_full=True, b_full=True, out=None):
         for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
@@ -211,6 +256,8 @@ class Context:
         ld = n_blk_cap * bs
         k_full = a_i.shape[1] if a_full else (b_i.shape[0] if b_full else 0)
         out = torch.empty((m, n), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        self._simm_shapes(m, n, ld, k_full, e, f, a_i, b_i, c_i, out, a_full, b_full)
+        _index_list(blk_idx, n_blk_dev, n_blk_cap, a_full or b_full)
         need = workspace_bytes(OP_SIMM, m, ld, n, bs)
         ws = self.workspace(need)
         flags = (FULL_A if a_full else 0) | (FULL_B if b_full else 0)
@@ -246,6 +293,12 @@ class Context:
         n_full = b_i.shape[0 if neuron_major else 1] if b_full else 0
         ld = n_blk_cap * bs
         out = torch.empty((m, ld), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        self._somm_shapes(m, k, ld, n_full, f, a_i, b_i, c_i, out, b_full, neuron_major)
+        _index_list(blk_idx, n_blk_dev, n_blk_cap, True)
+        for t, nm, cnt in ((blk_comp, "blk_comp", 0 if n_blk_dev is not None else n_blk_cap),
+                           (row_comp, "row_comp", 0 if n_row_dev is not None else m)):
+            if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous() or t.numel() < cnt:
+                raise TypeError("%s must be a contiguous int32 tensor on the GPU with %d entries" % (nm, cnt))
         need = workspace_bytes(OP_SOMM, m, k, ld, bs)
         ws = self.workspace(need)
         self._sync_stream()
@@ -269,6 +322,8 @@ class Context:
         ld = n_blk_cap * bs
         k_full = a_i.shape[1] if a_full else (b_i.shape[0] if b_full else 0)
         out = torch.empty((m, n), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        self._simm_shapes(m, n, ld, k_full, e, f, a_i, b_i, c_i, out, a_full, b_full)
+        _index_list(blk_idx, n_blk_dev, n_blk_cap, True)
         need = workspace_bytes(OP_SIMM, m, ld, n, bs)
         ws = self.workspace(need)
         flags = (FULL_A if a_full else 0) | (FULL_B if b_full else 0)

@@ -28,6 +28,7 @@ struct comet_ctx {
     char err[512];
 };
 
+
 static inline int comet_fail(comet_ctx* ctx, int code, const char* fmt, ...) {
     if (ctx) {
         va_list ap;
@@ -69,3 +70,4 @@ struct comet_device_guard {
 
 // Limits shared by the host checks and the kernels' 32-bit index arithmetic.
 static const int64_t COMET_DIM_MAX = (1ll << 24) - 1;
+static const int64_t COMET_ROWS_MAX = (1ll << 22) - 128;   // rows of the activation side of a share call

@@ -1,6 +1,9 @@
 // Context management of the comet_ring library.
 #include "common.h"
 
+size_t comet_compact_workspace_bytes(int64_t n_tok, int64_t nb);
+size_t comet_gemm_workspace_bytes(int64_t m, int64_t kc_cap, int64_t n_cap);
+
 extern "C" {
 
 const char* comet_version(void) { return "comet_ring 0.1 (gfx950)"; }
@@ -111,6 +114,16 @@ int comet_timing_end(comet_ctx* ctx, double* total_ms, int* launches) {
     *total_ms = sum;
     *launches = n;
     return COMET_OK;
+}
+
+size_t comet_workspace_bytes(int op, int64_t m, int64_t k, int64_t n, int bs) {
+    (void)bs;
+    switch (op) {
+        case COMET_OP_COMPACT: return comet_compact_workspace_bytes(m, n);
+        case COMET_OP_SOMM:
+        case COMET_OP_SIMM: return comet_gemm_workspace_bytes(m, k, n);
+        default: return 0;
+    }
 }
 
 const char* comet_last_error(const comet_ctx* ctx) { return ctx ? ctx->err : "null context"; }

@@ -20,10 +20,11 @@ __device__ __forceinline__ u64x2 combine(u64x2 a, u64x2 b) {
 // One block walks chunks of EW_THREADS * EW_UNROLL 16-byte vectors; all loads
 // of a chunk are issued before the first store so that each lane keeps
 // 2 * EW_UNROLL requests in flight.
+// The output may be one of the inputs (same address): every element is read and then written by
+// the same lane, so the pointers carry no no-alias promise.
 template <bool SUB>
-__global__ __launch_bounds__(EW_THREADS) void ew_kernel(const u64* __restrict__ a,
-                                                        const u64* __restrict__ b,
-                                                        u64* __restrict__ o, size_t n_elems) {
+__global__ __launch_bounds__(EW_THREADS) void ew_kernel(const u64* a, const u64* b, u64* o,
+                                                        size_t n_elems) {
     const size_t nvec = n_elems >> 1;
     const u64x2* av = reinterpret_cast<const u64x2*>(a);
     const u64x2* bv = reinterpret_cast<const u64x2*>(b);

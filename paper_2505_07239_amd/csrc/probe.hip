@@ -1,10 +1,7 @@
 // Roofline probes: register-resident issue loops that measure what the chip
-// sustains for the two candidate ways of doing ring arithmetic, and the
-// workspace-size query.  Measurement aids only; no protocol step uses them.
+// sustains for the two candidate ways of doing ring arithmetic.  Measurement
+// aids only; no protocol step uses them.
 #include "common.h"
-
-size_t comet_compact_workspace_bytes(int64_t n_tok, int64_t nb);
-size_t comet_gemm_workspace_bytes(int64_t m, int64_t kc_cap, int64_t n_cap);
 
 namespace {
 
@@ -104,16 +101,6 @@ int comet_probe_valu_mac64(comet_ctx* ctx, int blocks, int iters, uint64_t* out,
     COMET_LAUNCH_CHECK(ctx, "comet_probe_valu_mac64");
     if (macs) *macs = (double)blocks * 256.0 * iters * PROBE_MAC_PER_ITER;
     return COMET_OK;
-}
-
-size_t comet_workspace_bytes(int op, int64_t m, int64_t k, int64_t n, int bs) {
-    (void)bs;
-    switch (op) {
-        case COMET_OP_COMPACT: return comet_compact_workspace_bytes(m, n);
-        case COMET_OP_SOMM:
-        case COMET_OP_SIMM: return comet_gemm_workspace_bytes(m, k, n);
-        default: return 0;
-    }
 }
 
 }  // extern "C"

@@ -319,7 +319,7 @@ size_t step_ws_bytes(int64_t m, int64_t kc_cap) {
 // a selector, then twice (two tile shapes) one count plus one entry per tile of the smallest
 // tile shape, 64 x 64
 size_t gemm_ws_bytes(int64_t m, int64_t kc_cap, int64_t n_cap) {
-    if (m < 1 || kc_cap < 0 || n_cap < 0 || m > COMET_DIM_MAX || kc_cap > COMET_DIM_MAX || n_cap > COMET_DIM_MAX)
+    if (m < 1 || kc_cap < 0 || n_cap < 0 || m > COMET_ROWS_MAX || kc_cap > COMET_DIM_MAX || n_cap > COMET_DIM_MAX)
         return 0;
     const size_t tiles = (size_t)((m + 63) / 64) * (size_t)((n_cap + 63) / 64);
     return planes_bytes(m, kc_cap) + (((2 * (tiles + 1) + 1) * sizeof(int) + 255) & ~(size_t)255) +
@@ -437,8 +437,9 @@ int check_common(comet_ctx* ctx, const char* what, int party, int64_t m, int bs,
     }
     if (!blk_idx && (flags & (COMET_FULL_A | COMET_FULL_B)))
         return comet_fail(ctx, COMET_EINVAL, "%s: blk_idx required for full-size operands", what);
-    if (m > COMET_DIM_MAX / 2 || (int64_t)n_blk_cap * bs > COMET_DIM_MAX)
-        return comet_fail(ctx, COMET_ECAP, "%s: dimension beyond 2^24 (m beyond 2^23)", what);
+    // rows: the packing kernel walks 64-row slabs of the padded row count on grid.y (< 65536)
+    if (m > COMET_ROWS_MAX || (int64_t)n_blk_cap * bs > COMET_DIM_MAX)
+        return comet_fail(ctx, COMET_ECAP, "%s: dimension beyond 2^24 (m beyond 2^22 - 128)", what);
     return COMET_OK;
 }
 

@@ -169,26 +169,33 @@ def test_compact_mask_output_alignment(ctx, shift, density):
 # (3) output shares
 # ---------------------------------------------------------------------------
 
+SENTINEL = np.uint64(0x5EA15EA15EA15EA1)
+
+
 def _run_share(ctx, kind, party, bs, idx_np, cap, e, f, a_i, b_i, c_i, a_full=True, b_full=True,
                n_blk_on_device=True):
+    """The output buffer starts out full of a sentinel, so that a caller can see what was written."""
     gi = torch.zeros(max(cap, 1), dtype=torch.int32, device="cuda")
     gi[:len(idx_np)] = torch.from_numpy(idx_np).cuda()
     n_dev = torch.tensor([len(idx_np)], dtype=torch.int32, device="cuda") if n_blk_on_device else None
+    zshape = (e.shape[0], cap * bs) if kind == "somm" else (e.shape[0], f.shape[1])
+    out = torch.full(zshape, int(SENTINEL.view(np.int64)), dtype=torch.int64, device="cuda")
     if kind == "somm":
         return ctx.somm_share(party, bs, gi, n_dev, cap, up(e), up(f), up(a_i), up(b_i), up(c_i),
-                              b_full=b_full)
+                              b_full=b_full, out=out)
     return ctx.simm_share(party, bs, gi, n_dev, cap, up(e), up(f), up(a_i), up(b_i), up(c_i),
-                          a_full=a_full, b_full=b_full)
+                          a_full=a_full, b_full=b_full, out=out)
 
 
 def _pad_cols(a, ld):
-    out = np.zeros((a.shape[0], ld), np.uint64)
+    """Spare columns hold junk: nothing at or beyond n_blk * bs may be read."""
+    out = u64(4242, a.shape[0] + 7 * ld, a.shape[0], ld)
     out[:, :a.shape[1]] = a
     return out
 
 
 def _pad_rows(a, ld):
-    out = np.zeros((ld, a.shape[1]), np.uint64)
+    out = u64(4243, a.shape[1] + 7 * ld, ld, a.shape[1])
     out[:a.shape[0]] = a
     return out
 
@@ -334,6 +341,7 @@ def test_share_few_rows_compact_triples(ctx, kind):
             z = _run_share(ctx, kind, party, bs, case.idx, cap, *args, b_full=False)
             torch.cuda.synchronize()
             assert np.array_equal(down(z)[:, :t * bs], case.z[party])
+            assert np.all(down(z)[:, t * bs:] == SENTINEL)      # spare columns are never written
         else:
             a_sel = co.index_cols(case.a[party], case.idx, bs)
             b_sel = co.index_rows(case.b[party], case.idx, bs)
@@ -361,6 +369,7 @@ def test_share_compact_triples_and_spare_capacity(ctx, kind):
             torch.cuda.synchronize()
             got = down(z)
             assert np.array_equal(got[:, :t * bs], case.z[party])
+            assert np.all(got[:, t * bs:] == SENTINEL)          # spare columns are never written
         else:
             a_sel = co.index_cols(case.a[party], case.idx, bs)
             b_sel = co.index_rows(case.b[party], case.idx, bs)

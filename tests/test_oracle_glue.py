@@ -123,17 +123,6 @@ def test_share_local_rescaling_wraps_when_the_shares_straddle_the_ring():
     assert abs(got - (1 << 4)) > 1 and abs((got - (1 << 4)) % (1 << 48)) <= 1
 
 
-def test_prefetch_rule_reproduces_the_papers_threshold():
-    """Sec. 6.2: for OPT-6.7B (token vector 4096 words, head weight 4096 x 128) a not-activated
-    head needs at least 128 cache misses before prefetching it pays off."""
-    from workloads import configs
-    w, x = 4096 * 128, 4096
-    assert not configs.prefetch_pays_off(1000, 128, w, x)
-    assert configs.prefetch_pays_off(1000, 129, w, x)
-    # misses beyond those of the activated heads cost extra rows and never pay for themselves
-    assert not configs.prefetch_pays_off(10, 500, w, x)
-
-
 def test_mha_masks_shape_and_structure():
     from workloads import configs
     cfg = configs.mha_config()

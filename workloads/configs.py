@@ -187,10 +187,3 @@ def mha_head_masks(cfg: MhaConfig, seed: int = rng.BASE_SEED):
             qkv[cfg.tokens + r, h + head] = 1          # K of that head
             qkv[cfg.tokens + r, 2 * h + head] = 1      # V of that head
     return qkv, out_mask
-
-
-def prefetch_pays_off(l1: int, l2: int, head_weight_words: int, token_words: int) -> bool:
-    """Cost-benefit rule of Sec. 6.2 for prefetching a not-activated head: with ``l2`` cache
-    misses for it and ``l1`` for the activated heads, prefetch iff
-    ``l2 > w / x + max(0, l2 - l1)`` (w: size of the head's weight matrix, x: token vector size)."""
-    return l2 > head_weight_words / token_words + max(0, l2 - l1)
