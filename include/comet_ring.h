@@ -155,6 +155,22 @@ int comet_somm_share(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_
                      const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i,
                      void* ws, size_t ws_bytes);
 
+/* comet_somm_share for callers that cannot allocate device memory and have no
+ * workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments and result as
+ * comet_somm_share, without (ws, ws_bytes): the scratch is a static device array
+ * of COMET_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs
+ * on holds its own copy until the process ends).  The call allocates nothing.
+ * Sizes whose comet_workspace_bytes(COMET_OP_SOMM, ...) exceeds the array are
+ * rejected with COMET_ECAP.  All calls on one GPU share that GPU's array, from
+ * any context or stream: calls that overlap in time on one GPU race, the caller
+ * must order them (one stream, or events). */
+enum { COMET_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024 };
+int comet_somm_share_static(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_full, int bs,
+                            const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap,
+                            int flags, const uint64_t* E, const uint64_t* F, const uint64_t* A_i,
+                            const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i);
+
 /* SIMM (Protocol 3, subsequent layer: FC2 / down), contraction restricted to
  * the kept neurons (the sum of the per-neuron outer products of Protocol 3):
  *     [Z]_i = [C]_i + E [B]_i + [A]_i F + party * E F        (mod 2^64)

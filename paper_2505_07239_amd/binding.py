@@ -25,7 +25,7 @@ TUNE_GEMM_GRID, TUNE_GEMM_CHUNK, TUNE_GEMM_TILE, TUNE_SKINNY, TUNE_SKINNY_SLICES
 EXPORTS = [
     "comet_create", "comet_destroy", "comet_set_stream", "comet_last_error", "comet_version",
     "comet_workspace_bytes", "comet_mask_share", "comet_mask_share_gather", "comet_open",
-    "comet_compact_mask", "comet_somm_share", "comet_simm_share",
+    "comet_compact_mask", "comet_somm_share", "comet_somm_share_static", "comet_simm_share",
     "comet_components", "comet_somm_share_blocks", "comet_simm_share_masked",
     "comet_permute_mask", "comet_scatter_cols", "comet_truncate_share",
     "comet_set_tuning", "comet_timing_begin", "comet_timing_end", "comet_probe_mfma_i8", "comet_probe_valu_mac64", "comet_probe_copy",
@@ -65,6 +65,7 @@ def load_library() -> ctypes.CDLL:
     share = [vp, i32, i64, i64, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz]
     lib.comet_somm_share.argtypes = share
     lib.comet_simm_share.argtypes = share
+    lib.comet_somm_share_static.argtypes = share[:-2]
     lib.comet_components.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.comet_somm_share_blocks.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, i32, vp, vp, i32,
                                             vp, vp, vp, vp, vp, vp, vp, sz]
@@ -266,6 +267,26 @@ class Context:
                                               _ptr(n_blk_dev), n_blk_cap, flags, _ptr(e), _ptr(f),
                                               _ptr(a_i), _ptr(b_i), _ptr(c_i), _ptr(out), _ptr(ws),
                                               need))
+        return out
+
+    def somm_share_static(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, e, f, a_i, b_i, c_i,
+                          b_full=True, neuron_major=False, out=None):
+        """``somm_share`` on the library's static scratch array: no workspace, no allocation
+        inside the call (pass ``out``, or the result tensor is the one torch allocation)."""
+        for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
+            _words(t, nm)
+        m, k = e.shape
+        n_full = b_i.shape[0 if neuron_major else 1] if b_full else 0
+        ld = n_blk_cap * bs
+        out = torch.empty((m, ld), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        self._somm_shapes(m, k, ld, n_full, f, a_i, b_i, c_i, out, b_full, neuron_major)
+        _index_list(blk_idx, n_blk_dev, n_blk_cap, b_full)
+        self._sync_stream()
+        flags = (FULL_B if b_full else 0) | (WEIGHTS_NEURON_MAJOR if neuron_major else 0)
+        self._check(self.lib.comet_somm_share_static(self.h, party, m, k, n_full, bs, _ptr(blk_idx),
+                                                     _ptr(n_blk_dev), n_blk_cap, flags,
+                                                     _ptr(e), _ptr(f), _ptr(a_i), _ptr(b_i), _ptr(c_i),
+                                                     _ptr(out)))
         return out
 
     # ---- (4) Protocols 2 and 3 in general form ----

@@ -25,9 +25,13 @@ struct comet_ctx {
     int skinny_slices; // 0 = automatic
     hipEvent_t* ev;  // timing event pairs, or null
     int ev_cap, ev_used;
+    void* static_ws; // this device's copy of the library's static scratch array (device address)
     char err[512];
 };
 
+// Device address and size of the static scratch array on `device` (which must be current).
+// Defined beside the array, in ring_gemm.hip; looked up once per device.
+int comet_static_scratch(int device, void** ptr, size_t* bytes);
 
 static inline int comet_fail(comet_ctx* ctx, int code, const char* fmt, ...) {
     if (ctx) {

@@ -19,9 +19,21 @@ int comet_create(comet_ctx** out, int device_id) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) return COMET_EDEVICE;
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return COMET_EDEVICE;
+    // the device's copy of the static scratch array: looked up here, once, with the device current
+    void* static_ws = nullptr;
+    {
+        int prev = -1;
+        if (hipGetDevice(&prev) != hipSuccess) return COMET_EDEVICE;
+        if (prev != device_id && hipSetDevice(device_id) != hipSuccess) return COMET_EDEVICE;
+        size_t bytes = 0;
+        const int rc = comet_static_scratch(device_id, &static_ws, &bytes);
+        if (prev != device_id) (void)hipSetDevice(prev);
+        if (rc != COMET_OK) return rc;
+    }
     comet_ctx* ctx = new (std::nothrow) comet_ctx;
     if (!ctx) return COMET_EINVAL;
     ctx->device = device_id;
+    ctx->static_ws = static_ws;
     ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     ctx->stream = nullptr;
     ctx->gemm_grid = 0;

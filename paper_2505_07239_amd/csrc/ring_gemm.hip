@@ -40,6 +40,36 @@
 //                  large operands; they are never re-written to memory.
 #include "ring_gemm_kernel.h"
 
+#include <mutex>
+
+// Scratch of comet_somm_share_static, the entry point for callers that cannot allocate: a
+// file-scope device array, one copy per GPU for the life of the process.  In host code the
+// name `scratch` is only a handle for hipGetSymbolAddress: the address a kernel may use is the
+// one that call returns for the current device, kept in scratch_ptr[] and handed to the kernels
+// as an argument like any caller-owned workspace.
+constexpr size_t STATIC_SCRATCH_BYTES = COMET_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static void* scratch_ptr[MAX_DEVICES];
+static std::mutex scratch_mutex;
+
+int comet_static_scratch(int device, void** ptr, size_t* bytes) {
+    if (device < 0 || device >= MAX_DEVICES || !ptr || !bytes) return COMET_EINVAL;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[device]) {
+        void* q = nullptr;
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) {
+            (void)hipGetLastError();
+            return COMET_EDEVICE;
+        }
+        scratch_ptr[device] = q;
+    }
+    *ptr = scratch_ptr[device];
+    *bytes = STATIC_SCRATCH_BYTES;
+    return COMET_OK;
+}
+
 namespace {
 
 using namespace comet_gemm;
@@ -521,6 +551,27 @@ int comet_somm_share(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_
                                E, F, A_i, B_i, C_i, Z_i);
     if (rc) return rc;
     return run_share(ctx, what, p, ws, ws_bytes);
+}
+
+int comet_somm_share_static(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_full, int bs,
+                            const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap,
+                            int flags, const uint64_t* E, const uint64_t* F, const uint64_t* A_i,
+                            const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i) {
+    const char* what = "comet_somm_share_static";
+    COMET_CHECK_CTX(ctx);
+    GemmParams p = {};
+    const int rc = somm_params(ctx, what, p, party, m, k, n_full, bs, blk_idx, n_blk_dev, n_blk_cap, flags,
+                               E, F, A_i, B_i, C_i, Z_i);
+    if (rc) return rc;
+    const size_t need = gemm_ws_bytes(p.m, p.kc_cap, p.n_cap);
+    if (need == 0 || need > STATIC_SCRATCH_BYTES)
+        return comet_fail(ctx, COMET_ECAP,
+                          "%s: needs %zu bytes of scratch, the static array holds %zu "
+                          "(use comet_somm_share with a workspace)", what, need, STATIC_SCRATCH_BYTES);
+    if (!ctx->static_ws)
+        return comet_fail(ctx, COMET_EDEVICE, "%s: static scratch was not resolved on this device", what);
+    // every part of the scratch a call reads it has written before, so nothing needs clearing
+    return run_share(ctx, what, p, ctx->static_ws, STATIC_SCRATCH_BYTES);
 }
 
 int comet_somm_share_blocks(comet_ctx* ctx, int party, int64_t m_cap, int64_t k, int64_t n_full,
