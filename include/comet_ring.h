@@ -66,8 +66,16 @@ enum { COMET_OP_COMPACT = 0, COMET_OP_SOMM = 1, COMET_OP_SIMM = 2 };
  * are stored one ROW per neuron (n x k, the transpose of the k x n form), the
  * layout in which a kept neuron is one contiguous run of k words in both
  * projections of an FFN (the weights are permuted and stored once, offline,
- * Sec. 4.2, so their layout is free to choose).  The result is the same. */
-enum { COMET_FULL_A = 1, COMET_FULL_B = 2, COMET_WEIGHTS_NEURON_MAJOR = 4 };
+ * Sec. 4.2, so their layout is free to choose).  The result is the same.
+ * COMET_WEIGHT_PLANES: the weight-side operands B_i and F are passed as DIGIT
+ * PLANES, the format comet_open_weight_planes() writes (the opened F directly
+ * from the two masked shares, B_i packed once, offline, like the triple itself,
+ * Sec. 3.2), at the same logical shapes as their word forms.  The share kernels
+ * then move both operands into the matrix cores without any per-step
+ * arithmetic; the result is the same, bit for bit.  Not with
+ * COMET_WEIGHTS_NEURON_MAJOR; with COMET_FULL_B in a SIMM call bs must be a
+ * multiple of 16 (COMET_EINVAL otherwise). */
+enum { COMET_FULL_A = 1, COMET_FULL_B = 2, COMET_WEIGHTS_NEURON_MAJOR = 4, COMET_WEIGHT_PLANES = 8 };
 
 /* ---- context ---------------------------------------------------------- */
 
@@ -115,6 +123,22 @@ int comet_mask_share_gather(comet_ctx* ctx, const uint64_t* w_i, const uint64_t*
  * e may be the same buffer as d_0 or d_1 (same address, no partial overlap). */
 int comet_open(comet_ctx* ctx, const uint64_t* d_0, const uint64_t* d_1, uint64_t* e,
                size_t n_elems);
+
+/* The opening of a weight-side operand written as digit planes: planes :=
+ * pack(g_0 + g_1) for a k x n row-major matrix of words (k = contraction rows,
+ * n = columns), or pack(g_0) when g_1 is NULL (used once, offline, for a triple
+ * share B_i).  Each word x is split into eight signed base-256 digits d_t
+ * (x = sum d_t 2^(8t) mod 2^64, -128 <= d_t <= 127); a 16-byte unit holds digit t
+ * of the sixteen rows 32 s + 16 g + 0..15 of one column c, and units are ordered
+ * (s, c / 64, t, g, c % 64); rows at or beyond k read as zero, the last chunk of
+ * 64 columns is padded (its padding is never read).  planes must hold
+ * comet_weight_planes_bytes(k, n) = ceil(k / 32) * 32 * ceil(n / 64) * 64 * 8
+ * bytes and must not overlap the inputs.  Pass the
+ * result wherever a share call takes F or B_i, together with
+ * COMET_WEIGHT_PLANES.  k, n < 2^24, k * n < 2^31. */
+size_t comet_weight_planes_bytes(int64_t k, int64_t n);
+int comet_open_weight_planes(comet_ctx* ctx, const uint64_t* g_0, const uint64_t* g_1, int64_t k,
+                             int64_t n, void* planes);
 
 /* ---- (2) sparsity distribution -> ordered index list -------------------- */
 

@@ -19,12 +19,13 @@ LIB_PATH = os.path.join(_HERE, "libcomet_ring.so")
 
 AXIS_COLS, AXIS_ROWS = 0, 1
 OP_COMPACT, OP_SOMM, OP_SIMM = 0, 1, 2
-FULL_A, FULL_B, WEIGHTS_NEURON_MAJOR = 1, 2, 4
+FULL_A, FULL_B, WEIGHTS_NEURON_MAJOR, WEIGHT_PLANES = 1, 2, 4, 8
 TUNE_GEMM_GRID, TUNE_GEMM_CHUNK, TUNE_GEMM_TILE, TUNE_SKINNY, TUNE_SKINNY_SLICES = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "comet_create", "comet_destroy", "comet_set_stream", "comet_last_error", "comet_version",
     "comet_workspace_bytes", "comet_mask_share", "comet_mask_share_gather", "comet_open",
+    "comet_weight_planes_bytes", "comet_open_weight_planes",
     "comet_compact_mask", "comet_somm_share", "comet_somm_share_static", "comet_simm_share",
     "comet_components", "comet_somm_share_blocks", "comet_simm_share_masked",
     "comet_permute_mask", "comet_scatter_cols", "comet_truncate_share",
@@ -60,6 +61,9 @@ def load_library() -> ctypes.CDLL:
     lib.comet_workspace_bytes.restype = sz
     lib.comet_mask_share.argtypes = [vp, vp, vp, vp, sz]
     lib.comet_open.argtypes = [vp, vp, vp, vp, sz]
+    lib.comet_weight_planes_bytes.argtypes = [i64, i64]
+    lib.comet_weight_planes_bytes.restype = sz
+    lib.comet_open_weight_planes.argtypes = [vp, vp, vp, i64, i64, vp]
     lib.comet_mask_share_gather.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, i32]
     lib.comet_compact_mask.argtypes = [vp, vp, i64, i64, vp, vp, vp, sz]
     share = [vp, i32, i64, i64, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz]
@@ -96,6 +100,34 @@ def _words(t: torch.Tensor, what: str) -> torch.Tensor:
     if t.dtype != torch.int64 or not t.is_cuda or not t.is_contiguous():
         raise TypeError("%s must be a contiguous int64 tensor on the GPU" % what)
     return t
+
+
+class WeightPlanes:
+    """A weight-side operand (F or B_i) in the digit-plane format of ``comet_open_weight_planes``:
+    the raw buffer plus the logical shape ``k x n`` of the matrix it stands for."""
+
+    def __init__(self, buf: torch.Tensor, k: int, n: int):
+        self.buf, self.shape = buf, (k, n)
+
+    def data_ptr(self):
+        return self.buf.data_ptr()
+
+
+def _weights(t, what: str):
+    """A weight-side operand: words (int64 tensor) or planes."""
+    if isinstance(t, WeightPlanes):
+        return t
+    return _words(t, what)
+
+
+def _operands(e, f, a_i, b_i, c_i) -> int:
+    """Type checks of the five operands of a share call; returns the flag bit for weight planes
+    (F and B_i are either both words or both planes)."""
+    _words(e, "E"), _words(a_i, "A_i"), _words(c_i, "C_i")
+    _weights(f, "F"), _weights(b_i, "B_i")
+    if isinstance(f, WeightPlanes) != isinstance(b_i, WeightPlanes):
+        raise TypeError("F and B_i must both be words or both be weight planes")
+    return WEIGHT_PLANES if isinstance(f, WeightPlanes) else 0
 
 
 def _index_list(blk_idx, n_blk_dev, n_blk_cap: int, required: bool):
@@ -180,6 +212,22 @@ class Context:
         self._check(self.lib.comet_open(self.h, _ptr(d_0), _ptr(d_1), _ptr(out), d_0.numel()))
         return out
 
+    def open_weight_planes(self, g_0, g_1=None, out=None) -> WeightPlanes:
+        """F = g_0 + g_1 (or g_0 alone: offline packing of a triple share) as digit planes."""
+        _words(g_0, "g_0")
+        k, n = g_0.shape
+        if g_1 is not None:
+            _words(g_1, "g_1")
+            _shape(g_1, (k, n), "g_1")
+        need = int(self.lib.comet_weight_planes_bytes(k, n))
+        if out is None:
+            out = torch.empty(max(need, 16), dtype=torch.uint8, device=g_0.device)
+        elif out.dtype != torch.uint8 or not out.is_cuda or out.numel() < need:
+            raise TypeError("out must be a uint8 tensor on the GPU of at least %d bytes" % need)
+        self._sync_stream()
+        self._check(self.lib.comet_open_weight_planes(self.h, _ptr(g_0), _ptr(g_1), k, n, _ptr(out)))
+        return WeightPlanes(out, k, n)
+
     def mask_share_gather(self, w_i, b_i, axis, bs, blk_idx, n_blk_dev, n_blk_cap, out=None):
         _words(w_i, "w_i"), _words(b_i, "b_i")
         rows, cols = w_i.shape
@@ -216,8 +264,7 @@ class Context:
     def somm_share(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, e, f, a_i, b_i, c_i,
                    b_full=True, neuron_major=False, out=None):
         """``neuron_major``: ``f`` and ``b_i`` are stored one row per neuron (n x k)."""
-        for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
-            _words(t, nm)
+        planes = _operands(e, f, a_i, b_i, c_i)
         m, k = e.shape
         n_full = b_i.shape[0 if neuron_major else 1] if b_full else 0
         ld = n_blk_cap * bs
@@ -227,7 +274,7 @@ class Context:
         need = workspace_bytes(OP_SOMM, m, k, ld, bs)
         ws = self.workspace(need)
         self._sync_stream()
-        flags = (FULL_B if b_full else 0) | (WEIGHTS_NEURON_MAJOR if neuron_major else 0)
+        flags = (FULL_B if b_full else 0) | (WEIGHTS_NEURON_MAJOR if neuron_major else 0) | planes
         self._check(self.lib.comet_somm_share(self.h, party, m, k, n_full, bs, _ptr(blk_idx),
                                               _ptr(n_blk_dev), n_blk_cap, flags,
                                               _ptr(e), _ptr(f), _ptr(a_i), _ptr(b_i), _ptr(c_i),
@@ -250,8 +297,7 @@ class Context:
 
     def simm_share(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, e, f, a_i, b_i, c_i,
                    a_full=True, b_full=True, out=None):
-        for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
-            _words(t, nm)
+        planes = _operands(e, f, a_i, b_i, c_i)
         m = e.shape[0]
         n = f.shape[1]
         ld = n_blk_cap * bs
@@ -261,7 +307,7 @@ class Context:
         _index_list(blk_idx, n_blk_dev, n_blk_cap, a_full or b_full)
         need = workspace_bytes(OP_SIMM, m, ld, n, bs)
         ws = self.workspace(need)
-        flags = (FULL_A if a_full else 0) | (FULL_B if b_full else 0)
+        flags = (FULL_A if a_full else 0) | (FULL_B if b_full else 0) | planes
         self._sync_stream()
         self._check(self.lib.comet_simm_share(self.h, party, m, k_full, n, bs, _ptr(blk_idx),
                                               _ptr(n_blk_dev), n_blk_cap, flags, _ptr(e), _ptr(f),
@@ -273,8 +319,7 @@ class Context:
                           b_full=True, neuron_major=False, out=None):
         """``somm_share`` on the library's static scratch array: no workspace, no allocation
         inside the call (pass ``out``, or the result tensor is the one torch allocation)."""
-        for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
-            _words(t, nm)
+        planes = _operands(e, f, a_i, b_i, c_i)
         m, k = e.shape
         n_full = b_i.shape[0 if neuron_major else 1] if b_full else 0
         ld = n_blk_cap * bs
@@ -282,7 +327,7 @@ class Context:
         self._somm_shapes(m, k, ld, n_full, f, a_i, b_i, c_i, out, b_full, neuron_major)
         _index_list(blk_idx, n_blk_dev, n_blk_cap, b_full)
         self._sync_stream()
-        flags = (FULL_B if b_full else 0) | (WEIGHTS_NEURON_MAJOR if neuron_major else 0)
+        flags = (FULL_B if b_full else 0) | (WEIGHTS_NEURON_MAJOR if neuron_major else 0) | planes
         self._check(self.lib.comet_somm_share_static(self.h, party, m, k, n_full, bs, _ptr(blk_idx),
                                                      _ptr(n_blk_dev), n_blk_cap, flags,
                                                      _ptr(e), _ptr(f), _ptr(a_i), _ptr(b_i), _ptr(c_i),
@@ -308,8 +353,7 @@ class Context:
 
     def somm_share_blocks(self, party, bs, blk_idx, blk_comp, n_blk_dev, n_blk_cap, row_comp, n_row_dev,
                           e, f, a_i, b_i, c_i, b_full=True, neuron_major=False, out=None):
-        for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
-            _words(t, nm)
+        planes = _operands(e, f, a_i, b_i, c_i)
         m, k = e.shape
         n_full = b_i.shape[0 if neuron_major else 1] if b_full else 0
         ld = n_blk_cap * bs
@@ -326,14 +370,13 @@ class Context:
         self._check(self.lib.comet_somm_share_blocks(
             self.h, party, m, k, n_full, bs, _ptr(blk_idx), _ptr(blk_comp), _ptr(n_blk_dev), n_blk_cap,
             _ptr(row_comp), _ptr(n_row_dev),
-            (FULL_B if b_full else 0) | (WEIGHTS_NEURON_MAJOR if neuron_major else 0), _ptr(e), _ptr(f), _ptr(a_i),
+            (FULL_B if b_full else 0) | (WEIGHTS_NEURON_MAJOR if neuron_major else 0) | planes, _ptr(e), _ptr(f), _ptr(a_i),
             _ptr(b_i), _ptr(c_i), _ptr(out), _ptr(ws), need))
         return out
 
     def simm_share_masked(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, token_mask, e, f, a_i, b_i, c_i,
                           a_full=True, b_full=True, out=None):
-        for t, nm in ((e, "E"), (f, "F"), (a_i, "A_i"), (b_i, "B_i"), (c_i, "C_i")):
-            _words(t, nm)
+        planes = _operands(e, f, a_i, b_i, c_i)
         if token_mask.dtype != torch.uint8 or not token_mask.is_cuda or not token_mask.is_contiguous():
             raise TypeError("token_mask must be a contiguous uint8 tensor on the GPU")
         m = e.shape[0]
@@ -347,7 +390,7 @@ class Context:
         _index_list(blk_idx, n_blk_dev, n_blk_cap, True)
         need = workspace_bytes(OP_SIMM, m, ld, n, bs)
         ws = self.workspace(need)
-        flags = (FULL_A if a_full else 0) | (FULL_B if b_full else 0)
+        flags = (FULL_A if a_full else 0) | (FULL_B if b_full else 0) | planes
         self._sync_stream()
         self._check(self.lib.comet_simm_share_masked(
             self.h, party, m, k_full, n, bs, _ptr(blk_idx), _ptr(n_blk_dev), n_blk_cap, flags,

@@ -12,7 +12,9 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcomet_ring.so")
 # the variants of the matrix-core kernel come first: they take longest to compile
 SOURCES = ["ring_gemm_tile_32x256.hip", "ring_gemm_tile_32x256_listed.hip", "ring_gemm_tile_128x64.hip",
-           "ring_gemm_tile_64x64.hip", "ring_gemm_tile_64x64_listed.hip", "ring_gemm.hip",
+           "ring_gemm_tile_64x64.hip", "ring_gemm_tile_64x64_listed.hip",
+           "ring_gemm_planes_128x64.hip", "ring_gemm_planes_64x64.hip", "ring_gemm_planes_64x64_listed.hip",
+           "ring_gemm_planes_32x128.hip", "ring_gemm_planes_32x128_listed.hip", "ring_gemm.hip", "wplanes.hip",
            "ring_skinny.hip", "ctx.hip", "elementwise.hip", "compact.hip", "components.hip", "glue.hip", "probe.hip"]
 FLAGS = ["-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-fvisibility=default",
          # the LDS-DMA helper names M0 as clobbered, which clang flags as a reserved register

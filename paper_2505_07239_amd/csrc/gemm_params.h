@@ -24,6 +24,7 @@ struct GemmParams {
     const u64* B;  long ldb;  int b_full;
     const u64* F;  long ldf;
     int w_tr;       // SOMM: B_i and F are stored neuron-major (one row of k words per output column)
+    int w_planes;   // B_i and F are digit planes (comet_open_weight_planes); ldb / ldf = their columns
     const u64* C;
     u64* Z;        long ldz;
     // packed digit planes of [E | A']

@@ -374,8 +374,9 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         if (p.bs == (1 << sh)) p.bs_shift = sh;
 
     if (p.n_cap == 0) return COMET_OK;
-    // (the few-row kernel reads the weights along the output columns: row-major weights only)
-    if (p.m <= COMET_SKINNY_MAX_ROWS && ctx->skinny_mode != 1 && !p.w_tr) return comet_launch_skinny(ctx, what, p);
+    // (the few-row kernel reads the weights along the output columns: row-major words only)
+    if (p.m <= COMET_SKINNY_MAX_ROWS && ctx->skinny_mode != 1 && !p.w_tr && !p.w_planes)
+        return comet_launch_skinny(ctx, what, p);
     // digit planes of [E | A'] and Z := C, one launch
     {
         unsigned gx = (unsigned)((p.ks_cap * 2 + 3) / 4);
@@ -401,9 +402,10 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
             return launch_gemm<2, 2, 1, 1>(ctx, what, p);
         }
         if (p.m <= 32) {
-            hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, 32, 256, list_a,
-                               (const int*)nullptr, 0, (int*)nullptr);
+            hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, 32, p.w_planes ? 128 : 256,
+                               list_a, (const int*)nullptr, 0, (int*)nullptr);
             COMET_LAUNCH_CHECK(ctx, what);
+            if (p.w_planes) return launch_gemm<1, 4, 1, 1>(ctx, what, p);
             return launch_gemm<1, 4, 1, 2>(ctx, what, p);
         }
         hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, 128, 64, list_a,
@@ -449,7 +451,7 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         hipLaunchKernelGGL(step_offsets_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, bm);
         COMET_LAUNCH_CHECK(ctx, what);
     }
-    if (bm == 32) return launch_gemm<1, 4, 1, 2>(ctx, what, p);
+    if (bm == 32) return p.w_planes ? launch_gemm<1, 4, 1, 1>(ctx, what, p) : launch_gemm<1, 4, 1, 2>(ctx, what, p);
     if (bm == 64) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
     return launch_gemm<2, 2, 2, 1>(ctx, what, p);
 }
@@ -458,8 +460,10 @@ int check_common(comet_ctx* ctx, const char* what, int party, int64_t m, int bs,
                  int flags, const void* const* ptrs, int n_ptrs, const int32_t* blk_idx) {
     if (party != 0 && party != 1) return comet_fail(ctx, COMET_EINVAL, "%s: party must be 0 or 1", what);
     if (m < 1 || bs < 1 || n_blk_cap < 0) return comet_fail(ctx, COMET_EINVAL, "%s: bad size", what);
-    if (flags & ~(COMET_FULL_A | COMET_FULL_B | COMET_WEIGHTS_NEURON_MAJOR))
+    if (flags & ~(COMET_FULL_A | COMET_FULL_B | COMET_WEIGHTS_NEURON_MAJOR | COMET_WEIGHT_PLANES))
         return comet_fail(ctx, COMET_EINVAL, "%s: unknown flag", what);
+    if ((flags & COMET_WEIGHT_PLANES) && (flags & COMET_WEIGHTS_NEURON_MAJOR))
+        return comet_fail(ctx, COMET_EINVAL, "%s: weight planes have a layout of their own", what);
     for (int i = 0; i < n_ptrs; ++i) {
         if (!ptrs[i]) return comet_fail(ctx, COMET_EINVAL, "%s: null pointer (operand %d)", what, i);
         if (!comet_aligned16(ptrs[i]))
@@ -500,6 +504,7 @@ int somm_params(comet_ctx* ctx, const char* what, GemmParams& p, int party, int6
         if (k & 1) return comet_fail(ctx, COMET_EINVAL, "%s: neuron-major weights need an even k", what);
         p.w_tr = 1; p.ldb = k; p.ldf = k;
     }
+    p.w_planes = (flags & COMET_WEIGHT_PLANES) ? 1 : 0;
     p.C = (const u64*)C_i; p.Z = (u64*)Z_i; p.ldz = ld;
     return COMET_OK;
 }
@@ -527,6 +532,10 @@ int simm_params(comet_ctx* ctx, const char* what, GemmParams& p, int party, int6
     p.A = (const u64*)A_i; p.a_full = (flags & COMET_FULL_A) ? 1 : 0; p.lda = p.a_full ? k_full : ld;
     p.B = (const u64*)B_i; p.b_full = (flags & COMET_FULL_B) ? 1 : 0; p.ldb = n;
     p.F = (const u64*)F; p.ldf = n;
+    p.w_planes = (flags & COMET_WEIGHT_PLANES) ? 1 : 0;
+    // planes of a full-size B_i are gathered in units of sixteen contraction rows
+    if (p.w_planes && p.b_full && (bs % 16) != 0)
+        return comet_fail(ctx, COMET_EINVAL, "%s: weight planes of a full-size B_i need bs to be a multiple of 16", what);
     p.C = (const u64*)C_i; p.Z = (u64*)Z_i; p.ldz = n;
     return COMET_OK;
 }

@@ -5,6 +5,7 @@
 #pragma once
 
 #include "common.h"
+#include "digits.h"
 #include "gemm_params.h"
 
 #include <type_traits>
@@ -20,7 +21,6 @@ typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 constexpr int KSTEP = 32;       // ring words contracted per matrix instruction
 constexpr int MAX_SEG = 256;    // contraction steps an int32 plane can absorb
 constexpr int GT = 256;         // threads per workgroup (4 wavefronts)
-constexpr u64 DIGIT_BIAS = 0x0080808080808080ull;
 
 // how the weight-side rows of B_i are addressed (SIMM with a full-size B_i only)
 constexpr int GATHER_NONE = 0;   // rows are the compact contraction index
@@ -28,36 +28,11 @@ constexpr int GATHER_POW2 = 1;   // block gather, bs a power of two >= 8
 constexpr int GATHER_ANY = 2;    // block gather, any bs
 // SOMM with neuron-major weights: B_i and F hold one row of k contiguous words per output column
 constexpr int WEIGHTS_TR = 3;
-
-__device__ __forceinline__ u64 to_digits(u64 x) { return (x + DIGIT_BIAS) ^ DIGIT_BIAS; }
-
-// 4x4 byte transpose: in a0..a3 byte b of word j  ->  out word b, byte j
-__device__ __forceinline__ void transpose4(u32 a0, u32 a1, u32 a2, u32 a3, u32& o0, u32& o1,
-                                           u32& o2, u32& o3) {
-    const u32 p01l = __builtin_amdgcn_perm(a1, a0, 0x05010400u);
-    const u32 p01h = __builtin_amdgcn_perm(a1, a0, 0x07030602u);
-    const u32 p23l = __builtin_amdgcn_perm(a3, a2, 0x05010400u);
-    const u32 p23h = __builtin_amdgcn_perm(a3, a2, 0x07030602u);
-    o0 = __builtin_amdgcn_perm(p23l, p01l, 0x05040100u);
-    o1 = __builtin_amdgcn_perm(p23l, p01l, 0x07060302u);
-    o2 = __builtin_amdgcn_perm(p23h, p01h, 0x05040100u);
-    o3 = __builtin_amdgcn_perm(p23h, p01h, 0x07060302u);
-}
-
-// Eight consecutive-k words (already in digit form) -> for each digit t one
-// 8-byte group holding digit t of k0..k7.
-__device__ __forceinline__ void digits_to_planes(const u64 (&v)[8], u64 (&plane)[8]) {
-    u32 lo[8], hi[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { lo[j] = (u32)v[j]; hi[j] = (u32)(v[j] >> 32); }
-    u32 a[8], b[8];   // a: k0..3, b: k4..7, index = digit
-    transpose4(lo[0], lo[1], lo[2], lo[3], a[0], a[1], a[2], a[3]);
-    transpose4(hi[0], hi[1], hi[2], hi[3], a[4], a[5], a[6], a[7]);
-    transpose4(lo[4], lo[5], lo[6], lo[7], b[0], b[1], b[2], b[3]);
-    transpose4(hi[4], hi[5], hi[6], hi[7], b[4], b[5], b[6], b[7]);
-#pragma unroll
-    for (int t = 0; t < 8; ++t) plane[t] = (u64)a[t] | ((u64)b[t] << 32);
-}
+// B_i and F arrive as digit planes (see PlaneLoader); with W_PLANES_GATHER the rows of a
+// full-size B_i are gathered by block (SIMM, bs a multiple of 16)
+constexpr int W_PLANES = 4;
+constexpr int W_PLANES_GATHER = 5;
+constexpr bool is_planes(int gmode) { return gmode == W_PLANES || gmode == W_PLANES_GATHER; }
 
 // Packed layout of [E | A'] in 16-byte units: group (half h, step s, digit t,
 // k-half g) is a run of mpad units, one per row; the 16 bytes of a unit are
@@ -82,19 +57,27 @@ struct Tile {
     static constexpr int WBASE = XSTAGES * XBYTES;
     static constexpr int SMEM = XSTAGES * XBYTES + WSTAGES * WBYTES;
     static constexpr int XVEC = XBYTES / 16 / GT;    // 16-byte units per thread per stage
+    static constexpr int WVEC = WBYTES / 16 / GT;    // same for a weight stage filled by LDS-DMA
     static constexpr int WTASK = BN * 4 / GT;        // (column, octet) tasks per thread per stage
     // vector-memory loads a thread issues per step: the LDS-DMA units plus, per weight task,
     // eight 8-byte loads (or four 16-byte loads when the weights are neuron-major)
-    // and one load of a block id with the power-of-two row gather
+    // and one load of a block id with the power-of-two row gather; with weight planes only
+    // LDS-DMA units
     static constexpr int vm_per_step(int gmode) {
+        if (is_planes(gmode)) return XVEC + WVEC;
         return XVEC + (gmode == WEIGHTS_TR ? 4 : 8) * WTASK + (gmode == GATHER_POW2 ? WTASK : 0);
     }
-    static constexpr int VM_PER_STEP = vm_per_step(GATHER_POW2);   // the largest
+    // weight planes are written by LDS-DMA two steps ahead, like the activation planes: three
+    // stages, plus the step table of the segment
+    static constexpr int wstages(int gmode) { return is_planes(gmode) ? 3 : WSTAGES; }
+    static constexpr int smem(int gmode) {
+        return XSTAGES * XBYTES + wstages(gmode) * WBYTES + (is_planes(gmode) ? MAX_SEG * 16 : 0);
+    }
     // two workgroups share a compute unit when one needs at most half of its registers and LDS
-    static constexpr int WG_PER_CU = (WM * WN == 1 && SMEM <= 80 * 1024) ? 2 : 1;
+    static constexpr int wg_per_cu(int gmode) { return (WM * WN == 1 && smem(gmode) <= 80 * 1024) ? 2 : 1; }
     static_assert(WAVES_M * WAVES_N * 64 == GT, "four wavefronts per workgroup");
     static_assert(XVEC >= 1 && WTASK >= 1, "tile too small for the loader");
-    static_assert(VM_PER_STEP < 63, "outstanding-load counter has 6 bits");
+    static_assert(vm_per_step(GATHER_POW2) < 63, "outstanding-load counter has 6 bits");
     static_assert(SMEM <= 160 * 1024, "LDS of one CDNA4 compute unit");
 };
 
@@ -176,6 +159,7 @@ struct Loader {
     static constexpr int P_TASK = P_DMA + T::XVEC;
     static constexpr int PER_TASK = 8 + 4 + 8;
     static constexpr int P_END = P_TASK + PER_TASK * W;
+    static constexpr int VM_PER_STEP = T::vm_per_step(GMODE);
 
     __device__ __forceinline__ void setup(const GemmParams& p, int tm, int tn, int n_eff) {
 #pragma unroll
@@ -402,6 +386,153 @@ struct Loader {
 
 };
 
+
+// Loader for weight-side operands that arrive as digit planes (W_PLANES, W_PLANES_GATHER).
+//
+// B_i and F are stored in the unit format of the packed activation planes, transposed: a
+// 16-byte unit holds digit t of the sixteen contraction words k = 32 s + 16 g + 0..15 of ONE
+// column, and units are ordered (step s, chunk of 64 columns, digit t, k-half g, column inside
+// the chunk): the sixteen runs (t, g) of a step and a column chunk are 16 KB of consecutive
+// memory.  A weight stage of a tile is sixteen runs of BN units, each run of 64 columns one
+// wavefront-wide LDS-DMA transfer:
+// the step needs no vector arithmetic, no registers and no LDS store for either operand, only
+// the matrix instructions and their fragment reads.  The planes of F come out of the opening
+// kernel, those of B_i (triple material) are packed offline.
+//
+// Everything a step's transfers depend on -- which half of the stacked contraction it is in,
+// where its activation planes start, which rows of the weight operand it contracts (after the
+// block gather of a full-size B_i, or through the step list of Protocol 3's row sets) -- is put
+// into a small LDS table once per segment (build_table) and read one step ahead, so that a
+// step contains no global index loads and no address arithmetic beyond a few scalar operations.
+template <class T, int KIND, int GMODE, bool LISTED>
+struct PlaneLoader {
+    static constexpr int XV = T::XVEC, WV = T::WVEC;
+    static constexpr int P_END = XV + WV;
+    static constexpr int VM_PER_STEP = XV + WV;
+    static constexpr int XGRP_PER_PASS = GT / T::BM;
+    static_assert(GT % T::BM == 0, "tile rows must divide the block");
+    static_assert(T::BN % 64 == 0, "a wavefront's transfer stays inside one run of units");
+
+    unsigned pcb[WV], pcf[WV], pcsel[WV];   // lane's byte offset of its column inside a run: B_i, F, selected
+    const unsigned char* xsrc;              // this thread's first 16-byte unit of step (h = 0, s = 0)
+    size_t xstride;
+    const unsigned char* xs2;               // same for the look-ahead step
+    const char* pbase;                      // planes of the half the look-ahead step is in
+    size_t prow;                            // bytes per contraction step of the whole operand (its column chunks x 16 KB)
+    int n0a, n0b;                           // first row of the two k-halves in the operand's own row numbering
+    v4i pend;                               // table entry of the step after the look-ahead step
+    const int* tab;                         // LDS: per position of the segment {x group, n0a, n0b, half}
+    const int* steps;                       // listed contraction steps of this row tile, or null
+
+    __device__ __forceinline__ void setup(const GemmParams& p, int tm, int tn, int n_eff) {
+#pragma unroll
+        for (int j = 0; j < WV; ++j) {
+            const int u = threadIdx.x + GT * j;            // unit of the stage: run u / BN, column u % BN
+            int col = tn * T::BN + u % T::BN;
+            col = col < n_eff ? col : n_eff - 1;
+            long bcol = col;
+            if (KIND == KIND_SOMM && p.b_full) {
+                const int blk = col / p.bs;
+                const long st = block_start(p, blk);
+                bcol = (st < 0 ? 0 : st) + (col - blk * p.bs);
+            }
+            // chunk of 64 columns, then the column inside it (columns stay below 2^24: host check)
+            pcb[j] = ((unsigned)bcol >> 6) * 16384u + ((unsigned)bcol & 63u) * 16u;
+            pcf[j] = ((unsigned)col >> 6) * 16384u + ((unsigned)col & 63u) * 16u;
+        }
+        steps = nullptr;
+        const int grp = threadIdx.x / T::BM, within = threadIdx.x % T::BM;
+        xsrc = p.xp + ((size_t)grp * p.mpad + (size_t)tm * T::BM + within) * 16;
+        xstride = (size_t)XGRP_PER_PASS * p.mpad * 16;
+    }
+
+    // Table of the segment that starts at position ks0 of the stacked contraction and has L
+    // steps (all threads; the caller synchronises).  Rows past the end of the contraction keep
+    // a valid address: their activation digits are zero.
+    __device__ __forceinline__ void build_table(const GemmParams& p, int* table, int ks0, int L, int KS, int kc) {
+        for (int q = threadIdx.x; q < L; q += GT) {
+            const int ks = ks0 + q;
+            const int h = ks >= KS ? 1 : 0;
+            int s = ks - h * KS;
+            if constexpr (LISTED) s = steps[s];
+            int n0[2];
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const int k0 = s * KSTEP + 16 * g;
+                n0[g] = k0;
+                if (GMODE == W_PLANES_GATHER && h == 0) {
+                    // bs is a multiple of 16 (host check), so a half lies inside one block
+                    const int kb = k0 <= kc - 16 ? k0 : kc - 16;
+                    const int blk = kb / p.bs;
+                    const long st = block_start(p, blk);
+                    n0[g] = (int)(st < 0 ? 0 : st) + (kb - blk * p.bs);
+                }
+            }
+            v4i e = {h * p.ks_cap + s, n0[0], n0[1], h};
+            *reinterpret_cast<v4i*>(table + 4 * q) = e;
+        }
+        tab = table;
+    }
+
+    __device__ __forceinline__ void prime() { pend = *reinterpret_cast<const v4i*>(tab); }
+
+    // Fix the step (position q of the segment) the following transfers work on.  Positions are
+    // visited in order (q, then q + 1 capped at qlimit), which lets the entry of the next one be
+    // read here, a whole step before it is needed.
+    __device__ __forceinline__ void begin(const GemmParams& p, int q, int, int, int qlimit) {
+        const int xg = __builtin_amdgcn_readfirstlane(pend.x);
+        n0a = __builtin_amdgcn_readfirstlane(pend.y);
+        n0b = __builtin_amdgcn_readfirstlane(pend.z);
+        const int h2 = __builtin_amdgcn_readfirstlane(pend.w);
+        const int qn = q + 1 < qlimit ? q + 1 : qlimit;
+        pend = *reinterpret_cast<const v4i*>(tab + 4 * qn);
+        xs2 = xsrc + (size_t)xg * 16 * p.mpad * 16;
+        pbase = reinterpret_cast<const char*>(h2 ? p.F : p.B);
+        prow = (size_t)(((h2 ? p.ldf : p.ldb) + 63) >> 6) * 16384u;
+#pragma unroll
+        for (int j = 0; j < WV; ++j) pcsel[j] = pcb[j] + ((pcf[j] - pcb[j]) & (0u - (unsigned)h2));
+    }
+
+    template <int J>
+    __device__ __forceinline__ void xdma_piece(unsigned char* xstage) {
+        const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+        const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)xstage;
+        const unsigned lds = __builtin_amdgcn_readfirstlane(lds0 + (wave * 64 + GT * J) * 16);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :
+                     : "s"(lds), "v"(xs2 + J * xstride)
+                     : "memory", "m0");
+    }
+
+    // run (digit t, k-half g) of the weight stage: scalar start of the run in the operand, the
+    // lane's column offset, one transfer per wavefront
+    template <int J>
+    __device__ __forceinline__ void wdma_piece(unsigned char* wstage) {
+        const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+        const int run = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * J) / T::BN));   // t * 2 + g
+        const int r0 = (run & 1) ? n0b : n0a;
+        const char* sb = pbase + (size_t)(r0 >> 5) * prow + (size_t)((run & ~1) | ((r0 >> 4) & 1)) * 1024u;
+        const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)wstage;
+        const unsigned lds = __builtin_amdgcn_readfirstlane(lds0 + (wave * 64 + GT * J) * 16);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(lds), "v"(pcsel[J]), "s"(sb)
+                     : "memory", "m0");
+    }
+
+    template <int P, bool SPLIT>
+    __device__ __forceinline__ void piece(const GemmParams&, int, unsigned char* xstage, unsigned char* wstage) {
+        if constexpr (P < XV) xdma_piece<P>(xstage);
+        else if constexpr (P < P_END) wdma_piece<P - XV>(wstage);
+    }
+
+    template <int P0, bool SPLIT, int... Ps>
+    __device__ __forceinline__ void pieces(std::integer_sequence<int, Ps...>, const GemmParams& p,
+                                           int kc, unsigned char* xstage, unsigned char* wstage) {
+        (piece<P0 + Ps, SPLIT>(p, kc, xstage, wstage), ...);
+    }
+};
+
 __device__ __forceinline__ v4i lds_frag(const unsigned char* p) {
     return *reinterpret_cast<const v4i*>(p);
 }
@@ -462,13 +593,12 @@ struct ReadMap {
 // share of the look-ahead pieces (see Loader).  The scheduling fences keep the
 // compiler from regrouping them.  ks_next2 is clamped by the caller: past the
 // end of a segment the look-ahead work is redundant but harmless.
-template <class T, int KIND, int GMODE, bool LISTED, int WM, int WN, int... Ms>
+template <class T, class L, int WM, int WN, int... Ms>
 __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>, const GemmParams& p,
-                                               Loader<T, KIND, GMODE, LISTED>& ld, v16i (&acc)[WM][WN][8],
+                                               L& ld, v16i (&acc)[WM][WN][8],
                                                const unsigned char* xs, const unsigned char* ws,
                                                unsigned char* ws_next, unsigned char* xs_next2,
                                                int a_off, int b_off, int ks_next2, int ks_limit, int KS, int kc) {
-    using L = Loader<T, KIND, GMODE, LISTED>;
     using SM = SlotMap<WM, WN>;
     constexpr int NM = 36 * WM * WN;
     v4i bf[WN][8];
@@ -511,30 +641,32 @@ __device__ __forceinline__ void gemm_step_impl(std::integer_sequence<int, Ms...>
         ...);
     // The activation planes of the next step were requested one step ago; only the loads
     // issued during this step may still be in flight past this point.
-    wait_and_barrier<T::vm_per_step(GMODE)>();
+    wait_and_barrier<L::VM_PER_STEP>();
 }
 
-template <class T, int KIND, int GMODE, bool LISTED, int WM, int WN>
-__device__ __forceinline__ void gemm_step(const GemmParams& p, Loader<T, KIND, GMODE, LISTED>& ld,
+template <class T, class L, int WM, int WN>
+__device__ __forceinline__ void gemm_step(const GemmParams& p, L& ld,
                                           v16i (&acc)[WM][WN][8], const unsigned char* xs,
                                           const unsigned char* ws, unsigned char* ws_next,
                                           unsigned char* xs_next2, int a_off, int b_off,
                                           int ks_next2, int ks_limit, int KS, int kc) {
-    gemm_step_impl<T, KIND, GMODE, LISTED, WM, WN>(std::make_integer_sequence<int, 36 * WM * WN>{}, p, ld, acc,
-                                           xs, ws, ws_next, xs_next2, a_off, b_off, ks_next2, ks_limit,
-                                           KS, kc);
+    gemm_step_impl<T, L, WM, WN>(std::make_integer_sequence<int, 36 * WM * WN>{}, p, ld, acc,
+                                 xs, ws, ws_next, xs_next2, a_off, b_off, ks_next2, ks_limit, KS, kc);
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool LISTED>
-__global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) void ring_gemm_kernel(GemmParams p) {
+__global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMODE))) void ring_gemm_kernel(GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
+    constexpr bool PLANES = is_planes(GMODE);
+    using LD = std::conditional_t<PLANES, PlaneLoader<T, KIND, GMODE, LISTED>, Loader<T, KIND, GMODE, LISTED>>;
     // Three activation stages filled by LDS-DMA two steps ahead, as separate
     // arrays so that the compiler can tell a stage being filled from the one
     // being read; two weight stages written from registers one step ahead.
     __shared__ __align__(16) unsigned char xs0[T::XBYTES];
     __shared__ __align__(16) unsigned char xs1[T::XBYTES];
     __shared__ __align__(16) unsigned char xs2[T::XBYTES];
-    __shared__ __align__(16) unsigned char wsm[T::WSTAGES * T::WBYTES];
+    __shared__ __align__(16) unsigned char wsm[T::wstages(GMODE) * T::WBYTES];
+    __shared__ __align__(16) int steptab[PLANES ? MAX_SEG * 4 : 4];
 
     if (p.tile_sel && *p.tile_sel != p.tile_sel_want) return;   // the other tile shape was chosen
     const int nblk = n_blocks(p);
@@ -567,7 +699,7 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) vo
     const int a_off = (g * T::BM + wm * WM * 32 + r) * 16;
     const int b_off = (g * T::BN + wn * WN * 32 + r) * 16;
 
-    Loader<T, KIND, GMODE, LISTED> ld;
+    LD ld;
 
     // Work units are ordered chunk-major: all tiles for contraction steps
     // [0, CH), then all tiles for [CH, 2 CH), ...  Workgroups that run side by
@@ -634,29 +766,51 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::WG_PER_CU)) vo
 
         // prologue: step ks0 staged, step ks0+1 in flight
         const int ks_last = ks0 + L - 1;
-        {
-            using LD = Loader<T, KIND, GMODE, LISTED>;
+        if constexpr (PLANES) {
+            // the segment's step table first (the stages and the table of the previous segment
+            // are no longer read: every wavefront has passed that segment's last barrier)
+            ld.build_table(p, steptab, ks0, L, KSt, kc);
+            __syncthreads();
+            ld.prime();
+            ld.begin(p, 0, KSt, kc, L - 1);
+            ld.template pieces<0, true>(std::make_integer_sequence<int, LD::P_END>{}, p, kc, xs0, wsm);
+            ld.begin(p, 1 < L - 1 ? 1 : L - 1, KSt, kc, L - 1);
+            ld.template pieces<0, true>(std::make_integer_sequence<int, LD::P_END>{}, p, kc, xs1, wsm + T::WBYTES);
+            wait_and_barrier<0>();
+            // positions of the segment instead of contraction steps; stage i % 3 of both operands
+            for (int i = 0; i < L; i += 3) {
+                const int q2 = i + 2;
+                gemm_step<T, LD, WM, WN>(p, ld, acc, xs0, wsm, wsm + 2 * T::WBYTES, xs2, a_off, b_off,
+                                         q2 < L - 1 ? q2 : L - 1, L - 1, KSt, kc);
+                if (i + 1 < L)
+                    gemm_step<T, LD, WM, WN>(p, ld, acc, xs1, wsm + T::WBYTES, wsm, xs0, a_off, b_off,
+                                             q2 + 1 < L - 1 ? q2 + 1 : L - 1, L - 1, KSt, kc);
+                if (i + 2 < L)
+                    gemm_step<T, LD, WM, WN>(p, ld, acc, xs2, wsm + 2 * T::WBYTES, wsm + T::WBYTES, xs1, a_off, b_off,
+                                             q2 + 2 < L - 1 ? q2 + 2 : L - 1, L - 1, KSt, kc);
+            }
+        } else {
             ld.prime(p, ks0, KSt, kc);
             ld.begin(p, ks0, KSt, kc, ks_last);
             ld.template pieces<LD::P_DMA, false>(std::make_integer_sequence<int, LD::P_END - LD::P_DMA>{}, p, kc, xs0, wsm);
             ld.begin(p, ks0 + 1 < ks_last ? ks0 + 1 : ks_last, KSt, kc, ks_last);
             ld.template pieces<LD::P_DMA, true>(std::make_integer_sequence<int, LD::P_END - LD::P_DMA>{}, p, kc, xs1, wsm);
-        }
-        wait_and_barrier<0>();
+            wait_and_barrier<0>();
 
-        for (int i = 0; i < L; i += 3) {
-            const int k2 = ks0 + i + 2;
-            gemm_step<T, KIND, GMODE, LISTED, WM, WN>(p, ld, acc, xs0, wsm + (i & 1) * T::WBYTES,
-                                              wsm + ((i + 1) & 1) * T::WBYTES, xs2, a_off, b_off,
-                                              k2 < ks_last ? k2 : ks_last, ks_last, KSt, kc);
-            if (i + 1 < L)
-                gemm_step<T, KIND, GMODE, LISTED, WM, WN>(p, ld, acc, xs1, wsm + ((i + 1) & 1) * T::WBYTES,
-                                                  wsm + (i & 1) * T::WBYTES, xs0, a_off, b_off,
-                                                  k2 + 1 < ks_last ? k2 + 1 : ks_last, ks_last, KSt, kc);
-            if (i + 2 < L)
-                gemm_step<T, KIND, GMODE, LISTED, WM, WN>(p, ld, acc, xs2, wsm + (i & 1) * T::WBYTES,
-                                                  wsm + ((i + 1) & 1) * T::WBYTES, xs1, a_off, b_off,
-                                                  k2 + 2 < ks_last ? k2 + 2 : ks_last, ks_last, KSt, kc);
+            for (int i = 0; i < L; i += 3) {
+                const int k2 = ks0 + i + 2;
+                gemm_step<T, LD, WM, WN>(p, ld, acc, xs0, wsm + (i & 1) * T::WBYTES,
+                                         wsm + ((i + 1) & 1) * T::WBYTES, xs2, a_off, b_off,
+                                         k2 < ks_last ? k2 : ks_last, ks_last, KSt, kc);
+                if (i + 1 < L)
+                    gemm_step<T, LD, WM, WN>(p, ld, acc, xs1, wsm + ((i + 1) & 1) * T::WBYTES,
+                                             wsm + (i & 1) * T::WBYTES, xs0, a_off, b_off,
+                                             k2 + 1 < ks_last ? k2 + 1 : ks_last, ks_last, KSt, kc);
+                if (i + 2 < L)
+                    gemm_step<T, LD, WM, WN>(p, ld, acc, xs2, wsm + (i & 1) * T::WBYTES,
+                                             wsm + ((i + 1) & 1) * T::WBYTES, xs1, a_off, b_off,
+                                             k2 + 2 < ks_last ? k2 + 2 : ks_last, ks_last, KSt, kc);
+            }
         }
         // the look-ahead transfers of the last steps are redundant; let them land before the
         // stages are reused
@@ -710,6 +864,26 @@ GemmKernel gemm_kernel_for(const GemmParams& p) {
     }
 }
 
+// The variants that read weight planes: their own translation units (ring_gemm_planes_*.hip).
+template <int WAVES_M, int WAVES_N, int WM, int WN, bool LISTED>
+GemmKernel gemm_planes_kernel_for(const GemmParams& p) {
+    if (p.kind == KIND_SIMM) {
+        if (p.b_full) return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, W_PLANES_GATHER, LISTED>;
+        return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, W_PLANES, LISTED>;
+    }
+    if constexpr (LISTED) {
+        return nullptr;
+    } else {
+        return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, W_PLANES, false>;
+    }
+}
+
+extern template GemmKernel gemm_planes_kernel_for<2, 2, 2, 1, false>(const GemmParams&);
+extern template GemmKernel gemm_planes_kernel_for<2, 2, 1, 1, false>(const GemmParams&);
+extern template GemmKernel gemm_planes_kernel_for<2, 2, 1, 1, true>(const GemmParams&);
+extern template GemmKernel gemm_planes_kernel_for<1, 4, 1, 1, false>(const GemmParams&);
+extern template GemmKernel gemm_planes_kernel_for<1, 4, 1, 1, true>(const GemmParams&);
+
 extern template GemmKernel gemm_kernel_for<2, 2, 2, 1, false>(const GemmParams&);
 extern template GemmKernel gemm_kernel_for<2, 2, 1, 1, false>(const GemmParams&);
 extern template GemmKernel gemm_kernel_for<2, 2, 1, 1, true>(const GemmParams&);
@@ -720,7 +894,20 @@ template <int WAVES_M, int WAVES_N, int WM, int WN>
 int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     GemmKernel kern = nullptr;
-    if (p.step_list) {
+    constexpr bool PLANES_ONLY = WAVES_N == 4 && WN == 1;     // the 32 x 128 tile exists for weight planes only
+    constexpr bool WORDS_ONLY = WAVES_N == 4 && WN == 2;      // the 32 x 256 tile needs two weight stages
+    if (p.w_planes) {
+        if constexpr (WORDS_ONLY) {
+            kern = nullptr;
+        } else if (p.step_list) {
+            if constexpr (WM * WN == 2 && WAVES_N == 2) kern = nullptr;
+            else kern = gemm_planes_kernel_for<WAVES_M, WAVES_N, WM, WN, true>(p);
+        } else {
+            kern = gemm_planes_kernel_for<WAVES_M, WAVES_N, WM, WN, false>(p);
+        }
+    } else if constexpr (PLANES_ONLY) {
+        kern = nullptr;
+    } else if (p.step_list) {
         // per-token row sets: only the tile shapes the dispatch picks for them have such variants
         if constexpr (WM * WN == 2 && WAVES_N == 2) kern = nullptr;
         else kern = gemm_kernel_for<WAVES_M, WAVES_N, WM, WN, true>(p);
@@ -732,7 +919,8 @@ int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
     const long kt = 2l * p.ks_cap;
     const long units_cap = tiles * kt;
     // a chip-sized grid, shrunk when there is too little work to share out
-    long grid = (ctx->num_cu / 8) * 8 * T::WG_PER_CU;
+    const int gmode_lds = p.w_planes ? W_PLANES : GATHER_NONE;    // what decides the LDS footprint
+    long grid = (ctx->num_cu / 8) * 8 * T::wg_per_cu(gmode_lds);
     if (grid < 8) grid = 8;
     const long want = (units_cap + 1) / 2;      // at least two contraction steps per workgroup
     if (want < grid) grid = want < 8 ? (want < 1 ? 1 : want) : (want / 8) * 8;

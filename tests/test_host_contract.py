@@ -59,3 +59,16 @@ def test_null_context_is_rejected_without_touching_a_device():
     assert lib.comet_mask_share(None, None, None, None, 16) == -1          # COMET_EINVAL
     assert lib.comet_truncate_share(None, 0, None, None, 16, 16) == -1
     assert lib.comet_permute_mask(None, None, None, None, None, 4, 4, 0, 1) == -1
+
+
+def test_device_side_stream_equals_the_host_stream():
+    """bench.py draws its large inputs with torch on the device; the words must be the ones the
+    tests draw on the host from the same (seed, stream, index)."""
+    import numpy as np
+    torch = pytest.importorskip("torch")
+    from workloads import rng
+    for seed, stream, n, off in ((rng.BASE_SEED, 300005, 4099, 0), (1, 99999, 77, 12345),
+                                 (rng.BASE_SEED, 7, 5, 1 << 40)):
+        host = rng.uniform_u64(seed, stream, n, off)
+        dev = rng.uniform_u64_torch(seed, stream, n, "cpu", off).numpy().view(np.uint64)
+        assert np.array_equal(host, dev)

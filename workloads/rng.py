@@ -66,3 +66,35 @@ def gaussian_f64(seed: int, stream_id: int, n: int) -> np.ndarray:
     out[0::2] = r * np.cos(t)
     out[1::2] = r * np.sin(t)
     return out[:n]
+
+
+# ---------------------------------------------------------------------------
+# the same streams drawn on a torch device (plumbing for large device-resident inputs)
+# ---------------------------------------------------------------------------
+
+def _s64(c: int) -> int:
+    """A 64-bit constant as the signed value with the same bits (torch has no uint64 arithmetic)."""
+    c &= _MASK64
+    return c - (1 << 64) if c >= (1 << 63) else c
+
+
+def uniform_u64_torch(seed: int, stream_id: int, n: int, device, offset: int = 0):
+    """Elements ``offset .. offset+n`` of stream ``(seed, stream_id)`` as an ``int64`` torch
+    tensor on ``device`` whose bits equal :func:`uniform_u64` word for word (two's-complement
+    wrap-around multiplication, logical shifts emulated by masking)."""
+    import torch
+    key = _s64(int(_stream_key(seed, stream_id)))
+    out = torch.empty(n, dtype=torch.int64, device=device)
+    chunk = 1 << 26
+
+    def lsr(z, s):
+        return (z >> s) & ((1 << (64 - s)) - 1)
+
+    for s in range(0, n, chunk):
+        e = min(n, s + chunk)
+        z = torch.arange(offset + s + 1, offset + e + 1, dtype=torch.int64, device=device)
+        z = z * _s64(int(_GOLDEN)) + key
+        z = (z ^ lsr(z, 30)) * _s64(int(_M1))
+        z = (z ^ lsr(z, 27)) * _s64(int(_M2))
+        out[s:e] = z ^ lsr(z, 31)
+    return out
