@@ -7,13 +7,18 @@ projection of the layer (gate / up: SOMM, down: SIMM) mask both parties'
 shares, open them, and compute both parties' output shares.  All inputs are
 resident in HBM before the timed region starts.
 
-Prints ONE JSON line.  ``value`` is ring-GEMM throughput: algorithmic ring
+Prints ONE JSON line.  ``value`` is ring-GEMM throughput of the headline
+workload (config 3 unless ``--workload`` says otherwise): algorithmic ring
 operations (1 multiply-accumulate mod 2^64 = 2 ops, two products per party per
 projection -- the minimum for Eq. 1) of one step divided by the step time.
 Both simulated parties run on the same GPU one after the other, so this is the
-rate one party's GPU sustains.
+rate one party's GPU sustains.  ``configs`` holds the same measurement, with
+fewer steps, for every configuration (c1 .. c5 at all five densities), each with
+the roofline that bounds it, the bytes the two parties would exchange (cost
+model of the optimality appendix) and a check of a block of output rows against
+the CPU oracle.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--configs all]
 """
 from __future__ import annotations
 
@@ -31,12 +36,16 @@ METRIC = "sparse secret-shared FFN ring-GEMM Gop/s (mod 2^64) per party; % of ro
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 INT8_OPS_PER_RING_MAC = 72   # 36 digit products, 2 ops each
+ALL_CONFIGS = ["c1", "c2", "c3", "c4", "c5_d100", "c5_d050", "c5_d025", "c5_d010", "c5_d005"]
 
-# HBM bytes per ring-GEMM launch (average over the launches of one step) from rocprofv3 --pmc
+# HBM bytes per share-kernel launch (average over the launches of one step) from rocprofv3 --pmc
 # runs of this file: FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for
-# the copy probe of known size in the same run; the summaries are under profiles/.  None until
-# measured for that workload.
-GEMM_TRAFFIC_BYTES = {"c3": 199303800, "c4": 987125342}
+# the copy probe of known size in the same run.  The summaries, with the commands, are the
+# files named here under profiles/.  None until measured for that workload and operand format.
+GEMM_TRAFFIC = {
+    ("c3", "words"): (199303800, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
+    ("c4", "words"): (987125342, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
+}
 
 
 def log(msg):
@@ -56,13 +65,20 @@ def parse_workload(name):
 
 
 class Layer:
-    """Device buffers of one sparse FFN layer and the step that runs the path."""
+    """Device buffers of one sparse FFN layer and the step that runs the path.
 
-    def __init__(self, ctx, cfg, seed):
+    Shares and triple parts are the words of the seeded streams the GPU tests draw on the host
+    (``workloads.rng``, same seed, stream and index), generated on the device; the mask comes
+    from ``workloads.configs``.  ``planes``: the weight-side operands of the share calls travel
+    as digit planes -- F is opened directly in that format (``comet_open_weight_planes``), the
+    triple shares B_i are packed once, outside the step (offline material, Sec. 3.2)."""
+
+    def __init__(self, ctx, cfg, seed, planes):
         import numpy as np
         import torch
-        from workloads import configs
+        from workloads import configs, rng
         self.ctx, self.cfg = ctx, cfg
+        self.planes = bool(planes) and cfg.tokens > 8      # the few-row kernel reads words
         dev = torch.device("cuda:0")
         self.mask_np = configs.token_masks(cfg, seed)
         self.mask = torch.from_numpy(self.mask_np).to(dev)
@@ -70,36 +86,79 @@ class Layer:
         self.n_act = self.n_blk * cfg.bs
         self.idx = torch.zeros(cfg.nb, dtype=torch.int32, device=dev)
         self.n_dev = torch.zeros(1, dtype=torch.int32, device=dev)
-        gen = torch.Generator(device=dev)
 
-        def words(stream, *shape):
-            # additive shares and triple parts are uniform over Z_{2^64} whatever the secrets are
-            gen.manual_seed(seed * 1000003 + stream)
-            return torch.randint(-(2 ** 63), 2 ** 63 - 1, shape, dtype=torch.int64, device=dev,
-                                 generator=gen)
+        def words(mm, role, *shape, shift=0):
+            n = 1
+            for v in shape:
+                n *= v
+            return rng.uniform_u64_torch(seed, configs.stream_id(cfg, mm.index, role) + shift, n, dev).view(*shape)
 
         self.mm = []
         for mm in cfg.matmuls:
-            sid = lambda role, party=0: configs.stream_id(cfg, mm.index, role) * 2 + party
             b = dict(mm=mm)
-            b["x"] = [words(sid(0, i), mm.m, mm.k) for i in (0, 1)]
-            b["y"] = [words(sid(1, i), mm.k, mm.n) for i in (0, 1)]
-            b["a"] = [words(sid(4, i), mm.m, mm.k) for i in (0, 1)]
-            b["b"] = [words(sid(5, i), mm.k, mm.n) for i in (0, 1)]
+            # additive shares and triple shares are uniform over Z_{2^64} whatever the secrets are
+            b["x"] = [words(mm, configs.R_XSPLIT, mm.m, mm.k), words(mm, configs.R_X, mm.m, mm.k)]
+            b["y"] = [words(mm, configs.R_YSPLIT, mm.k, mm.n), words(mm, configs.R_Y, mm.k, mm.n)]
+            b["a"] = [words(mm, configs.R_ASPLIT, mm.m, mm.k), words(mm, configs.R_A, mm.m, mm.k)]
+            b["b"] = [words(mm, configs.R_BSPLIT, mm.k, mm.n), words(mm, configs.R_B, mm.k, mm.n)]
             if mm.kind == "somm":
                 dshape, gshape, zshape = (mm.m, mm.k), (mm.k, self.n_act), (mm.m, self.n_act)
             else:
                 dshape, gshape, zshape = (mm.m, self.n_act), (self.n_act, mm.n), (mm.m, mm.n)
-            b["c"] = [words(sid(8, i), *zshape) for i in (0, 1)]
+            b["c"] = [words(mm, configs.R_CSPLIT, *zshape, shift=50 * i) for i in (0, 1)]
             b["d"] = [torch.empty(dshape, dtype=torch.int64, device=dev) for _ in (0, 1)]
             b["g"] = [torch.empty(gshape, dtype=torch.int64, device=dev) for _ in (0, 1)]
             b["e"] = torch.empty(dshape, dtype=torch.int64, device=dev)
-            b["f"] = torch.empty(gshape, dtype=torch.int64, device=dev)
             b["z"] = [torch.empty(zshape, dtype=torch.int64, device=dev) for _ in (0, 1)]
-            b["macs_per_launch"] = 2 * mm.m * (mm.k if mm.kind == "somm" else self.n_act) * \
-                (self.n_act if mm.kind == "somm" else mm.n)
+            if self.planes:
+                b["bw"] = [ctx.open_weight_planes(b["b"][i]) for i in (0, 1)]       # offline
+                b["f"] = ctx.open_weight_planes(b["g"][0], b["g"][1])               # buffer of the right size
+            else:
+                b["bw"] = b["b"]
+                b["f"] = torch.empty(gshape, dtype=torch.int64, device=dev)
+            k_eff, n_eff = (mm.k, self.n_act) if mm.kind == "somm" else (self.n_act, mm.n)
+            b["macs_per_launch"] = 2 * mm.m * k_eff * n_eff
+            # ring elements one party sends for this product (its masked shares of both operands)
+            b["sent_elems"] = mm.m * k_eff + k_eff * n_eff
+            b["sent_elems_dense"] = mm.m * mm.k + mm.k * mm.n
             self.mm.append(b)
         self.ring_ops_per_step = sum(2 * 2 * b["macs_per_launch"] for b in self.mm)   # 2 parties, 2 ops/MAC
+
+    def _mask_and_open(self, ctx, b, idx, n_dev):
+        import paper_2505_07239_amd as comet
+        cfg, mm = self.cfg, b["mm"]
+        for i in (0, 1):
+            if mm.kind == "somm":
+                ctx.mask_share(b["x"][i], b["a"][i], out=b["d"][i])
+                ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_COLS, cfg.bs, idx, n_dev, self.n_blk,
+                                      out=b["g"][i])
+            else:
+                ctx.mask_share_gather(b["x"][i], b["a"][i], comet.AXIS_COLS, cfg.bs, idx, n_dev, self.n_blk,
+                                      out=b["d"][i])
+                ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_ROWS, cfg.bs, idx, n_dev, self.n_blk,
+                                      out=b["g"][i])
+        ctx.open(b["d"][0], b["d"][1], out=b["e"])
+        if self.planes:
+            ctx.open_weight_planes(b["g"][0], b["g"][1], out=b["f"].buf)
+        else:
+            ctx.open(b["g"][0], b["g"][1], out=b["f"])
+
+    def _shares(self, ctx, b, idx, n_dev):
+        cfg, mm = self.cfg, b["mm"]
+        for i in (0, 1):
+            if mm.kind == "somm":
+                ctx.somm_share(i, cfg.bs, idx, n_dev, self.n_blk, b["e"], b["f"], b["a"][i], b["bw"][i],
+                               b["c"][i], out=b["z"][i])
+            else:
+                ctx.simm_share(i, cfg.bs, idx, n_dev, self.n_blk, b["e"], b["f"], b["a"][i], b["bw"][i],
+                               b["c"][i], out=b["z"][i])
+
+    def step(self):
+        ctx = self.ctx
+        ctx.compact_mask(self.mask, self.idx, self.n_dev)
+        for b in self.mm:
+            self._mask_and_open(ctx, b, self.idx, self.n_dev)
+            self._shares(ctx, b, self.idx, self.n_dev)
 
     # ---- the same step with the bandwidth-bound kernels and the ring GEMMs on two streams ----
     def enable_overlap(self, ctx_stream_kernels):
@@ -110,7 +169,6 @@ class Layer:
         import torch
         self.ctx_ew = ctx_stream_kernels
         self.s_ew, self.s_gemm = torch.cuda.Stream(), torch.cuda.Stream()
-        dev = self.idx.device
         self.sets = []
         for q in (0, 1):
             st = {"idx": self.idx if q == 0 else torch.zeros_like(self.idx),
@@ -122,80 +180,83 @@ class Layer:
                     c2 = dict(b)
                     for key in ("d", "g", "z"):
                         c2[key] = [torch.empty_like(t) for t in b[key]]
-                    for key in ("e", "f"):
-                        c2[key] = torch.empty_like(b[key])
+                    c2["e"] = torch.empty_like(b["e"])
+                    c2["f"] = self.ctx.open_weight_planes(b["g"][0], b["g"][1]) if self.planes \
+                        else torch.empty_like(b["f"])
                     st["mm"].append(c2)
             st["ew_done"] = [torch.cuda.Event() for _ in self.mm]
             st["gemm_done"] = torch.cuda.Event()
             st["gemm_done"].record(torch.cuda.current_stream())
             self.sets.append(st)
         self.parity = 0
-        del dev
 
     def step_overlapped(self):
         import torch
-        import paper_2505_07239_amd as comet
-        cfg = self.cfg
         st = self.sets[self.parity]
         self.parity ^= 1
         with torch.cuda.stream(self.s_ew):
             self.s_ew.wait_event(st["gemm_done"])          # the GEMMs that last read this set are done
-            ctx = self.ctx_ew
-            ctx.compact_mask(self.mask, st["idx"], st["n_dev"])
+            self.ctx_ew.compact_mask(self.mask, st["idx"], st["n_dev"])
             for j, b in enumerate(st["mm"]):
-                mm = b["mm"]
-                for i in (0, 1):
-                    if mm.kind == "somm":
-                        ctx.mask_share(b["x"][i], b["a"][i], out=b["d"][i])
-                        ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_COLS, cfg.bs, st["idx"],
-                                              st["n_dev"], self.n_blk, out=b["g"][i])
-                    else:
-                        ctx.mask_share_gather(b["x"][i], b["a"][i], comet.AXIS_COLS, cfg.bs, st["idx"],
-                                              st["n_dev"], self.n_blk, out=b["d"][i])
-                        ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_ROWS, cfg.bs, st["idx"],
-                                              st["n_dev"], self.n_blk, out=b["g"][i])
-                ctx.open(b["d"][0], b["d"][1], out=b["e"])
-                ctx.open(b["g"][0], b["g"][1], out=b["f"])
+                self._mask_and_open(self.ctx_ew, b, st["idx"], st["n_dev"])
                 st["ew_done"][j].record(self.s_ew)
         with torch.cuda.stream(self.s_gemm):
-            ctx = self.ctx
             for j, b in enumerate(st["mm"]):
-                mm = b["mm"]
                 self.s_gemm.wait_event(st["ew_done"][j])
-                for i in (0, 1):
-                    if mm.kind == "somm":
-                        ctx.somm_share(i, cfg.bs, st["idx"], st["n_dev"], self.n_blk, b["e"], b["f"],
-                                       b["a"][i], b["b"][i], b["c"][i], out=b["z"][i])
-                    else:
-                        ctx.simm_share(i, cfg.bs, st["idx"], st["n_dev"], self.n_blk, b["e"], b["f"],
-                                       b["a"][i], b["b"][i], b["c"][i], out=b["z"][i])
+                self._shares(self.ctx, b, st["idx"], st["n_dev"])
             st["gemm_done"].record(self.s_gemm)
 
-    def step(self):
-        import paper_2505_07239_amd as comet
-        ctx, cfg = self.ctx, self.cfg
-        ctx.compact_mask(self.mask, self.idx, self.n_dev)
-        for b in self.mm:
-            mm = b["mm"]
-            for i in (0, 1):
-                if mm.kind == "somm":
-                    ctx.mask_share(b["x"][i], b["a"][i], out=b["d"][i])
-                    ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_COLS, cfg.bs, self.idx,
-                                          self.n_dev, self.n_blk, out=b["g"][i])
-                else:
-                    ctx.mask_share_gather(b["x"][i], b["a"][i], comet.AXIS_COLS, cfg.bs, self.idx,
-                                          self.n_dev, self.n_blk, out=b["d"][i])
-                    ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_ROWS, cfg.bs, self.idx,
-                                          self.n_dev, self.n_blk, out=b["g"][i])
-            ctx.open(b["d"][0], b["d"][1], out=b["e"])
-            ctx.open(b["g"][0], b["g"][1], out=b["f"])
-            for i in (0, 1):
-                if mm.kind == "somm":
-                    ctx.somm_share(i, cfg.bs, self.idx, self.n_dev, self.n_blk, b["e"], b["f"],
-                                   b["a"][i], b["b"][i], b["c"][i], out=b["z"][i])
-                else:
-                    ctx.simm_share(i, cfg.bs, self.idx, self.n_dev, self.n_blk, b["e"], b["f"],
-                                   b["a"][i], b["b"][i], b["c"][i], out=b["z"][i])
+
+def run_timed(ctx, layer, steps, warmup, run_step=None):
+    """W untimed steps, then exactly K timed ones between two synchronisations; the share kernel
+    alone is timed with HIP events inside the library.  Returns (ms per step, share kernel us)."""
+    import torch
+    run_step = run_step or layer.step
+    for _ in range(warmup):
+        run_step()
+    torch.cuda.synchronize()
+    ctx.timing_begin(2 * len(layer.mm) * steps)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    gemm_ms, n_timed = ctx.timing_end()
+    return (t1 - t0) * 1e3 / steps, gemm_ms, n_timed
+
+
+def roofline_of(layer, wname, ms_per_step, gemm_ms, n_timed, steps, skinny_forced, probes):
+    """The roofline object of the dominant kernel of a workload."""
+    cfg = layer.cfg
+    fmt = "planes" if layer.planes else "words"
+    traffic, source = GEMM_TRAFFIC.get((wname, fmt), (None, None))
+    macs_per_launch = sum(b["macs_per_launch"] for b in layer.mm) / len(layer.mm)
+    avg_ms = gemm_ms / max(n_timed, 1)
+    share = avg_ms * 2 * len(layer.mm) / ms_per_step
+    common = {"traffic": traffic, "traffic_source": source, "avg_launch_ms": avg_ms, "launches_timed": n_timed,
+              "ring_macs_per_launch": macs_per_launch, "gemm_share_of_step": share, "weight_operands": fmt}
+    if cfg.tokens <= 8 and not skinny_forced:
+        # a few activation rows: the share calls take the vector-ALU kernel, bound by reading the
+        # two weight-side operands (B_i and F, kc x n words each) once per launch
+        wbytes = macs_per_launch / cfg.tokens * 8.0
+        ach = wbytes / (avg_ms * 1e-3) / 1e9
+        r = {"bound": "hbm", "kernel": "ring_skinny_kernel", "achieved": ach, "peak": PEAK_HBM_GBS,
+             "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+             "note": "algorithmic bytes: the weight-side operands B_i and F of one launch, 8 bytes "
+                     "per word, read once"}
+        if probes:
+            r["frac_of_measured_copy"] = ach / probes["copy_GBs"]
+    else:
+        ach = INT8_OPS_PER_RING_MAC * macs_per_launch / (avg_ms * 1e-3) / 1e12
+        r = {"bound": "mfma", "kernel": "ring_gemm_kernel", "achieved": ach, "peak": PEAK_INT8_TOPS,
+             "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS,
+             "note": "algorithmic int8 ops: 36 digit products x 2 ops per ring MAC, two products per "
+                     "party (2*m*k*n_act ring MACs per launch)"}
+        if probes:
+            r["frac_of_measured_mfma_issue"] = ach / probes["mfma_i8_issue_TOPs"]
+            r["frac_of_measured_mfma_issue_random_operands"] = ach / probes["mfma_i8_issue_random_operands_TOPs"]
+    r.update(common)
+    return r
 
 
 def cpu_baseline(layer, budget_s=20.0):
@@ -215,7 +276,9 @@ def cpu_baseline(layer, budget_s=20.0):
     one_ops, one_s = 0.0, 0.0                 # the one-row trials: one output row, so one thread
     for b in layer.mm:
         mm = b["mm"]
-        e, f = host(b["e"]), host(b["f"])
+        # the opened operands as words: E as the GPU wrote it, F from the two masked shares
+        # (the GPU path may hold F only as digit planes)
+        e, f = host(b["e"]), co.open_(host(b["g"][0]), host(b["g"][1]))
         k_eff, n_eff = e.shape[1], f.shape[1]
         a_sel, b_sel = [], []
         for i in (0, 1):
@@ -249,6 +312,52 @@ def cpu_baseline(layer, budget_s=20.0):
             "matches_gpu": bool(ok)}
 
 
+def config_entry(ctx, name, probes, planes, skinny_forced, steps=10, warmup=3, layer=None, timing=None,
+                 check=None):
+    """One configuration: short timed run, roofline, exchanged bytes, oracle check of a row block."""
+    import torch
+    from workloads import rng
+    cfg, wname = parse_workload(name)
+    own = layer is None
+    if own:
+        layer = Layer(ctx, cfg, rng.BASE_SEED, planes)
+        timing = run_timed(ctx, layer, steps, warmup)
+    ms, gemm_ms, n_timed = timing
+    roof = roofline_of(layer, wname, ms, gemm_ms, n_timed, steps, skinny_forced, probes)
+    if cfg.cid == 1:
+        # a few microseconds of arithmetic per launch: launch latency decides, no roofline applies
+        roof = {"bound": "latency", "kernel": roof["kernel"], "achieved": None, "peak": None, "unit": None,
+                "frac": None, "avg_launch_ms": roof["avg_launch_ms"], "weight_operands": roof["weight_operands"]}
+    if check is None:
+        check = cpu_baseline(layer, budget_s=1.0)
+    sent = sum(b["sent_elems"] for b in layer.mm)
+    dense = sum(b["sent_elems_dense"] for b in layer.mm)
+    entry = {
+        "workload": "%s, %d tokens, d_model %d, d_ff %d, block %d, %d of %d blocks kept; %s" %
+                    (cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs, layer.n_blk, cfg.nb,
+                     "+".join(m.name for m in cfg.matmuls)),
+        "ms_per_step": ms, "steps": steps if own else None,
+        "gops_per_party": layer.ring_ops_per_step / (ms * 1e-3) / 1e9,
+        "share_kernel_us": gemm_ms / max(n_timed, 1) * 1e3,
+        "ring_macs_per_launch": sum(b["macs_per_launch"] for b in layer.mm) / len(layer.mm),
+        "roofline": {k: roof.get(k) for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "traffic")},
+        "frac_of_measured_mfma_issue": roof.get("frac_of_measured_mfma_issue"),
+        "frac_of_measured_copy": roof.get("frac_of_measured_copy"),
+        "weight_operands": roof["weight_operands"],
+        # cost model of the optimality appendix: every party sends its masked shares of both
+        # operands of every product once, 8 bytes per ring element, two directions
+        "exchanged_bytes_both_directions": 8 * sent * 2,
+        "exchanged_bytes_dense_layer": 8 * dense * 2,
+        "exchange_reduction": dense / sent,
+        "oracle_check": check["sample"],
+        "matches_gpu": check["matches_gpu"],
+    }
+    if own:
+        del layer
+        torch.cuda.empty_cache()
+    return entry
+
+
 def general_forms(ctx, timed):
     """Protocols 2 and 3 with per-token masks on a batch of four unrelated requests (256 tokens,
     LLaMA-7B gate projection, 15 % of the blocks per token): component search, the share
@@ -264,12 +373,9 @@ def general_forms(ctx, timed):
     comp = ctx.components(tm)
     torch.cuda.synchronize()
     n_row, n_blk, n_comp = (int(comp[q].item()) for q in ("n_row", "n_blk", "n_comp"))
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(77)
-    words = lambda *shape: torch.randint(-(2 ** 63), 2 ** 63 - 1, shape, dtype=torch.int64, device=dev,
-                                         generator=gen)
+    words = lambda st, *shape: rng.uniform_u64_torch(rng.BASE_SEED, 9000 + st, int(np.prod(shape)), dev).view(*shape)
     n_act = n_blk * bs
-    e, a, f, b, c = words(m, k), words(m, k), words(k, n_act), words(k, nb * bs), words(m, n_act)
+    e, a, f, b, c = words(1, m, k), words(2, m, k), words(3, k, n_act), words(4, k, nb * bs), words(5, m, n_act)
     z = torch.empty_like(c)
     out = {"general_n_components": n_comp, "general_rows": n_row, "general_blocks": n_blk}
     out["components_us"] = timed(lambda: ctx.components(tm), reps=20) * 1e6
@@ -288,7 +394,7 @@ def general_forms(ctx, timed):
     # down projection with per-token row sets (same masks, union of the blocks contracted)
     idx, n_dev = ctx.compact_mask(tm)
     kc = n_blk * bs
-    e2, a2, f2, b2, c2 = words(m, kc), words(m, nb * bs), words(kc, k), words(nb * bs, k), words(m, k)
+    e2, a2, f2, b2, c2 = words(6, m, kc), words(7, m, nb * bs), words(8, kc, k), words(9, nb * bs, k), words(10, m, k)
     z2 = torch.empty_like(c2)
     t_rows = timed(lambda: ctx.simm_share_masked(1, bs, idx, n_dev, n_blk, tm, e2, f2, a2, b2, c2, out=z2),
                    reps=10)
@@ -298,36 +404,40 @@ def general_forms(ctx, timed):
     return out
 
 
-def weight_layouts(ctx, timed):
-    """SOMM of the LLaMA-7B gate projection (256 tokens, 52 of 344 blocks) with the weight side
-    stored row-major (d x f, kept neurons are 256-byte segments of every row) and neuron-major
-    (f x d, a kept neuron is one contiguous row): the indexed masking of the weights and the
-    share call, each with the full-size triple part indexed in the kernel."""
+def weight_side_masking(ctx, timed_rotating):
+    """Indexed masking of the weight side of the LLaMA-7B gate projection (4096 x 11008 words,
+    52 of 344 blocks of 32): row-major weights (kept neurons are 256-byte segments of every row)
+    and neuron-major weights (a kept neuron is one contiguous row), each repeated on ONE pair of
+    input buffers (the kept part, 109 MB, then stays in the last-level cache) and on FOUR pairs
+    in rotation (2.9 GB: every call reads from HBM, which is what a layer step sees)."""
+    import numpy as np
     import torch
     import paper_2505_07239_amd as comet
     from workloads import masks, rng
-    m, k, nb, bs = 256, 4096, 344, 32
+    k, nb, bs = 4096, 344, 32
     dev = torch.device("cuda:0")
     mask = masks.clustered_block_mask(rng.BASE_SEED, 9100, nb, 0.15, 4.0)[None, :]
     idx, n_dev = ctx.compact_mask(torch.from_numpy(mask).to(dev))
     t_blk = int(n_dev.item())
     n_act = t_blk * bs
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(79)
-    words = lambda *shape: torch.randint(-(2 ** 63), 2 ** 63 - 1, shape, dtype=torch.int64, device=dev,
-                                         generator=gen)
-    e, a, c = words(m, k), words(m, k), words(m, n_act)
-    z = torch.empty_like(c)
+    sets = [(rng.uniform_u64_torch(rng.BASE_SEED, 9100 + 2 * q, k * nb * bs, dev),
+             rng.uniform_u64_torch(rng.BASE_SEED, 9101 + 2 * q, k * nb * bs, dev)) for q in range(4)]
     out = {}
     for name, tr in (("row_major", False), ("neuron_major", True)):
-        y, b = (words(nb * bs, k), words(nb * bs, k)) if tr else (words(k, nb * bs), words(k, nb * bs))
+        shape = (nb * bs, k) if tr else (k, nb * bs)
         g = torch.empty((n_act, k) if tr else (k, n_act), dtype=torch.int64, device=dev)
         axis = comet.AXIS_ROWS if tr else comet.AXIS_COLS
-        t = timed(lambda: ctx.mask_share_gather(y, b, axis, bs, idx, n_dev, t_blk, out=g), reps=20)
-        out["somm_weights_%s_mask_GBs" % name] = 24.0 * k * n_act / t / 1e9
-        t = timed(lambda: ctx.somm_share(1, bs, idx, n_dev, t_blk, e, g, a, b, c, neuron_major=tr, out=z),
-                  reps=10)
-        out["somm_weights_%s_share_us" % name] = t * 1e6
+        call = lambda q: ctx.mask_share_gather(sets[q][0].view(*shape), sets[q][1].view(*shape), axis, bs, idx,
+                                               n_dev, t_blk, out=g)
+        out["somm_weights_%s_mask_GBs" % name] = 24.0 * k * n_act / timed_rotating(call, 1) / 1e9
+        out["somm_weights_%s_mask_from_hbm_GBs" % name] = 24.0 * k * n_act / timed_rotating(call, 4) / 1e9
+    # the opening of the masked weights written as digit planes, next to the plain opening
+    g0, g1 = sets[0][0][:k * n_act].view(k, n_act), sets[1][0][:k * n_act].view(k, n_act)
+    o = torch.empty_like(g0)
+    out["open_GBs_gate_weights"] = 24.0 * k * n_act / timed_rotating(lambda q: ctx.open(g0, g1, out=o), 1) / 1e9
+    pl = ctx.open_weight_planes(g0, g1)
+    out["open_weight_planes_GBs_gate_weights"] = \
+        24.0 * k * n_act / timed_rotating(lambda q: ctx.open_weight_planes(g0, g1, out=pl.buf), 1) / 1e9
     return out
 
 
@@ -336,13 +446,13 @@ def glue_steps(ctx, timed):
     activations of 4096 tokens at the FFN width): achieved GB/s of algorithmic bytes."""
     import torch
     import paper_2505_07239_amd as comet
+    from workloads import rng
     rows, cols, bs = 4096, 11008, 32
     dev = torch.device("cuda:0")
+    words = lambda st, *shape: rng.uniform_u64_torch(rng.BASE_SEED, 9200 + st, shape[0] * shape[1], dev).view(*shape)
+    x, mk, o = words(1, rows, cols), words(2, rows, cols), torch.empty((rows, cols), dtype=torch.int64, device=dev)
     gen = torch.Generator(device=dev)
     gen.manual_seed(78)
-    words = lambda *shape: torch.randint(-(2 ** 63), 2 ** 63 - 1, shape, dtype=torch.int64, device=dev,
-                                         generator=gen)
-    x, mk, o = words(rows, cols), words(rows, cols), torch.empty((rows, cols), dtype=torch.int64, device=dev)
     pc = torch.randperm(cols, device=dev, generator=gen).to(torch.int32)
     pr = torch.randperm(rows, device=dev, generator=gen).to(torch.int32)
     n = rows * cols
@@ -356,7 +466,7 @@ def glue_steps(ctx, timed):
     keep = 52
     idx = (torch.arange(keep, device=dev, dtype=torch.int32) * 6).contiguous()
     nd = torch.tensor([keep], dtype=torch.int32, device=dev)
-    c = words(rows, keep * bs)
+    c = words(3, rows, keep * bs)
     t = timed(lambda: ctx.scatter_cols(c, bs, idx, nd, keep, cols, out=o), reps=10)
     out["scatter_GBs"] = (8.0 * n + 16.0 * rows * keep * bs) / t / 1e9   # zero fill + kept blocks read and written
     return out
@@ -365,7 +475,7 @@ def glue_steps(ctx, timed):
 def micro(ctx, layer):
     """Per-kernel yardsticks on the same device (stderr + returned dict)."""
     import torch
-    from workloads import masks
+    from workloads import masks, rng
     out = {}
 
     def timed(fn, reps=20):
@@ -379,9 +489,21 @@ def micro(ctx, layer):
         torch.cuda.synchronize()
         return s.elapsed_time(e) / reps * 1e-3
 
+    def timed_rotating(call, n_sets, reps=24):
+        for q in range(n_sets):
+            call(q)
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for r in range(reps):
+            call(r % n_sets)
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) / reps * 1e-3
+
     n = 11008 * 4096                                  # weight side of the dense down projection
-    a = torch.randint(-(2 ** 63), 2 ** 63 - 1, (n,), dtype=torch.int64, device="cuda")
-    b = torch.randint(-(2 ** 63), 2 ** 63 - 1, (n,), dtype=torch.int64, device="cuda")
+    a = rng.uniform_u64_torch(rng.BASE_SEED, 9301, n, "cuda")
+    b = rng.uniform_u64_torch(rng.BASE_SEED, 9302, n, "cuda")
     o = torch.empty_like(a)
     t = timed(lambda: ctx.open(a, b, out=o))
     out["open_GBs"] = 24.0 * n / t / 1e9
@@ -403,7 +525,7 @@ def micro(ctx, layer):
     out["compact_layer_mask_us"] = t * 1e6
     out.update(general_forms(ctx, timed))
     out.update(glue_steps(ctx, timed))
-    out.update(weight_layouts(ctx, timed))
+    out.update(weight_side_masking(ctx, timed_rotating))
     macs = ctx.probe_mfma_i8(1024, 2000)
     t = timed(lambda: ctx.probe_mfma_i8(1024, 2000), reps=5)
     out["mfma_i8_issue_TOPs"] = 2.0 * macs / t / 1e12
@@ -425,7 +547,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3",
-                    help="c1..c4, c5_d100 / c5_d050 / c5_d025 / c5_d010 / c5_d005")
+                    help="headline workload: c1..c4, c5_d100 / c5_d050 / c5_d025 / c5_d010 / c5_d005")
+    ap.add_argument("--configs", default="all",
+                    help="configurations measured besides the headline: all, none, or a comma list")
+    ap.add_argument("--weights", default="planes", choices=["planes", "words"],
+                    help="format of the weight-side operands of the share calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true")
     ap.add_argument("--overlap", action="store_true",
@@ -460,29 +586,22 @@ def main():
     ctx.set_tuning(comet.TUNE_GEMM_TILE, args.gemm_tile)
     ctx.set_tuning(comet.TUNE_SKINNY, args.skinny)
     ctx.set_tuning(comet.TUNE_SKINNY_SLICES, args.skinny_slices)
-    layer = Layer(ctx, cfg, rng.BASE_SEED)
-    log("workload %s: %s, m=%d d=%d f=%d bs=%d kept blocks %d/%d (n_act=%d), %.2f G ring ops/step" %
-        (wname, cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs, layer.n_blk, cfg.nb,
-         layer.n_act, layer.ring_ops_per_step / 1e9))
+    planes = args.weights == "planes"
+    layer = Layer(ctx, cfg, rng.BASE_SEED, planes)
+    log("workload %s: %s, m=%d d=%d f=%d bs=%d kept blocks %d/%d (n_act=%d), %.2f G ring ops/step, weight "
+        "operands as %s" % (wname, cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs, layer.n_blk, cfg.nb,
+                            layer.n_act, layer.ring_ops_per_step / 1e9, "planes" if layer.planes else "words"))
 
     run_step = layer.step
     if args.overlap:
         ctx_ew = comet.Context(0)
         layer.enable_overlap(ctx_ew)
         run_step = layer.step_overlapped
-    for _ in range(args.warmup):
-        run_step()
-    torch.cuda.synchronize()
-    launches = 2 * len(layer.mm) * args.steps
     if args.graph:
         # One step captured in a HIP graph (every call only enqueues kernels) and replayed: the
         # launch gaps between the thirty-odd kernels of a step go away.  The share kernel is timed
         # with HIP events in an eager pass first, since events do not work inside a replay.
-        ctx.timing_begin(launches)
-        for _ in range(args.steps):
-            layer.step()
-        torch.cuda.synchronize()
-        gemm_ms, n_timed = ctx.timing_end()
+        _, gemm_ms, n_timed = run_timed(ctx, layer, args.steps, args.warmup)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             layer.step()
@@ -492,21 +611,16 @@ def main():
         for _ in range(args.steps):
             graph.replay()
         torch.cuda.synchronize()
-        t1 = time.perf_counter()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     else:
-        ctx.timing_begin(launches)
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            run_step()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        gemm_ms, n_timed = ctx.timing_end()
+        ms_per_step, gemm_ms, n_timed = run_timed(ctx, layer, args.steps, args.warmup, run_step)
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = layer.ring_ops_per_step / (ms_per_step * 1e-3) / 1e9
-    macs_per_launch = sum(b["macs_per_launch"] for b in layer.mm) / len(layer.mm)
-    gemm_ms_avg = gemm_ms / max(n_timed, 1)
-    achieved = INT8_OPS_PER_RING_MAC * macs_per_launch / (gemm_ms_avg * 1e-3) / 1e12
+    kernels = None
+    if not args.no_micro:
+        kernels = micro(ctx, layer)
+        for k, v in kernels.items():
+            log("%s = %.4g" % (k, v))
     result = {
         "metric": METRIC, "value": value, "unit": "Gop/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -518,51 +632,43 @@ def main():
                                 "+".join(m.name for m in cfg.matmuls)),
                    "ring_ops_per_step": layer.ring_ops_per_step,
                    "launches_per_step": 2 * len(layer.mm),
+                   "weight_operands": "digit planes (F opened in that format, B_i packed offline)"
+                                      if layer.planes else "words",
+                   "inputs": "seeded streams of workloads/ (seed %d), drawn on the device" % rng.BASE_SEED,
                    "submission": "hip graph replay" if args.graph else
                                  ("eager, two streams" if args.overlap else "eager")},
-        "roofline": {"bound": "mfma", "kernel": "ring_gemm_kernel",
-                     "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                     "frac": achieved / PEAK_INT8_TOPS,
-                     "traffic": GEMM_TRAFFIC_BYTES.get(wname),
-                     "avg_launch_ms": gemm_ms_avg, "launches_timed": n_timed,
-                     "ring_macs_per_launch": macs_per_launch,
-                     "gemm_share_of_step": gemm_ms / max(n_timed, 1) * launches / ((t1 - t0) * 1e3),
-                     "note": "algorithmic int8 ops: 36 digit products x 2 ops per ring MAC, two "
-                             "products per party (2*m*k*n_act ring MACs per launch)"},
+        "roofline": roofline_of(layer, wname, ms_per_step, gemm_ms, n_timed, args.steps, bool(args.skinny), kernels),
     }
-    if cfg.tokens <= 8 and not args.skinny:
-        # a few activation rows: the share calls take the vector-ALU kernel, bound by reading the
-        # two weight-side operands (B_i and F, kc x n words each) once per launch
-        wbytes = sum(b["macs_per_launch"] for b in layer.mm) / len(layer.mm) / cfg.tokens * 8.0
-        ach = wbytes / (gemm_ms_avg * 1e-3) / 1e9
-        result["roofline"] = {"bound": "hbm", "kernel": "ring_skinny_kernel", "achieved": ach,
-                              "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-                              "traffic": GEMM_TRAFFIC_BYTES.get(wname),
-                              "avg_launch_ms": gemm_ms_avg, "launches_timed": n_timed,
-                              "ring_macs_per_launch": macs_per_launch,
-                              "gemm_share_of_step": gemm_ms / max(n_timed, 1) * launches / ((t1 - t0) * 1e3),
-                              "note": "algorithmic bytes: the weight-side operands B_i and F of "
-                                      "one launch, 8 bytes per word, read once"}
-    if not args.no_micro:
-        result["kernels"] = micro(ctx, layer)
-        for k, v in result["kernels"].items():
-            log("%s = %.4g" % (k, v))
-        if result["roofline"]["bound"] == "mfma":
-            result["roofline"]["frac_of_measured_mfma_issue"] = achieved / result["kernels"]["mfma_i8_issue_TOPs"]
-            result["roofline"]["frac_of_measured_mfma_issue_random_operands"] = \
-                achieved / result["kernels"]["mfma_i8_issue_random_operands_TOPs"]
-        else:
-            result["roofline"]["frac_of_measured_copy"] = result["roofline"]["achieved"] / result["kernels"]["copy_GBs"]
+    if kernels is not None:
+        result["kernels"] = kernels
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(layer)
         log("cpu oracle: %.2f Gop/s on %d threads; rows match GPU: %s" %
             (result["cpu_baseline"]["value"], result["cpu_baseline"]["cores"],
              result["cpu_baseline"]["matches_gpu"]))
-        if not result["cpu_baseline"]["matches_gpu"]:
-            log("ERROR: GPU result differs from the oracle on the sampled rows")
-            print(json.dumps(result))
-            sys.exit(3)
+    names = [] if args.configs == "none" else (ALL_CONFIGS if args.configs == "all" else args.configs.split(","))
+    if names and not args.overlap and not args.graph:
+        result["configs"] = {}
+        for name in names:
+            _, canon = parse_workload(name)
+            if canon == wname:
+                entry = config_entry(ctx, name, kernels, planes, bool(args.skinny), layer=layer,
+                                     timing=(ms_per_step, gemm_ms, n_timed), check=result.get("cpu_baseline"))
+                entry["steps"] = args.steps
+            else:
+                entry = config_entry(ctx, name, kernels, planes, bool(args.skinny))
+            result["configs"][canon] = entry
+            log("%s: %.3f ms/step, %.0f Gop/s per party, share kernel %.1f us, %s frac %s, oracle rows match: %s" %
+                (canon, entry["ms_per_step"], entry["gops_per_party"], entry["share_kernel_us"],
+                 entry["roofline"]["bound"],
+                 "%.3f" % entry["roofline"]["frac"] if entry["roofline"]["frac"] is not None else "n/a",
+                 entry["matches_gpu"]))
+    bad = (not args.no_cpu_baseline and not result["cpu_baseline"]["matches_gpu"]) or \
+        any(not e["matches_gpu"] for e in result.get("configs", {}).values())
     print(json.dumps(result))
+    if bad:
+        log("ERROR: GPU result differs from the oracle on the sampled rows")
+        sys.exit(3)
 
 
 if __name__ == "__main__":
