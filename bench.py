@@ -401,6 +401,13 @@ def general_forms(ctx, timed):
     t_plain = timed(lambda: ctx.simm_share(1, bs, idx, n_dev, n_blk, e2, f2, a2, b2, c2, out=z2), reps=10)
     out["simm_row_sets_us"] = t_rows * 1e6
     out["simm_union_of_masks_us"] = t_plain * 1e6
+    # component search on an element-granular mask at FFN width (bs = 1): 512 tokens of six
+    # unrelated requests by 13824 neurons, beyond the one-workgroup limits
+    em = torch.from_numpy(masks.grouped_token_masks(rng.BASE_SEED, 9050, 512, 13824, 6, 0.02)).to(dev)
+    out["components_512x13824_us"] = timed(lambda: ctx.components(em), reps=20) * 1e6
+    ctx.set_tuning(5, 1)          # the same multi-workgroup search on the small block-granular mask
+    out["components_multi_workgroup_us"] = timed(lambda: ctx.components(tm), reps=20) * 1e6
+    ctx.set_tuning(5, 0)
     return out
 
 

@@ -225,10 +225,12 @@ int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64
  *   blk_idx / blk_comp [nb]: the blocks at least one token uses, ordered by
  *       (component, block), and their component numbers;
  *   *n_row_dev, *n_blk_dev, *n_comp_dev: the three counts (device).
- * Entries beyond the counts are left untouched.  One workgroup does the whole
- * search in LDS (label propagation, then a sort): n_tok <= 1024, nb <= 4096 and
- * n_tok * ceil(nb / 32) <= 16384, else COMET_ECAP.  All outputs int32, 4-byte
- * aligned.  No workspace. */
+ * Entries beyond the counts hold unspecified values afterwards (the arrays
+ * double as scratch).  Small graphs (n_tok <= 1024, nb <= 4096, n_tok *
+ * ceil(nb / 32) <= 16384) are searched by one workgroup in LDS; larger ones, up
+ * to n_tok <= 4096 and nb <= 16384 (element-granular masks, bs = 1, at FFN
+ * width), by a lock-free union-find over all workgroups; COMET_ECAP beyond.
+ * All outputs int32, 4-byte aligned.  No workspace. */
 int comet_components(comet_ctx* ctx, const uint8_t* mask, int64_t n_tok, int64_t nb,
                      int32_t* row_idx, int32_t* row_comp, int32_t* n_row_dev,
                      int32_t* blk_idx, int32_t* blk_comp, int32_t* n_blk_dev,
@@ -320,9 +322,12 @@ int comet_truncate_share(comet_ctx* ctx, int party, const uint64_t* z, uint64_t*
  *                         matrix-core kernel like any other call
  *   COMET_TUNE_SKINNY_SLICES: pieces the stacked contraction is cut into by
  *                         the vector-ALU kernel (default: about eight
- *                         workgroups per compute unit) */
+ *                         workgroups per compute unit)
+ *   COMET_TUNE_COMPONENTS: 1 sends every comet_components call to the
+ *                         multi-workgroup search (small graphs normally take a
+ *                         one-workgroup kernel) */
 enum { COMET_TUNE_GEMM_GRID = 0, COMET_TUNE_GEMM_CHUNK = 1, COMET_TUNE_GEMM_TILE = 2,
-       COMET_TUNE_SKINNY = 3, COMET_TUNE_SKINNY_SLICES = 4 };
+       COMET_TUNE_SKINNY = 3, COMET_TUNE_SKINNY_SLICES = 4, COMET_TUNE_COMPONENTS = 5 };
 int comet_set_tuning(comet_ctx* ctx, int key, int value);
 
 /* Device-side timing of the ring-GEMM kernel alone (the share calls also run a

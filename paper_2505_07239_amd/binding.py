@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libcomet_ring.so")
 AXIS_COLS, AXIS_ROWS = 0, 1
 OP_COMPACT, OP_SOMM, OP_SIMM = 0, 1, 2
 FULL_A, FULL_B, WEIGHTS_NEURON_MAJOR, WEIGHT_PLANES = 1, 2, 4, 8
-TUNE_GEMM_GRID, TUNE_GEMM_CHUNK, TUNE_GEMM_TILE, TUNE_SKINNY, TUNE_SKINNY_SLICES = 0, 1, 2, 3, 4
+TUNE_GEMM_GRID, TUNE_GEMM_CHUNK, TUNE_GEMM_TILE, TUNE_SKINNY, TUNE_SKINNY_SLICES, TUNE_COMPONENTS = 0, 1, 2, 3, 4, 5
 
 EXPORTS = [
     "comet_create", "comet_destroy", "comet_set_stream", "comet_last_error", "comet_version",

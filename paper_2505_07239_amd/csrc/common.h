@@ -23,6 +23,7 @@ struct comet_ctx {
     int gemm_tile;   // 0 = automatic
     int skinny_mode;   // 0 = automatic, 1 = never take the vector-ALU path
     int skinny_slices; // 0 = automatic
+    int components_mode; // 0 = automatic, 1 = always the multi-workgroup component search
     hipEvent_t* ev;  // timing event pairs, or null
     int ev_cap, ev_used;
     void* static_ws; // this device's copy of the library's static scratch array (device address)

@@ -41,6 +41,7 @@ int comet_create(comet_ctx** out, int device_id) {
     ctx->gemm_tile = 0;
     ctx->skinny_mode = 0;
     ctx->skinny_slices = 0;
+    ctx->components_mode = 0;
     ctx->ev = nullptr;
     ctx->ev_cap = ctx->ev_used = 0;
     ctx->err[0] = '\0';
@@ -74,13 +75,14 @@ int comet_set_stream(comet_ctx* ctx, void* hip_stream) {
 
 int comet_set_tuning(comet_ctx* ctx, int key, int value) {
     COMET_CHECK_CTX(ctx);
-    if (key < COMET_TUNE_GEMM_GRID || key > COMET_TUNE_SKINNY_SLICES || value < 0 || value > (1 << 16))
+    if (key < COMET_TUNE_GEMM_GRID || key > COMET_TUNE_COMPONENTS || value < 0 || value > (1 << 16))
         return comet_fail(ctx, COMET_EINVAL, "comet_set_tuning: unknown key or bad value");
     if (key == COMET_TUNE_GEMM_GRID) ctx->gemm_grid = value;
     else if (key == COMET_TUNE_GEMM_CHUNK) ctx->gemm_chunk = value;
     else if (key == COMET_TUNE_GEMM_TILE) ctx->gemm_tile = value;
     else if (key == COMET_TUNE_SKINNY) ctx->skinny_mode = value;
-    else ctx->skinny_slices = value;
+    else if (key == COMET_TUNE_SKINNY_SLICES) ctx->skinny_slices = value;
+    else ctx->components_mode = value;
     return COMET_OK;
 }
 

@@ -58,8 +58,9 @@ def grouped_mask(seed, n_tok, nb, groups, per_tok):
     return m
 
 
-def flat_components(mask_blk):
-    comps = protocols.components(mask_blk)
+def flat_components(mask_blk, comps=None):
+    if comps is None:
+        comps = protocols.components(mask_blk)
     row_idx = np.concatenate([r for r, _ in comps]) if comps else np.zeros(0, np.int32)
     blk_idx = np.concatenate([c for _, c in comps]) if comps else np.zeros(0, np.int32)
     row_comp = np.concatenate([np.full(len(r), t, np.int32) for t, (r, _) in enumerate(comps)]) \
@@ -69,10 +70,46 @@ def flat_components(mask_blk):
     return comps, row_idx.astype(np.int32), row_comp, blk_idx.astype(np.int32), blk_comp
 
 
-def check_components(ctx, mask_blk):
+def fast_components(mask):
+    """Connected components by union-find on the host (test-side, for masks too large for the
+    oracle's depth-first search in pure Python); same listing convention as the oracle: ordered
+    by smallest row, rows and columns ascending inside a component.  Checked against the oracle's
+    search on small masks in test_fast_components_agree_with_the_oracle."""
+    m, n = mask.shape
+    parent = list(range(m + n))
+
+    def find(v):
+        while parent[v] != v:
+            parent[v] = parent[parent[v]]
+            v = parent[v]
+        return v
+
+    rs, cs = np.nonzero(mask)
+    for r, c in zip(rs.tolist(), cs.tolist()):
+        a, b = find(r), find(m + c)
+        if a != b:
+            parent[max(a, b)] = min(a, b)
+    groups = {}
+    for r in sorted(set(rs.tolist())):
+        groups.setdefault(find(r), ([], []))[0].append(r)
+    for c in sorted(set(cs.tolist())):
+        groups[find(m + c)][1].append(c)
+    return [(np.array(g[0], np.int32), np.array(g[1], np.int32)) for _, g in sorted(groups.items())]
+
+
+def test_fast_components_agree_with_the_oracle():
+    for seed, (m, nb, groups, per_tok) in enumerate([(8, 216, 3, 5), (40, 96, 4, 2), (200, 344, 6, 3)]):
+        mk = grouped_mask(900 + seed, m, nb, groups, per_tok)
+        a, b = fast_components(mk), protocols.components(mk)
+        assert len(a) == len(b)
+        for (r1, c1), (r2, c2) in zip(a, b):
+            assert np.array_equal(r1, r2) and np.array_equal(c1, c2)
+
+
+def check_components(ctx, mask_blk, comps=None):
     out = ctx.components(torch.from_numpy(mask_blk).cuda())
     torch.cuda.synchronize()
-    comps, row_idx, row_comp, blk_idx, blk_comp = flat_components(mask_blk)
+    comps, row_idx, row_comp, blk_idx, blk_comp = flat_components(mask_blk, comps)
     assert int(out["n_comp"].item()) == len(comps)
     assert int(out["n_row"].item()) == len(row_idx) and int(out["n_blk"].item()) == len(blk_idx)
     assert np.array_equal(out["row_idx"][:len(row_idx)].cpu().numpy(), row_idx)
@@ -119,9 +156,59 @@ def test_components_degenerate_and_config_masks(ctx):
 
 def test_components_rejects_oversize(ctx):
     import paper_2505_07239_amd as comet
-    with pytest.raises(comet.CometError) as ei:
-        ctx.components(torch.zeros((1025, 8), dtype=torch.uint8, device="cuda"))
-    assert ei.value.code == -3      # COMET_ECAP
+    for shape in ((4097, 8), (2, 16385)):
+        with pytest.raises(comet.CometError) as ei:
+            ctx.components(torch.zeros(shape, dtype=torch.uint8, device="cuda"))
+        assert ei.value.code == -3      # COMET_ECAP
+
+
+@pytest.fixture
+def big_search(ctx):
+    """Every comet_components call of the test takes the multi-workgroup search."""
+    import paper_2505_07239_amd as comet
+    ctx.set_tuning(comet.TUNE_COMPONENTS, 1)
+    yield ctx
+    ctx.set_tuning(comet.TUNE_COMPONENTS, 0)
+
+
+@pytest.mark.parametrize("n_tok,nb,groups,per_tok", [(1, 1, 1, 1), (8, 216, 3, 5), (40, 96, 4, 2),
+                                                     (200, 344, 6, 3), (512, 344, 1, 8), (1024, 500, 9, 2),
+                                                     (33, 4096, 7, 4), (5, 37, 5, 1), (300, 1000, 300, 1)])
+def test_components_multi_workgroup_search_on_small_graphs(big_search, n_tok, nb, groups, per_tok):
+    say("components (multi-workgroup) n_tok=%d nb=%d groups=%d" % (n_tok, nb, groups))
+    check_components(big_search, grouped_mask(70 + n_tok, n_tok, nb, groups, per_tok))
+
+
+def test_components_multi_workgroup_search_degenerate(big_search):
+    say("components (multi-workgroup) degenerate")
+    check_components(big_search, np.zeros((7, 50), np.uint8))
+    check_components(big_search, np.ones((9, 70), np.uint8))
+    check_components(big_search, np.eye(64, dtype=np.uint8))
+    n = 300                                       # a path: the deepest trees for the union-find
+    m = np.zeros((n, n), np.uint8)
+    for t in range(n):
+        m[t, t] = 1
+        if t + 1 < n:
+            m[t + 1, t] = 1
+    out = check_components(big_search, m[::-1].copy())
+    assert int(out["n_comp"].item()) == 1
+
+
+def element_mask(seed, n_tok, n_neurons, groups, density, mean_run=4.0):
+    """Element-granular sparsity distribution (bs = 1) at FFN width: the tokens of ``groups``
+    unrelated requests draw clustered neuron masks from disjoint ranges of the neurons."""
+    return masks.grouped_token_masks(seed, 7000, n_tok, n_neurons, groups, density, mean_run)
+
+
+@pytest.mark.parametrize("n_tok,n_neurons,groups,density", [(512, 13824, 6, 0.02), (256, 11008, 1, 0.15),
+                                                            (2048, 4096, 16, 0.01), (4096, 16384, 40, 0.002),
+                                                            (700, 16000, 9, 0.05)])
+def test_components_element_granular_at_ffn_width(ctx, n_tok, n_neurons, groups, density):
+    """Beyond the one-workgroup limits: hundreds of tokens by more than ten thousand neurons."""
+    mk = element_mask(1234 + n_tok, n_tok, n_neurons, groups, density)
+    say("components element-granular %d x %d, %d edges" % (n_tok, n_neurons, int(mk.sum())))
+    out = check_components(ctx, mk, fast_components(mk))
+    assert int(out["n_comp"].item()) >= 1
 
 
 # ---------------------------------------------------------------------------
@@ -129,6 +216,9 @@ def test_components_rejects_oversize(ctx):
 # ---------------------------------------------------------------------------
 
 @pytest.mark.parametrize("m,nb,bs,n,groups,per_tok", [(3, 12, 8, 40, 2, 2), (8, 24, 16, 96, 3, 3),
+                                                      # element-granular masks (bs = 1)
+                                                      (6, 50, 1, 40, 2, 5), (45, 200, 1, 70, 4, 9),
+                                                      (150, 333, 1, 64, 3, 20),
                                                       (13, 10, 3, 33, 2, 2), (40, 20, 32, 70, 4, 2),
                                                       (130, 16, 16, 200, 3, 4), (70, 9, 5, 64, 1, 3),
                                                       # several row tiles with different step lists
@@ -218,6 +308,9 @@ def _somm_blocks_case(ctx, seed, m, k, nb, bs, groups, per_tok, spare_rows=0, sp
 
 
 @pytest.mark.parametrize("m,k,nb,bs,groups,per_tok", [(8, 64, 24, 16, 3, 3), (5, 40, 12, 8, 2, 2),
+                                                      # element-granular masks (bs = 1)
+                                                      (7, 40, 60, 1, 2, 6), (40, 64, 200, 1, 4, 9),
+                                                      (130, 96, 300, 1, 3, 20), (300, 33, 500, 1, 5, 12),
                                                       (16, 96, 10, 3, 2, 2), (40, 70, 20, 32, 4, 2),
                                                       (200, 130, 16, 16, 3, 3), (300, 64, 40, 32, 5, 2),
                                                       (70, 33, 9, 5, 1, 3)])
@@ -310,6 +403,49 @@ def test_mha_sparse_qkv_and_output_layers(ctx):
 
 
 # ---------------------------------------------------------------------------
+# element-granular sparsity distributions at FFN width (bs = 1)
+# ---------------------------------------------------------------------------
+
+def test_general_forms_element_granular_at_ffn_width(ctx):
+    """512 tokens x 13824 neurons (the LLaMA-2-13B FFN width), every neuron its own block: the
+    component search beyond the one-workgroup limits, Protocol 2 on the result blocks and
+    Protocol 3 with per-token row sets, each compared in full with the oracle's one-pass form.
+    The other dimension of each product is kept short so that the oracle stays in seconds."""
+    m, neurons, k, n_out, groups = 512, 13824, 96, 64, 6
+    mk = element_mask(4321, m, neurons, groups, 0.02)
+    comps = fast_components(mk)
+    comp = check_components(ctx, mk, comps)
+    _, row_idx, row_comp, blk_idx, blk_comp = flat_components(mk, comps)
+    n_row, n_blk = len(row_idx), len(blk_idx)
+    say("element-granular FFN width: %d edges, %d components, %d rows, %d neurons" %
+        (int(mk.sum()), len(comps), n_row, n_blk))
+    seed = 4400
+    # --- Protocol 2, result blocks, bs = 1 ---
+    e, a = u64(seed, 1, n_row, k), u64(seed, 2, n_row, k)
+    f, b = u64(seed, 3, k, n_blk), u64(seed, 4, k, neurons)
+    c = u64(seed, 5, n_row, n_blk)
+    z = ctx.somm_share_blocks(1, 1, comp["blk_idx"], comp["blk_comp"], comp["n_blk"], n_blk, comp["row_comp"],
+                              comp["n_row"], up(e), up(f), up(a), up(b), up(c))
+    torch.cuda.synchronize()
+    want = co.beaver_share_blocks(1, e, f, a, np.ascontiguousarray(b[:, blk_idx]), c, row_comp, blk_comp)
+    assert np.array_equal(down(z), want)
+    # --- Protocol 3, per-token row sets, bs = 1 ---
+    idx_np = co.compact_mask(mk)
+    t = len(idx_np)
+    idx, n_dev = ctx.compact_mask(torch.from_numpy(mk).cuda())
+    e2, a2 = u64(seed, 11, m, t), u64(seed, 12, m, neurons)
+    f2, b2 = u64(seed, 13, t, n_out), u64(seed, 14, neurons, n_out)
+    c2 = u64(seed, 15, m, n_out)
+    z2 = ctx.simm_share_masked(0, 1, idx, n_dev, t, torch.from_numpy(mk).cuda(), up(e2), up(f2), up(a2), up(b2),
+                               up(c2))
+    torch.cuda.synchronize()
+    assert int(n_dev.item()) == t and np.array_equal(idx[:t].cpu().numpy(), idx_np)
+    want2 = co.beaver_share_sparse_input(0, e2, f2, co.index_cols(a2, idx_np, 1), co.index_rows(b2, idx_np, 1), c2,
+                                         np.ascontiguousarray(mk[:, idx_np]))
+    assert np.array_equal(down(z2), want2)
+
+
+# ---------------------------------------------------------------------------
 # seeded sweep over both general forms
 # ---------------------------------------------------------------------------
 
@@ -317,8 +453,8 @@ def _draw_general(case):
     r = rng.uniform_u64(4343, case, 10)
     pick = lambda i, lo, hi: lo + int(r[i] % np.uint64(hi - lo + 1))
     m = [2, 9, 16, 17, 40, 64, 100, 129, 260][pick(0, 0, 8)]
-    bs = [2, 3, 8, 16, 32, 64][pick(1, 0, 5)]
-    nb = pick(2, 3, max(3, min(36, 576 // bs)))
+    bs = [1, 2, 3, 8, 16, 32, 64][pick(1, 0, 6)]
+    nb = pick(2, 3, max(3, min(36 if bs > 1 else 300, 576 // bs)))
     groups = pick(3, 1, min(5, nb))
     per_tok = pick(4, 1, 4)
     other = pick(5, 8, 200)
