@@ -122,7 +122,9 @@ def test_compact_mask_configs(ctx, cid):
 
 @pytest.mark.parametrize("n_tok,nb", [(1, 1), (1, 15), (1, 16), (1, 17), (3, 100), (8, 216), (5, 4096),
                                       (1, 4097), (1, 16384), (1, 16385), (3, 50_000), (4, 65536),
-                                      (1, 1_000_003), (2, 3_000_000)])
+                                      (1, 1_000_003), (2, 3_000_000),
+                                      # several super-chunks of the pipelined form, one token and two
+                                      (1, 20_000_003), (2, 34_000_000)])
 def test_compact_mask_shapes(ctx, n_tok, nb):
     say("compact n_tok=%d nb=%d" % (n_tok, nb))
     m = np.stack([masks.stress_mask(34, 10 * t + nb % 7, nb, 0.15) for t in range(n_tok)])
