@@ -28,13 +28,13 @@ constexpr int CHUNK = CT * FL * ITEMS;   // flags per workgroup in the large pat
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ u32 nz_bits4(u32 w, int shift) {
-    // one bit per non-zero byte of w, placed at bit positions shift .. shift+3
-    u32 r = 0;
-    r |= ((w & 0x000000ffu) ? 1u : 0u);
-    r |= ((w & 0x0000ff00u) ? 2u : 0u);
-    r |= ((w & 0x00ff0000u) ? 4u : 0u);
-    r |= ((w & 0xff000000u) ? 8u : 0u);
-    return r << shift;
+    // one bit per non-zero byte of w, placed at bit positions shift .. shift+3, without a compare
+    // per byte: the top bit of (byte & 0x7f) + 0x7f, or-ed with the byte itself, is set exactly for
+    // a non-zero byte (no carry leaves a byte), and one multiplication moves the four top bits,
+    // which sit at bits 0, 8, 16, 24 after the shift, next to each other at bits 21 .. 24
+    u32 t = (w & 0x7f7f7f7fu) + 0x7f7f7f7fu;
+    t = ((t | w) & 0x80808080u) >> 7;
+    return (((t * 0x00204081u) >> 21) & 0xfu) << shift;
 }
 
 // OR over tokens of flags [c0, c0+16) -> 16-bit word.  Flags at or beyond nb read as 0.
@@ -267,11 +267,11 @@ __global__ __launch_bounds__(CT) void compact_emit_kernel(const unsigned short* 
     int* out = blk_idx + off;
     if (total <= STAGE_CAP) {
         const int ph = (int)((reinterpret_cast<uintptr_t>(out) >> 2) & 3);   // position inside a 16-byte quad
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            emit_bits(bits[j], (int)((w0 + j) * FL), stage + ph + pos);
-            pos += __builtin_popcount(bits[j]);
-        }
+        // the lane's 64 consecutive flags as two 32-bit halves: fewer, longer loops diverge less
+        // between the lanes than one loop per 16-bit word
+        const u32 lo = bits[0] | (bits[1] << 16), hi = bits[2] | (bits[3] << 16);
+        emit_bits(lo, (int)(w0 * FL), stage + ph + pos);
+        emit_bits(hi, (int)(w0 * FL) + 32, stage + ph + pos + __builtin_popcount(lo));
         __syncthreads();
         // stage[ph .. ph + total) -> out[0 .. total); quads q cover stage[4q .. 4q + 4)
         const int end = ph + total;
