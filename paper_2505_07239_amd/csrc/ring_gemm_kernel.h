@@ -654,6 +654,141 @@ __device__ __forceinline__ void gemm_step(const GemmParams& p, L& ld,
                                  xs, ws, ws_next, xs_next2, a_off, b_off, ks_next2, ks_limit, KS, kc);
 }
 
+// ---------------------------------------------------------------------------
+// step with the barrier in its middle (weight planes)
+// ---------------------------------------------------------------------------
+// With both operands arriving by LDS-DMA a step has nothing left to hide in the shadow of its
+// matrix instructions, and what then costs time is the step boundary: a barrier, and behind it a
+// full LDS round trip before the first matrix instruction has its fragments.  So here
+//   * the digit pairs are walked with the activation digit DESCENDING (7, 6, .., 0; weight digit
+//     ascending inside), which makes every fragment that the first instructions of a step need
+//     dead in the last instructions of the step before;
+//   * fragment reads run READ_LEAD instructions ahead straight across the step boundary: the last
+//     instructions of step i already read, from the stage of step i + 1, what the first ones of
+//     step i + 1 consume;
+//   * the barrier sits in the MIDDLE of the step.  Barrier b_i publishes the stage of step i + 1
+//     (requested after b_(i-1), a whole step earlier), so reads of that stage may start right
+//     after it, and it retires the stage of step i - 1 (every wavefront's reads of it are older
+//     than its b_i), which the transfers for step i + 2, issued behind b_i, then overwrite.
+// No instruction after a barrier waits for a read that was issued after that barrier.
+template <int WM, int WN>
+struct SlotMapDesc {
+    static constexpr int per_group(int g) { return (g + 1) * WM * WN; }      // group g holds digit t = 7 - g
+    static constexpr int group_of(int m) {
+        int g = 0;
+        while (m >= per_group(g)) { m -= per_group(g); ++g; }
+        return g;
+    }
+    static constexpr int in_group(int m) {
+        int g = 0;
+        while (m >= per_group(g)) { m -= per_group(g); ++g; }
+        return m;
+    }
+    static constexpr int t_of(int m) { return 7 - group_of(m); }
+    static constexpr int u_of(int m) { return in_group(m) / (WM * WN); }
+    static constexpr int i_of(int m) { return (in_group(m) / WN) % WM; }
+    static constexpr int j_of(int m) { return in_group(m) % WN; }
+};
+
+template <int WM, int WN>
+struct ReadMapMid {
+    using SM = SlotMapDesc<WM, WN>;
+    static constexpr int NR = 8 * (WM + WN);
+    static constexpr int NM = 36 * WM * WN;
+    static constexpr int READ_LEAD = 8;
+    static constexpr int MID = NM / 2;
+    static_assert(READ_LEAD < NM - MID, "reads of the next stage start behind the barrier");
+    static constexpr bool is_a(int r) { return r < 8 * WM; }
+    static constexpr int need(int r) {
+        for (int m = 0; m < NM; ++m) {
+            if (is_a(r)) {
+                if (SM::t_of(m) == r / WM && SM::i_of(m) == r % WM) return m;
+            } else {
+                if (SM::u_of(m) == (r - 8 * WM) / WN && SM::j_of(m) == (r - 8 * WM) % WN) return m;
+            }
+        }
+        return NM;
+    }
+    // instruction of the SAME step after which read R is issued, or, when negative, NM + slot is
+    // the instruction of the step BEFORE after which it is issued
+    static constexpr int slot(int r) { return need(r) - READ_LEAD; }
+};
+
+template <class T, int WM, int WN, int R>
+__device__ __forceinline__ void read_frag_mid(v4i (&a)[8][WM], v4i (&bf)[WN][8], const unsigned char* xs,
+                                              const unsigned char* ws, int a_off, int b_off) {
+    using RM = ReadMapMid<WM, WN>;
+    if constexpr (RM::is_a(R)) {
+        constexpr int t = R / WM, ii = R % WM;
+        a[t][ii] = lds_frag(xs + a_off + (t * 2 * T::BM + ii * 32) * 16);
+    } else {
+        constexpr int uu = (R - 8 * WM) / WN, j = (R - 8 * WM) % WN;
+        bf[j][uu] = lds_frag(ws + b_off + (uu * 2 * T::BN + j * 32) * 16);
+    }
+}
+
+// the reads a step's first instructions need, issued before the first step of a segment
+template <class T, int WM, int WN>
+__device__ __forceinline__ void prefetch_first_frags(v4i (&a)[8][WM], v4i (&bf)[WN][8], const unsigned char* xs,
+                                                     const unsigned char* ws, int a_off, int b_off) {
+    using RM = ReadMapMid<WM, WN>;
+    [&]<int... Rs>(std::integer_sequence<int, Rs...>) {
+        ([&] { if constexpr (RM::slot(Rs) < 0) read_frag_mid<T, WM, WN, Rs>(a, bf, xs, ws, a_off, b_off); }(), ...);
+    }(std::make_integer_sequence<int, RM::NR>{});
+}
+
+template <class T, class L, int WM, int WN, int... Ms>
+__device__ __forceinline__ void gemm_step_mid_impl(std::integer_sequence<int, Ms...>, const GemmParams& p, L& ld,
+                                                   v16i (&acc)[WM][WN][8], v4i (&a)[8][WM], v4i (&bf)[WN][8],
+                                                   const unsigned char* xs, const unsigned char* ws,
+                                                   const unsigned char* xs_next, const unsigned char* ws_next,
+                                                   unsigned char* xs_fill, unsigned char* ws_fill, int a_off,
+                                                   int b_off, int q_fill, int q_limit, int KS, int kc) {
+    using SM = SlotMapDesc<WM, WN>;
+    using RM = ReadMapMid<WM, WN>;
+    constexpr int NM = RM::NM, MID = RM::MID;
+    (
+        [&] {
+            constexpr int M = Ms;
+            if constexpr (M == MID) {
+                // b_i: this wavefront's transfers for the next step have landed and its reads of the
+                // previous step's stage are done; behind the barrier that holds for all wavefronts
+                wait_and_barrier<0>();
+                ld.begin(p, q_fill, KS, kc, q_limit);
+            }
+            constexpr int t = SM::t_of(M), uu = SM::u_of(M), ii = SM::i_of(M), j = SM::j_of(M);
+            acc[ii][j][t + uu] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t][ii], bf[j][uu],
+                                                                        acc[ii][j][t + uu], 0, 0, 0);
+            // reads for this step (its own stage) and, near the end, for the first instructions of
+            // the next step (the next stage, published by this step's barrier)
+            [&]<int... Rs>(std::integer_sequence<int, Rs...>) {
+                ([&] {
+                    if constexpr (RM::slot(Rs) == M) read_frag_mid<T, WM, WN, Rs>(a, bf, xs, ws, a_off, b_off);
+                    if constexpr (RM::slot(Rs) + NM == M)
+                        read_frag_mid<T, WM, WN, Rs>(a, bf, xs_next, ws_next, a_off, b_off);
+                }(), ...);
+            }(std::make_integer_sequence<int, RM::NR>{});
+            if constexpr (M >= MID) {
+                constexpr int p0 = (int)((long)(M - MID) * L::P_END / (NM - MID)),
+                              p1 = (int)((long)(M - MID + 1) * L::P_END / (NM - MID));
+                ld.template pieces<p0, true>(std::make_integer_sequence<int, p1 - p0>{}, p, kc, xs_fill, ws_fill);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }(),
+        ...);
+}
+
+template <class T, class L, int WM, int WN>
+__device__ __forceinline__ void gemm_step_mid(const GemmParams& p, L& ld, v16i (&acc)[WM][WN][8],
+                                              v4i (&a)[8][WM], v4i (&bf)[WN][8], const unsigned char* xs,
+                                              const unsigned char* ws, const unsigned char* xs_next,
+                                              const unsigned char* ws_next, unsigned char* xs_fill,
+                                              unsigned char* ws_fill, int a_off, int b_off, int q_fill,
+                                              int q_limit, int KS, int kc) {
+    gemm_step_mid_impl<T, L, WM, WN>(std::make_integer_sequence<int, 36 * WM * WN>{}, p, ld, acc, a, bf, xs, ws,
+                                     xs_next, ws_next, xs_fill, ws_fill, a_off, b_off, q_fill, q_limit, KS, kc);
+}
+
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool LISTED>
 __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMODE))) void ring_gemm_kernel(GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
@@ -777,17 +912,24 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMOD
             ld.begin(p, 1 < L - 1 ? 1 : L - 1, KSt, kc, L - 1);
             ld.template pieces<0, true>(std::make_integer_sequence<int, LD::P_END>{}, p, kc, xs1, wsm + T::WBYTES);
             wait_and_barrier<0>();
-            // positions of the segment instead of contraction steps; stage i % 3 of both operands
+            // Positions of the segment instead of contraction steps; stage i % 3 of both operands.
+            // Step i reads stage i % 3, prefetches from stage (i + 1) % 3 and, behind its barrier,
+            // requests position i + 2 into stage (i + 2) % 3.
+            v4i fa[8][WM], fb[WN][8];
+            prefetch_first_frags<T, WM, WN>(fa, fb, xs0, wsm, a_off, b_off);
             for (int i = 0; i < L; i += 3) {
                 const int q2 = i + 2;
-                gemm_step<T, LD, WM, WN>(p, ld, acc, xs0, wsm, wsm + 2 * T::WBYTES, xs2, a_off, b_off,
-                                         q2 < L - 1 ? q2 : L - 1, L - 1, KSt, kc);
+                gemm_step_mid<T, LD, WM, WN>(p, ld, acc, fa, fb, xs0, wsm, xs1, wsm + T::WBYTES, xs2,
+                                             wsm + 2 * T::WBYTES, a_off, b_off, q2 < L - 1 ? q2 : L - 1, L - 1,
+                                             KSt, kc);
                 if (i + 1 < L)
-                    gemm_step<T, LD, WM, WN>(p, ld, acc, xs1, wsm + T::WBYTES, wsm, xs0, a_off, b_off,
-                                             q2 + 1 < L - 1 ? q2 + 1 : L - 1, L - 1, KSt, kc);
+                    gemm_step_mid<T, LD, WM, WN>(p, ld, acc, fa, fb, xs1, wsm + T::WBYTES, xs2,
+                                                 wsm + 2 * T::WBYTES, xs0, wsm, a_off, b_off,
+                                                 q2 + 1 < L - 1 ? q2 + 1 : L - 1, L - 1, KSt, kc);
                 if (i + 2 < L)
-                    gemm_step<T, LD, WM, WN>(p, ld, acc, xs2, wsm + 2 * T::WBYTES, wsm + T::WBYTES, xs1, a_off, b_off,
-                                             q2 + 2 < L - 1 ? q2 + 2 : L - 1, L - 1, KSt, kc);
+                    gemm_step_mid<T, LD, WM, WN>(p, ld, acc, fa, fb, xs2, wsm + 2 * T::WBYTES, xs0, wsm, xs1,
+                                                 wsm + T::WBYTES, a_off, b_off, q2 + 2 < L - 1 ? q2 + 2 : L - 1,
+                                                 L - 1, KSt, kc);
             }
         } else {
             ld.prime(p, ks0, KSt, kc);
