@@ -47,6 +47,10 @@ struct GemmParams {
     int* step_off;
     int* step_list;
     long tmask_nb;
+    // launch shape of the matrix-core kernel, fixed on the host before the packing kernel runs
+    int grid;                 // workgroups
+    int tile_bm, tile_bn;     // output tile
+    int own_try;              // plain product (no result blocks, no step lists, default slicing)
 };
 
 static __device__ __forceinline__ int n_blocks(const GemmParams& p) {
@@ -72,6 +76,16 @@ static __device__ __forceinline__ int n_rows(const GemmParams& p) {
 static __device__ __forceinline__ bool token_uses(const GemmParams& p, int row, int blk) {
     const long b = p.blk_idx[blk];
     return b >= 0 && b < p.tmask_nb && p.tmask[(long)row * p.tmask_nb + b] != 0;
+}
+
+// Does every workgroup of the matrix-core kernel get whole output tiles (all of their contraction)?
+// Then a tile has one writer: the kernel stores Z = C + sum directly and the packing kernel leaves Z
+// alone; otherwise Z starts out as C and the slices of a tile meet in it through atomic adds.
+// Both kernels evaluate this with the same device-resident counts.
+static __device__ __forceinline__ bool owns_tiles(const GemmParams& p, int m_eff, int n_eff, int kc) {
+    if (!p.own_try || kc <= 0 || m_eff <= 0 || n_eff <= 0) return false;
+    const long tiles = (long)((m_eff + p.tile_bm - 1) / p.tile_bm) * ((n_eff + p.tile_bn - 1) / p.tile_bn);
+    return tiles % p.grid == 0;
 }
 
 // Start of block `blk` on the indexed axis, or -1 when the id does not fit the

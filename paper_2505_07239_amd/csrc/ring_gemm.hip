@@ -87,6 +87,8 @@ __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
         // Z := C on the kept region (the GEMM adds its partial sums onto it); with result blocks
         // (Protocol 2 in general form) Z := C on the blocks and zero between them
         const int n_eff = p.kind == KIND_SOMM ? nblk * p.bs : p.n_cap;
+        // (the share kernel writes Z = C + sum itself when every workgroup owns whole tiles)
+        if (owns_tiles(p, m_eff, n_eff, p.kind == KIND_SOMM ? p.kc_cap : nblk * p.bs)) return;
         const long stride = (long)gridDim.x * gridDim.y * GT;
         const long t0 = ((long)blockIdx.y * gridDim.x + blockIdx.x) * GT + threadIdx.x;
         if (((n_eff | p.ldz | p.bs) & 1) == 0 || (!p.row_comp && ((n_eff | p.ldz) & 1) == 0)) {
@@ -377,6 +379,41 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     // (the few-row kernel reads the weights along the output columns: row-major words only)
     if (p.m <= COMET_SKINNY_MAX_ROWS && ctx->skinny_mode != 1 && !p.w_tr && !p.w_planes)
         return comet_launch_skinny(ctx, what, p);
+    // Tile shape and launch plan first: the packing kernel has to know whether the share kernel
+    // will own its tiles (and then initialise Z itself).
+    using T128 = Tile<2, 2, 2, 1>;
+    using T64 = Tile<2, 2, 1, 1>;
+    using T32W = Tile<1, 4, 1, 2>;
+    using T32P = Tile<1, 4, 1, 1>;
+    const int gm = p.w_planes ? W_PLANES : GATHER_NONE;     // what decides the LDS footprint
+    auto plan = [&](int bm) {
+        if (bm == 128) plan_gemm(ctx, p, T128::BM, T128::BN, T128::wg_per_cu(gm));
+        else if (bm == 64) plan_gemm(ctx, p, T64::BM, T64::BN, T64::wg_per_cu(gm));
+        else if (p.w_planes) plan_gemm(ctx, p, T32P::BM, T32P::BN, T32P::wg_per_cu(gm));
+        else plan_gemm(ctx, p, T32W::BM, T32W::BN, T32W::wg_per_cu(gm));
+    };
+    auto launch = [&](int bm) {
+        plan(bm);
+        if (bm == 128) return launch_gemm<2, 2, 2, 1>(ctx, what, p);
+        if (bm == 64) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+        return p.w_planes ? launch_gemm<1, 4, 1, 1>(ctx, what, p) : launch_gemm<1, 4, 1, 2>(ctx, what, p);
+    };
+    // rows per workgroup tile: 128, 64 or 32
+    int bm = 128;
+    const long big_tiles = (long)((p.m + 127) / 128) * ((p.n_cap + 63) / 64);
+    if (ctx->gemm_tile == 2) bm = 64;
+    else if (p.m <= 32) bm = 32;
+    else if (p.m <= 64) bm = 64;
+    // a small product (a handful of 128 x 64 tiles) is bound by the fixed cost per workgroup:
+    // the 64 x 64 tile doubles the number of independent tiles
+    else if (!p.row_comp && big_tiles * 8 <= ctx->num_cu) bm = 64;
+    // a ragged last row tile: 64-row tiles when they pad the rows by clearly less (the smaller
+    // tile is about 5 % slower per product)
+    else if (!p.row_comp && (long)round_up(p.m, 64) * 110 < (long)round_up(p.m, 128) * 100) bm = 64;
+    // per-token row sets: 64-row tiles follow the row sets more closely
+    else if (p.tmask) bm = 64;
+    plan(bm);
+
     // digit planes of [E | A'] and Z := C, one launch
     {
         unsigned gx = (unsigned)((p.ks_cap * 2 + 3) / 4);
@@ -395,18 +432,12 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         int* list_a = sel + 1;
         int* list_b = list_a + 1 + (size_t)((p.m + 63) / 64) * (size_t)((p.n_cap + 63) / 64);
         p.tile_list = list_a;
-        if (ctx->gemm_tile == 2 || (p.m > 32 && p.m <= 64)) {
-            hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, 64, 64, list_a,
-                               (const int*)nullptr, 0, (int*)nullptr);
+        if (bm != 128) {
+            hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, bm,
+                               bm == 64 ? 64 : (p.w_planes ? 128 : 256), list_a, (const int*)nullptr, 0,
+                               (int*)nullptr);
             COMET_LAUNCH_CHECK(ctx, what);
-            return launch_gemm<2, 2, 1, 1>(ctx, what, p);
-        }
-        if (p.m <= 32) {
-            hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, 32, p.w_planes ? 128 : 256,
-                               list_a, (const int*)nullptr, 0, (int*)nullptr);
-            COMET_LAUNCH_CHECK(ctx, what);
-            if (p.w_planes) return launch_gemm<1, 4, 1, 1>(ctx, what, p);
-            return launch_gemm<1, 4, 1, 2>(ctx, what, p);
+            return launch(bm);
         }
         hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, 128, 64, list_a,
                            (const int*)nullptr, 0, (int*)nullptr);
@@ -416,26 +447,12 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         COMET_LAUNCH_CHECK(ctx, what);
         p.tile_sel = sel;
         p.tile_sel_want = 0;
-        int rc = launch_gemm<2, 2, 2, 1>(ctx, what, p);
+        int rc = launch(128);
         if (rc) return rc;
         p.tile_list = list_b;
         p.tile_sel_want = 1;
-        return launch_gemm<2, 2, 1, 1>(ctx, what, p);
+        return launch(64);
     }
-    // tile shape: rows per workgroup tile 128, 64 or 32
-    int bm = 128;
-    const long big_tiles = (long)((p.m + 127) / 128) * ((p.n_cap + 63) / 64);
-    if (ctx->gemm_tile == 2) bm = 64;
-    else if (p.m <= 32) bm = 32;
-    else if (p.m <= 64) bm = 64;
-    // a small product (a handful of 128 x 64 tiles) is bound by the fixed cost per workgroup:
-    // the 64 x 64 tile doubles the number of independent tiles
-    else if (big_tiles * 8 <= ctx->num_cu) bm = 64;
-    // a ragged last row tile: 64-row tiles when they pad the rows by clearly less (the smaller
-    // tile is about 5 % slower per product)
-    else if ((long)round_up(p.m, 64) * 110 < (long)round_up(p.m, 128) * 100) bm = 64;
-    // per-token row sets: 64-row tiles follow the row sets more closely
-    else if (p.tmask) bm = 64;
     if (p.tmask) {
         // list, per row tile, the contraction steps some token of the tile takes part in
         const size_t tiles64 = (size_t)((p.m + 63) / 64) * (size_t)((p.n_cap + 63) / 64);
@@ -451,9 +468,7 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         hipLaunchKernelGGL(step_offsets_kernel, dim3(1), dim3(GT), 0, ctx->stream, p, bm);
         COMET_LAUNCH_CHECK(ctx, what);
     }
-    if (bm == 32) return p.w_planes ? launch_gemm<1, 4, 1, 1>(ctx, what, p) : launch_gemm<1, 4, 1, 2>(ctx, what, p);
-    if (bm == 64) return launch_gemm<2, 2, 1, 1>(ctx, what, p);
-    return launch_gemm<2, 2, 2, 1>(ctx, what, p);
+    return launch(bm);
 }
 
 int check_common(comet_ctx* ctx, const char* what, int party, int64_t m, int bs, int n_blk_cap,

@@ -789,7 +789,10 @@ __device__ __forceinline__ void gemm_step_mid(const GemmParams& p, L& ld, v16i (
                                      xs_next, ws_next, xs_fill, ws_fill, a_off, b_off, q_fill, q_limit, KS, kc);
 }
 
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool LISTED>
+// OWN: the variant for launches planned so that every workgroup gets whole output tiles (see
+// owns_tiles()); it still checks that on the device, where the counts are, and falls back to the
+// shared-tile path.  The other variant never owns: it carries none of that code.
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool LISTED, bool OWN = false>
 __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMODE))) void ring_gemm_kernel(GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     constexpr bool PLANES = is_planes(GMODE);
@@ -842,6 +845,10 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMOD
     // (the activation planes of that slice stay hot in L2) and each XCD ends up
     // with whole slices, so a weight word is fetched from HBM by one XCD only.
     int CH = p.chunk;
+    // every workgroup owns whole tiles: units tile by tile, all of a tile's contraction in a row
+    bool own = false;
+    if constexpr (OWN) own = owns_tiles(p, m_eff, n_eff, kc);
+    if (own) CH = KT;
     if (p.row_comp) {
         // the number of listed tiles is only known here: as many slices as workgroups per tile
         int slices = (int)((G + tiles / 2) / tiles);
@@ -881,6 +888,7 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMOD
             ks0 = c * CH + (int)(rem - (long)tile_pos * clen);
             const int tile = p.row_comp ? p.tile_list[1 + tile_pos] : tile_pos;
             len = c * CH + clen - ks0;
+            if (len > MAX_SEG) len = MAX_SEG;      // (an owned tile's contraction may be longer than a segment)
             tm = tile % tiles_m;
             tn = tile / tiles_m;
         }
@@ -959,27 +967,45 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMOD
         wait_and_barrier<0>();
 
         // recombine the eight planes and add the partial sum onto Z
+        auto recombine = [&](int i, int j, int e) -> u64 {
+            // sum_s sext64(S_s) << 8s: the four low planes as 32 x 32 -> 64 bit signed
+            // multiply-adds, the four high planes only reach the upper word
+            long long lo = (long long)acc[i][j][0][e];
+            lo += (long long)acc[i][j][1][e] * (1 << 8);
+            lo += (long long)acc[i][j][2][e] * (1 << 16);
+            lo += (long long)acc[i][j][3][e] * (1 << 24);
+            const u32 hi = (u32)acc[i][j][4][e] + ((u32)acc[i][j][5][e] << 8) +
+                           ((u32)acc[i][j][6][e] << 16) + ((u32)acc[i][j][7][e] << 24);
+            return (u64)lo + ((u64)hi << 32);
+        };
+        // The only writer of a tile (own) stores Z = C + sum (Z += sum for a later segment of a long
+        // contraction: this lane's own earlier store, complete since the barrier above); the loads of
+        // a sub-tile go out together, ahead of the arithmetic.  Slices of a shared tile meet in Z,
+        // which started out as C, through atomic adds.
+        const u64* src = ks0 == 0 ? p.C : p.Z;
 #pragma unroll
         for (int i = 0; i < WM; ++i)
 #pragma unroll
             for (int j = 0; j < WN; ++j) {
                 const int col = tn * T::BN + (wn * WN + j) * 32 + r;
                 const int ccomp = (p.row_comp && col < n_eff) ? p.blk_comp[col / p.bs] : 0;
+                u64 prev[16];
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int row = tm * T::BM + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                    // sum_s sext64(S_s) << 8s: the four low planes as 32 x 32 -> 64 bit signed
-                    // multiply-adds, the four high planes only reach the upper word
-                    long long lo = (long long)acc[i][j][0][e];
-                    lo += (long long)acc[i][j][1][e] * (1 << 8);
-                    lo += (long long)acc[i][j][2][e] * (1 << 16);
-                    lo += (long long)acc[i][j][3][e] * (1 << 24);
-                    const u32 hi = (u32)acc[i][j][4][e] + ((u32)acc[i][j][5][e] << 8) +
-                                   ((u32)acc[i][j][6][e] << 16) + ((u32)acc[i][j][7][e] << 24);
-                    const u64 z = (u64)lo + ((u64)hi << 32);
+                    prev[e] = 0;
+                    if (own && row < m_eff && col < n_eff) prev[e] = src[(size_t)row * p.ldz + col];
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = tm * T::BM + (wm * WM + i) * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+                    const u64 z = recombine(i, j, e);
                     bool live = row < m_eff && col < n_eff;
                     if (live && p.row_comp) live = p.row_comp[row] == ccomp;   // on a result block
-                    if (live) atomicAdd(p.Z + (size_t)row * p.ldz + col, z);
+                    if (live) {
+                        if (own) p.Z[(size_t)row * p.ldz + col] = prev[e] + z;
+                        else atomicAdd(p.Z + (size_t)row * p.ldz + col, z);
+                    }
                 }
             }
         u += len;
@@ -990,6 +1016,29 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMOD
 // (LISTED) whether a step list is walked.  Instantiated explicitly, one translation unit per
 // (tile shape, LISTED), so that the variants compile side by side.
 using GemmKernel = void (*)(GemmParams);
+
+// the OWN variants (128 x 64 tile, no step lists): translation units of their own
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+GemmKernel gemm_own_planes_kernel_for(const GemmParams& p) {
+    if (p.kind == KIND_SIMM) {
+        if (p.b_full) return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, W_PLANES_GATHER, false, true>;
+        return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, W_PLANES, false, true>;
+    }
+    return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, W_PLANES, false, true>;
+}
+extern template GemmKernel gemm_own_planes_kernel_for<2, 2, 2, 1>(const GemmParams&);
+
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+GemmKernel gemm_own_kernel_for(const GemmParams& p) {
+    if (p.kind == KIND_SIMM) {
+        if (!p.b_full) return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_NONE, false, true>;
+        if (p.bs_shift >= 3) return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_POW2, false, true>;
+        return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, GATHER_ANY, false, true>;
+    }
+    if (p.w_tr) return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, WEIGHTS_TR, false, true>;
+    return ring_gemm_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, GATHER_NONE, false, true>;
+}
+extern template GemmKernel gemm_own_kernel_for<2, 2, 2, 1>(const GemmParams&);
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, bool LISTED>
 GemmKernel gemm_kernel_for(const GemmParams& p) {
@@ -1032,13 +1081,51 @@ extern template GemmKernel gemm_kernel_for<2, 2, 1, 1, true>(const GemmParams&);
 extern template GemmKernel gemm_kernel_for<1, 4, 1, 2, false>(const GemmParams&);
 extern template GemmKernel gemm_kernel_for<1, 4, 1, 2, true>(const GemmParams&);
 
+// Launch plan of the matrix-core kernel for an output tile BM x BN: the grid, the slice length and
+// whether the launch may turn out to own its tiles.  Fixed before the packing kernel is launched,
+// which has to know whether the share kernel will initialise Z itself.
+inline void plan_gemm(const comet_ctx* ctx, GemmParams& p, int BM, int BN, int wg_per_cu) {
+    const long tiles = (long)((p.m + BM - 1) / BM) * ((p.n_cap + BN - 1) / BN);
+    const long kt = 2l * p.ks_cap;
+    const long units_cap = tiles * kt;
+    // a chip-sized grid, shrunk when there is too little work to share out
+    long grid = (ctx->num_cu / 8) * 8 * wg_per_cu;
+    if (grid < 8) grid = 8;
+    const long want = (units_cap + 1) / 2;      // at least two contraction steps per workgroup
+    if (want < grid) grid = want < 8 ? (want < 1 ? 1 : want) : (want / 8) * 8;
+    if (ctx->gemm_grid > 0) grid = ctx->gemm_grid;
+    // Slice length: as many slices as there are workgroups per tile, so that a workgroup's
+    // share of the units is one slice of one tile and all workgroups sweep their slice in
+    // lockstep (the activation planes of a slice are then shared through L2).
+    if (ctx->gemm_chunk > 0) {
+        p.chunk = ctx->gemm_chunk;
+    } else {
+        long slices = (grid + tiles / 2) / tiles;
+        if (slices < 1) slices = 1;
+        p.chunk = (int)((kt + slices - 1) / slices);
+    }
+    if (p.chunk > MAX_SEG) p.chunk = MAX_SEG;
+    if (p.chunk < 1) p.chunk = 1;
+    p.grid = (int)grid;
+    p.tile_bm = BM;
+    p.tile_bn = BN;
+    // Owned tiles: plain product, default slicing, the 128 x 64 tile, and a tile count (at full
+    // capacity; the kernel checks the device-resident counts) that the grid divides
+    p.own_try = (!p.row_comp && !p.tmask && ctx->gemm_chunk == 0 && BM == 128 && tiles % grid == 0) ? 1 : 0;
+}
+
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     GemmKernel kern = nullptr;
     constexpr bool PLANES_ONLY = WAVES_N == 4 && WN == 1;     // the 32 x 128 tile exists for weight planes only
     constexpr bool WORDS_ONLY = WAVES_N == 4 && WN == 2;      // the 32 x 256 tile needs two weight stages
-    if (p.w_planes) {
+    constexpr bool HAS_OWN = WM * WN == 2 && WAVES_N == 2;    // the 128 x 64 tile
+    if (p.own_try) {
+        if constexpr (HAS_OWN)
+            kern = p.w_planes ? gemm_own_planes_kernel_for<WAVES_M, WAVES_N, WM, WN>(p)
+                              : gemm_own_kernel_for<WAVES_M, WAVES_N, WM, WN>(p);
+    } else if (p.w_planes) {
         if constexpr (WORDS_ONLY) {
             kern = nullptr;
         } else if (p.step_list) {
@@ -1057,28 +1144,9 @@ int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
         kern = gemm_kernel_for<WAVES_M, WAVES_N, WM, WN, false>(p);
     }
     if (!kern) return comet_fail(ctx, COMET_EINVAL, "%s: no kernel variant for this call", what);
-    const long tiles = (long)((p.m + T::BM - 1) / T::BM) * ((p.n_cap + T::BN - 1) / T::BN);
-    const long kt = 2l * p.ks_cap;
-    const long units_cap = tiles * kt;
-    // a chip-sized grid, shrunk when there is too little work to share out
-    const int gmode_lds = p.w_planes ? W_PLANES : GATHER_NONE;    // what decides the LDS footprint
-    long grid = (ctx->num_cu / 8) * 8 * T::wg_per_cu(gmode_lds);
-    if (grid < 8) grid = 8;
-    const long want = (units_cap + 1) / 2;      // at least two contraction steps per workgroup
-    if (want < grid) grid = want < 8 ? (want < 1 ? 1 : want) : (want / 8) * 8;
-    if (ctx->gemm_grid > 0) grid = ctx->gemm_grid;
-    // Slice length: as many slices as there are workgroups per tile, so that a workgroup's
-    // share of the units is one slice of one tile and all workgroups sweep their slice in
-    // lockstep (the activation planes of a slice are then shared through L2).
-    if (ctx->gemm_chunk > 0) {
-        p.chunk = ctx->gemm_chunk;
-    } else {
-        long slices = (grid + tiles / 2) / tiles;
-        if (slices < 1) slices = 1;
-        p.chunk = (int)((kt + slices - 1) / slices);
-    }
-    if (p.chunk > MAX_SEG) p.chunk = MAX_SEG;
-    if (p.chunk < 1) p.chunk = 1;
+    if (p.tile_bm != T::BM || p.tile_bn != T::BN || p.grid < 1)
+        return comet_fail(ctx, COMET_EINVAL, "%s: launch plan does not match the kernel", what);
+    const long grid = p.grid;
     const bool timed = ctx->ev && ctx->ev_used + 2 <= ctx->ev_cap;
     if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], ctx->stream);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), 0, ctx->stream, p);

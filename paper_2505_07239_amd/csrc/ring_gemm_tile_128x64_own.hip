@@ -1,0 +1,5 @@
+// The 128 x 64 output tile of the int8 matrix-core kernel: the variants for launches in which every
+// workgroup owns whole output tiles (see owns_tiles() and ring_gemm_kernel.h).
+#include "ring_gemm_kernel.h"
+
+template comet_gemm::GemmKernel comet_gemm::gemm_own_kernel_for<2, 2, 2, 1>(const GemmParams&);
