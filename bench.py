@@ -4,7 +4,11 @@
 One *step* is one pass of the whole local path of a sparse FFN layer over one
 batch of synthetic input: compact the predicted block mask, then for every
 projection of the layer (gate / up: SOMM, down: SIMM) mask both parties'
-shares, open them, and compute both parties' output shares.  All inputs are
+shares, open them, and compute both parties' output shares.  The share products
+that are ready together go into one grouped call (gate and up of both parties,
+then down of both parties; the library runs them as one launch when the single
+launches would be short); ``--per-call`` makes one call per product and party,
+and the default line carries that run too (``per_call``).  All inputs are
 resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  ``value`` is ring-GEMM throughput of the headline
@@ -43,8 +47,8 @@ ALL_CONFIGS = ["c1", "c2", "c3", "c4", "c5_d100", "c5_d050", "c5_d025", "c5_d010
 # the copy probe of known size in the same run.  The summaries, with the commands, are the
 # files named here under profiles/.  None until measured for that workload and operand format.
 GEMM_TRAFFIC = {
-    ("c3", "words"): (199303800, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
-    ("c4", "words"): (987125342, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
+    ("c3", "words", "single"): (199303800, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
+    ("c4", "words", "single"): (987125342, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
 }
 
 
@@ -160,6 +164,23 @@ class Layer:
             self._mask_and_open(ctx, b, self.idx, self.n_dev)
             self._shares(ctx, b, self.idx, self.n_dev)
 
+    def step_grouped(self):
+        """The same step with the share products that are ready together in one call each
+        (``comet_share_group``): both parties' shares of the projections of the preceding layer
+        (gate and up wait for nothing but their own openings), then both parties' shares of the
+        subsequent layer."""
+        ctx, cfg = self.ctx, self.cfg
+        ctx.compact_mask(self.mask, self.idx, self.n_dev)
+        for kind in ("somm", "simm"):
+            group = [b for b in self.mm if b["mm"].kind == kind]
+            if not group:
+                continue
+            for b in group:
+                self._mask_and_open(ctx, b, self.idx, self.n_dev)
+            members = [(i, b["e"], b["f"], b["a"][i], b["bw"][i], b["c"][i]) for b in group for i in (0, 1)]
+            outs = [b["z"][i] for b in group for i in (0, 1)]
+            ctx.share_group(kind, cfg.bs, self.idx, self.n_dev, self.n_blk, members, out=outs)
+
     # ---- the same step with the bandwidth-bound kernels and the ring GEMMs on two streams ----
     def enable_overlap(self, ctx_stream_kernels):
         """Second set of the buffers a step writes (index list, masked and opened operands,
@@ -209,31 +230,58 @@ class Layer:
 
 def run_timed(ctx, layer, steps, warmup, run_step=None):
     """W untimed steps, then exactly K timed ones between two synchronisations; the share kernel
-    alone is timed with HIP events inside the library.  Returns (ms per step, share kernel us)."""
+    alone is timed with HIP events inside the library.  Returns a dict: ms per step, summed time
+    and number of the share launches that were timed, share launches per step."""
     import torch
-    run_step = run_step or layer.step
-    for _ in range(warmup):
+    import paper_2505_07239_amd as comet
+    run_step = run_step or layer.step_grouped
+    # share launches per step (the library decides which products of a grouped call share a
+    # launch): counted on the last warm-up step
+    per_step = 0
+    for w in range(max(warmup, 1)):
+        last = w == max(warmup, 1) - 1
+        if last:
+            ctx.set_tuning(comet.TUNE_TIMING_STRIDE, 1)
+            ctx.timing_begin(4 * len(layer.mm))
         run_step()
+        if last:
+            torch.cuda.synchronize()
+            _, per_step = ctx.timing_end()
     torch.cuda.synchronize()
-    ctx.timing_begin(2 * len(layer.mm) * steps)
+    # A timed launch idles the stream for about ten microseconds around the kernel, so only every
+    # n-th share launch of the timed region carries an event pair, n coprime to the launches per
+    # step: every projection and party is sampled equally often.
+    stride = 5 if per_step % 5 else 7
+    if per_step * steps < 4 * stride:
+        stride = 1
+    ctx.set_tuning(comet.TUNE_TIMING_STRIDE, stride)
+    ctx.timing_begin(per_step * steps)
     t0 = time.perf_counter()
     for _ in range(steps):
         run_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     gemm_ms, n_timed = ctx.timing_end()
-    return (t1 - t0) * 1e3 / steps, gemm_ms, n_timed
+    ctx.set_tuning(comet.TUNE_TIMING_STRIDE, 0)
+    return {"ms_per_step": (t1 - t0) * 1e3 / steps, "gemm_ms": gemm_ms, "n_timed": n_timed,
+            "launches_per_step": per_step, "timing_stride": stride}
 
 
-def roofline_of(layer, wname, ms_per_step, gemm_ms, n_timed, steps, skinny_forced, probes):
+def roofline_of(layer, wname, timing, skinny_forced, probes):
     """The roofline object of the dominant kernel of a workload."""
     cfg = layer.cfg
     fmt = "planes" if layer.planes else "words"
-    traffic, source = GEMM_TRAFFIC.get((wname, fmt), (None, None))
-    macs_per_launch = sum(b["macs_per_launch"] for b in layer.mm) / len(layer.mm)
+    ms_per_step, gemm_ms, n_timed = timing["ms_per_step"], timing["gemm_ms"], timing["n_timed"]
+    per_step = max(timing["launches_per_step"], 1)
+    grouped = per_step < 2 * len(layer.mm)
+    traffic, source = GEMM_TRAFFIC.get((wname, fmt, "grouped" if grouped else "single"), (None, None))
+    # both parties' shares of every projection, over the share launches of a step (a grouped
+    # launch computes several of them)
+    macs_per_launch = 2 * sum(b["macs_per_launch"] for b in layer.mm) / per_step
     avg_ms = gemm_ms / max(n_timed, 1)
-    share = avg_ms * 2 * len(layer.mm) / ms_per_step
+    share = avg_ms * per_step / ms_per_step
     common = {"traffic": traffic, "traffic_source": source, "avg_launch_ms": avg_ms, "launches_timed": n_timed,
+              "launches_per_step": per_step, "timing_stride": timing["timing_stride"],
               "ring_macs_per_launch": macs_per_launch, "gemm_share_of_step": share, "weight_operands": fmt}
     if cfg.tokens <= 8 and not skinny_forced:
         # a few activation rows: the share calls take the vector-ALU kernel, bound by reading the
@@ -251,7 +299,8 @@ def roofline_of(layer, wname, ms_per_step, gemm_ms, n_timed, steps, skinny_force
         r = {"bound": "mfma", "kernel": "ring_gemm_kernel", "achieved": ach, "peak": PEAK_INT8_TOPS,
              "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS,
              "note": "algorithmic int8 ops: 36 digit products x 2 ops per ring MAC, two products per "
-                     "party (2*m*k*n_act ring MACs per launch)"}
+                     "party (2*m*k*n_act ring MACs per share product; a grouped launch computes "
+                     "several products)"}
         if probes:
             r["frac_of_measured_mfma_issue"] = ach / probes["mfma_i8_issue_TOPs"]
             r["frac_of_measured_mfma_issue_random_operands"] = ach / probes["mfma_i8_issue_random_operands_TOPs"]
@@ -322,12 +371,13 @@ def config_entry(ctx, name, probes, planes, skinny_forced, steps=10, warmup=3, l
     if own:
         layer = Layer(ctx, cfg, rng.BASE_SEED, planes)
         timing = run_timed(ctx, layer, steps, warmup)
-    ms, gemm_ms, n_timed = timing
-    roof = roofline_of(layer, wname, ms, gemm_ms, n_timed, steps, skinny_forced, probes)
+    ms, gemm_ms, n_timed = timing["ms_per_step"], timing["gemm_ms"], timing["n_timed"]
+    roof = roofline_of(layer, wname, timing, skinny_forced, probes)
     if cfg.cid == 1:
         # a few microseconds of arithmetic per launch: launch latency decides, no roofline applies
         roof = {"bound": "latency", "kernel": roof["kernel"], "achieved": None, "peak": None, "unit": None,
-                "frac": None, "avg_launch_ms": roof["avg_launch_ms"], "weight_operands": roof["weight_operands"]}
+                "frac": None, "avg_launch_ms": roof["avg_launch_ms"], "weight_operands": roof["weight_operands"],
+                "ring_macs_per_launch": roof["ring_macs_per_launch"], "launches_per_step": roof["launches_per_step"]}
     if check is None:
         check = cpu_baseline(layer, budget_s=1.0)
     sent = sum(b["sent_elems"] for b in layer.mm)
@@ -339,7 +389,8 @@ def config_entry(ctx, name, probes, planes, skinny_forced, steps=10, warmup=3, l
         "ms_per_step": ms, "steps": steps if own else None,
         "gops_per_party": layer.ring_ops_per_step / (ms * 1e-3) / 1e9,
         "share_kernel_us": gemm_ms / max(n_timed, 1) * 1e3,
-        "ring_macs_per_launch": sum(b["macs_per_launch"] for b in layer.mm) / len(layer.mm),
+        "ring_macs_per_launch": roof["ring_macs_per_launch"],
+        "launches_per_step": roof["launches_per_step"],
         "roofline": {k: roof.get(k) for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "traffic")},
         "frac_of_measured_mfma_issue": roof.get("frac_of_measured_mfma_issue"),
         "frac_of_measured_copy": roof.get("frac_of_measured_copy"),
@@ -561,6 +612,8 @@ def main():
                     help="format of the weight-side operands of the share calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true")
+    ap.add_argument("--per-call", action="store_true",
+                    help="one share call per product and party instead of the grouped calls")
     ap.add_argument("--overlap", action="store_true",
                     help="run the bandwidth-bound kernels and the ring GEMMs on two streams")
     ap.add_argument("--graph", action="store_true",
@@ -599,7 +652,7 @@ def main():
         "operands as %s" % (wname, cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs, layer.n_blk, cfg.nb,
                             layer.n_act, layer.ring_ops_per_step / 1e9, "planes" if layer.planes else "words"))
 
-    run_step = layer.step
+    run_step = layer.step if args.per_call else layer.step_grouped
     if args.overlap:
         ctx_ew = comet.Context(0)
         layer.enable_overlap(ctx_ew)
@@ -608,7 +661,7 @@ def main():
         # One step captured in a HIP graph (every call only enqueues kernels) and replayed: the
         # launch gaps between the thirty-odd kernels of a step go away.  The share kernel is timed
         # with HIP events in an eager pass first, since events do not work inside a replay.
-        _, gemm_ms, n_timed = run_timed(ctx, layer, args.steps, args.warmup)
+        timing = run_timed(ctx, layer, args.steps, args.warmup, layer.step)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             layer.step()
@@ -618,9 +671,10 @@ def main():
         for _ in range(args.steps):
             graph.replay()
         torch.cuda.synchronize()
-        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+        timing["ms_per_step"] = (time.perf_counter() - t0) * 1e3 / args.steps
     else:
-        ms_per_step, gemm_ms, n_timed = run_timed(ctx, layer, args.steps, args.warmup, run_step)
+        timing = run_timed(ctx, layer, args.steps, args.warmup, run_step)
+    ms_per_step = timing["ms_per_step"]
 
     value = layer.ring_ops_per_step / (ms_per_step * 1e-3) / 1e9
     kernels = None
@@ -638,14 +692,26 @@ def main():
                                 layer.n_blk, cfg.nb, cfg.mask_kind,
                                 "+".join(m.name for m in cfg.matmuls)),
                    "ring_ops_per_step": layer.ring_ops_per_step,
-                   "launches_per_step": 2 * len(layer.mm),
+                   "share_products_per_step": 2 * len(layer.mm),
+                   "share_launches_per_step": timing["launches_per_step"],
+                   "share_calls": "one call per product and party" if (args.per_call or args.graph or args.overlap)
+                                  else "comet_share_group: gate+up of both parties, then down of both parties",
                    "weight_operands": "digit planes (F opened in that format, B_i packed offline)"
                                       if layer.planes else "words",
                    "inputs": "seeded streams of workloads/ (seed %d), drawn on the device" % rng.BASE_SEED,
                    "submission": "hip graph replay" if args.graph else
                                  ("eager, two streams" if args.overlap else "eager")},
-        "roofline": roofline_of(layer, wname, ms_per_step, gemm_ms, n_timed, args.steps, bool(args.skinny), kernels),
+        "roofline": roofline_of(layer, wname, timing, bool(args.skinny), kernels),
     }
+    if run_step == layer.step_grouped and not args.graph:
+        # the same K steps with one share call per product and party, for comparison
+        t2 = run_timed(ctx, layer, args.steps, 2, layer.step)
+        r2 = roofline_of(layer, wname, t2, bool(args.skinny), kernels)
+        result["per_call"] = {"ms_per_step": t2["ms_per_step"], "value": layer.ring_ops_per_step / (t2["ms_per_step"] * 1e-3) / 1e9,
+                              "share_launches_per_step": t2["launches_per_step"], "avg_launch_ms": r2["avg_launch_ms"],
+                              "frac": r2["frac"], "frac_of_measured_mfma_issue": r2.get("frac_of_measured_mfma_issue")}
+        run_step()                      # leave the grouped calls' outputs in place for the oracle check
+        torch.cuda.synchronize()
     if kernels is not None:
         result["kernels"] = kernels
     if not args.no_cpu_baseline:
@@ -660,7 +726,7 @@ def main():
             _, canon = parse_workload(name)
             if canon == wname:
                 entry = config_entry(ctx, name, kernels, planes, bool(args.skinny), layer=layer,
-                                     timing=(ms_per_step, gemm_ms, n_timed), check=result.get("cpu_baseline"))
+                                     timing=timing, check=result.get("cpu_baseline"))
                 entry["steps"] = args.steps
             else:
                 entry = config_entry(ctx, name, kernels, planes, bool(args.skinny))

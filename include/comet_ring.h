@@ -214,6 +214,37 @@ int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64
                      const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i,
                      void* ws, size_t ws_bytes);
 
+/* Several share products of one shape in one call: the gate and up projections
+ * of one layer (Protocol 2 twice, over the same index list), the share
+ * products of several requests, or -- where one process plays both parties --
+ * the two parties' shares of one product.  Member j of `members` (an array in
+ * HOST memory, read before the call returns) names its party and its own six
+ * operands; shape, block size, index list and flags are common to all and mean
+ * what they mean for comet_somm_share (op = COMET_OP_SOMM: m, k, n = n_full) or
+ * comet_simm_share (op = COMET_OP_SIMM: m, k = k_full, n).  The result is, bit
+ * for bit, that of the n_members single calls.  With COMET_WEIGHT_PLANES and
+ * m > 64, members that are short launches on their own (see COMET_TUNE_GROUP)
+ * run as one operand-packing launch and one matrix-core launch over the union
+ * of their work units: the fixed cost of a launch is paid once and the tail of
+ * one product is filled by the next.  Otherwise they run one after the other.  No Z_i may alias another member's Z_i or any
+ * input.  Workspace: n_members * comet_workspace_bytes(op, ...) bytes.
+ * 1 <= n_members <= COMET_SHARE_GROUP_MAX; other limits as for the single
+ * calls. */
+enum { COMET_SHARE_GROUP_MAX = 8 };
+typedef struct comet_share_operands {
+    int32_t party;          /* 0 or 1 */
+    int32_t reserved;       /* 0 */
+    const uint64_t* E;
+    const uint64_t* F;
+    const uint64_t* A_i;
+    const uint64_t* B_i;
+    const uint64_t* C_i;
+    uint64_t* Z_i;
+} comet_share_operands;
+int comet_share_group(comet_ctx* ctx, int op, int n_members, const comet_share_operands* members,
+                      int64_t m, int64_t k, int64_t n, int bs, const int32_t* blk_idx,
+                      const int32_t* n_blk_dev, int n_blk_cap, int flags, void* ws, size_t ws_bytes);
+
 /* ---- (4) Protocols 2 and 3 in general form: per-token sparsity ---------- */
 
 /* Protocol 2 step 1 at (token, neuron block) granularity: connected components
@@ -325,16 +356,26 @@ int comet_truncate_share(comet_ctx* ctx, int party, const uint64_t* z, uint64_t*
  *                         workgroups per compute unit)
  *   COMET_TUNE_COMPONENTS: 1 sends every comet_components call to the
  *                         multi-workgroup search (small graphs normally take a
- *                         one-workgroup kernel) */
+ *                         one-workgroup kernel)
+ *   COMET_TUNE_TIMING_STRIDE: while timing is on (comet_timing_begin), time
+ *                         every value-th share call instead of every one; a
+ *                         timed launch costs the stream about ten microseconds
+ *                         of idle time around the kernel
+ *   COMET_TUNE_GROUP:     comet_share_group normally runs its members as one
+ *                         launch when a member alone is a short launch (8 to
+ *                         128 contraction steps of 32 words per workgroup);
+ *                         1 = whenever the operands allow it, 2 = never */
 enum { COMET_TUNE_GEMM_GRID = 0, COMET_TUNE_GEMM_CHUNK = 1, COMET_TUNE_GEMM_TILE = 2,
-       COMET_TUNE_SKINNY = 3, COMET_TUNE_SKINNY_SLICES = 4, COMET_TUNE_COMPONENTS = 5 };
+       COMET_TUNE_SKINNY = 3, COMET_TUNE_SKINNY_SLICES = 4, COMET_TUNE_COMPONENTS = 5,
+       COMET_TUNE_TIMING_STRIDE = 6, COMET_TUNE_GROUP = 7 };
 int comet_set_tuning(comet_ctx* ctx, int key, int value);
 
 /* Device-side timing of the ring-GEMM kernel alone (the share calls also run a
  * small operand-packing kernel, which this excludes).  comet_timing_begin
  * creates up to max_launches HIP event pairs; while timing is on, every share
- * call records one pair around its GEMM kernel on the context's stream.
- * comet_timing_end waits for the last recorded event, returns the summed
+ * call (every n-th with COMET_TUNE_TIMING_STRIDE = n) attaches one pair to the
+ * dispatch of its GEMM kernel on the context's stream: the pair reads the
+ * kernel's own start and end.  comet_timing_end waits for the last recorded event, returns the summed
  * kernel time and the number of launches timed, and destroys the events. */
 int comet_timing_begin(comet_ctx* ctx, int max_launches);
 int comet_timing_end(comet_ctx* ctx, double* total_ms, int* launches);

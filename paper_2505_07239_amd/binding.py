@@ -21,12 +21,13 @@ AXIS_COLS, AXIS_ROWS = 0, 1
 OP_COMPACT, OP_SOMM, OP_SIMM = 0, 1, 2
 FULL_A, FULL_B, WEIGHTS_NEURON_MAJOR, WEIGHT_PLANES = 1, 2, 4, 8
 TUNE_GEMM_GRID, TUNE_GEMM_CHUNK, TUNE_GEMM_TILE, TUNE_SKINNY, TUNE_SKINNY_SLICES, TUNE_COMPONENTS = 0, 1, 2, 3, 4, 5
+TUNE_TIMING_STRIDE, TUNE_GROUP = 6, 7
 
 EXPORTS = [
     "comet_create", "comet_destroy", "comet_set_stream", "comet_last_error", "comet_version",
     "comet_workspace_bytes", "comet_mask_share", "comet_mask_share_gather", "comet_open",
     "comet_weight_planes_bytes", "comet_open_weight_planes",
-    "comet_compact_mask", "comet_somm_share", "comet_somm_share_static", "comet_simm_share",
+    "comet_compact_mask", "comet_somm_share", "comet_somm_share_static", "comet_simm_share", "comet_share_group",
     "comet_components", "comet_somm_share_blocks", "comet_simm_share_masked",
     "comet_permute_mask", "comet_scatter_cols", "comet_truncate_share",
     "comet_set_tuning", "comet_timing_begin", "comet_timing_end", "comet_probe_mfma_i8", "comet_probe_valu_mac64", "comet_probe_copy",
@@ -70,6 +71,8 @@ def load_library() -> ctypes.CDLL:
     lib.comet_somm_share.argtypes = share
     lib.comet_simm_share.argtypes = share
     lib.comet_somm_share_static.argtypes = share[:-2]
+    lib.comet_share_group.argtypes = [vp, i32, i32, ctypes.POINTER(ShareOperands), i64, i64, i64, i32, vp, vp, i32,
+                                      i32, vp, sz]
     lib.comet_components.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.comet_somm_share_blocks.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, i32, vp, vp, i32,
                                             vp, vp, vp, vp, vp, vp, vp, sz]
@@ -100,6 +103,16 @@ def _words(t: torch.Tensor, what: str) -> torch.Tensor:
     if t.dtype != torch.int64 or not t.is_cuda or not t.is_contiguous():
         raise TypeError("%s must be a contiguous int64 tensor on the GPU" % what)
     return t
+
+
+SHARE_GROUP_MAX = 8
+
+
+class ShareOperands(ctypes.Structure):
+    """``comet_share_operands``: one member of a grouped share call."""
+    _fields_ = [("party", ctypes.c_int32), ("reserved", ctypes.c_int32), ("E", ctypes.c_void_p),
+                ("F", ctypes.c_void_p), ("A_i", ctypes.c_void_p), ("B_i", ctypes.c_void_p),
+                ("C_i", ctypes.c_void_p), ("Z_i", ctypes.c_void_p)]
 
 
 class WeightPlanes:
@@ -314,6 +327,50 @@ class Context:
                                               _ptr(a_i), _ptr(b_i), _ptr(c_i), _ptr(out), _ptr(ws),
                                               need))
         return out
+
+    def share_group(self, kind, bs, blk_idx, n_blk_dev, n_blk_cap, members, a_full=True, b_full=True, out=None):
+        """Several share products of one shape in one call (``comet_share_group``).  ``kind``:
+        "somm" or "simm"; ``members``: a list of ``(party, e, f, a_i, b_i, c_i)``; ``out``: a list
+        of output tensors, one per member, or None.  Returns the list of outputs."""
+        if kind not in ("somm", "simm"):
+            raise ValueError("kind must be 'somm' or 'simm'")
+        if not 1 <= len(members) <= SHARE_GROUP_MAX:
+            raise ValueError("1 to %d members" % SHARE_GROUP_MAX)
+        somm = kind == "somm"
+        ld = n_blk_cap * bs
+        outs, planes0, dims0 = [], None, None
+        arr = (ShareOperands * len(members))()
+        for j, (party, e, f, a_i, b_i, c_i) in enumerate(members):
+            planes = _operands(e, f, a_i, b_i, c_i)
+            if somm:
+                m, k = e.shape
+                n = b_i.shape[1] if b_full else 0
+                zshape = (m, ld)
+            else:
+                m, n = e.shape[0], f.shape[1]
+                k = a_i.shape[1] if a_full else (b_i.shape[0] if b_full else 0)
+                zshape = (m, n)
+            o = torch.empty(zshape, dtype=torch.int64, device=e.device) if out is None else _words(out[j], "out")
+            if somm:
+                self._somm_shapes(m, k, ld, n, f, a_i, b_i, c_i, o, b_full, False)
+            else:
+                self._simm_shapes(m, n, ld, k, e, f, a_i, b_i, c_i, o, a_full, b_full)
+            if j == 0:
+                planes0, dims0 = planes, (m, k, n)
+            elif planes != planes0 or (m, k, n) != dims0:
+                raise ValueError("the members of a group have one shape and one operand format")
+            arr[j] = ShareOperands(party, 0, *[t.data_ptr() for t in (e, f, a_i, b_i, c_i, o)])
+            outs.append(o)
+        m, k, n = dims0
+        _index_list(blk_idx, n_blk_dev, n_blk_cap, b_full or (a_full and not somm))
+        each = workspace_bytes(OP_SOMM, m, k, ld, bs) if somm else workspace_bytes(OP_SIMM, m, ld, n, bs)
+        need = each * len(members)
+        ws = self.workspace(need)
+        flags = planes0 | (FULL_B if b_full else 0) | (FULL_A if (a_full and not somm) else 0)
+        self._sync_stream()
+        self._check(self.lib.comet_share_group(self.h, OP_SOMM if somm else OP_SIMM, len(members), arr, m, k, n, bs,
+                                               _ptr(blk_idx), _ptr(n_blk_dev), n_blk_cap, flags, _ptr(ws), need))
+        return outs
 
     def somm_share_static(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, e, f, a_i, b_i, c_i,
                           b_full=True, neuron_major=False, out=None):

@@ -11,7 +11,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcomet_ring.so")
 # the variants of the matrix-core kernel come first: they take longest to compile
-SOURCES = ["ring_gemm_tile_128x64_own.hip", "ring_gemm_planes_128x64_own.hip", "ring_gemm_tile_32x256.hip", "ring_gemm_tile_32x256_listed.hip", "ring_gemm_tile_128x64.hip",
+SOURCES = ["ring_gemm_tile_128x64_own.hip", "ring_gemm_planes_128x64_own.hip",
+           "ring_gemm_group_128x64.hip", "ring_gemm_group_128x64_own.hip", "ring_gemm_tile_32x256.hip", "ring_gemm_tile_32x256_listed.hip", "ring_gemm_tile_128x64.hip",
            "ring_gemm_tile_64x64.hip", "ring_gemm_tile_64x64_listed.hip",
            "ring_gemm_planes_128x64.hip", "ring_gemm_planes_64x64.hip", "ring_gemm_planes_64x64_listed.hip",
            "ring_gemm_planes_32x128.hip", "ring_gemm_planes_32x128_listed.hip", "ring_gemm.hip", "wplanes.hip",

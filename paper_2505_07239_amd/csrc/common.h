@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdarg>
 #include <cstdint>
@@ -24,8 +25,11 @@ struct comet_ctx {
     int skinny_mode;   // 0 = automatic, 1 = never take the vector-ALU path
     int skinny_slices; // 0 = automatic
     int components_mode; // 0 = automatic, 1 = always the multi-workgroup component search
+    int group_mode;      // comet_share_group: 0 = automatic, 1 = one launch whenever possible, 2 = never
     hipEvent_t* ev;  // timing event pairs, or null
     int ev_cap, ev_used;
+    int ev_stride;   // time every ev_stride-th share call (0 or 1: every call)
+    long ev_seen;    // share calls since timing began
     void* static_ws; // this device's copy of the library's static scratch array (device address)
     char err[512];
 };
@@ -42,6 +46,14 @@ static inline int comet_fail(comet_ctx* ctx, int code, const char* fmt, ...) {
         va_end(ap);
     }
     return code;
+}
+
+// Is the share kernel about to be launched a timed one?  (counts the launch)
+static inline bool comet_time_this_launch(comet_ctx* ctx) {
+    if (!ctx->ev) return false;
+    const long seen = ctx->ev_seen++;
+    if (ctx->ev_stride > 1 && seen % ctx->ev_stride != 0) return false;
+    return ctx->ev_used + 2 <= ctx->ev_cap;
 }
 
 static inline bool comet_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -41,9 +41,12 @@ int comet_create(comet_ctx** out, int device_id) {
     ctx->gemm_tile = 0;
     ctx->skinny_mode = 0;
     ctx->skinny_slices = 0;
+    ctx->ev_stride = 0;
+    ctx->group_mode = 0;
     ctx->components_mode = 0;
     ctx->ev = nullptr;
     ctx->ev_cap = ctx->ev_used = 0;
+    ctx->ev_seen = 0;
     ctx->err[0] = '\0';
     *out = ctx;
     return COMET_OK;
@@ -55,6 +58,7 @@ static void drop_events(comet_ctx* ctx) {
     delete[] ctx->ev;
     ctx->ev = nullptr;
     ctx->ev_cap = ctx->ev_used = 0;
+    ctx->ev_seen = 0;
 }
 
 int comet_destroy(comet_ctx* ctx) {
@@ -75,13 +79,15 @@ int comet_set_stream(comet_ctx* ctx, void* hip_stream) {
 
 int comet_set_tuning(comet_ctx* ctx, int key, int value) {
     COMET_CHECK_CTX(ctx);
-    if (key < COMET_TUNE_GEMM_GRID || key > COMET_TUNE_COMPONENTS || value < 0 || value > (1 << 16))
+    if (key < COMET_TUNE_GEMM_GRID || key > COMET_TUNE_GROUP || value < 0 || value > (1 << 16))
         return comet_fail(ctx, COMET_EINVAL, "comet_set_tuning: unknown key or bad value");
     if (key == COMET_TUNE_GEMM_GRID) ctx->gemm_grid = value;
     else if (key == COMET_TUNE_GEMM_CHUNK) ctx->gemm_chunk = value;
     else if (key == COMET_TUNE_GEMM_TILE) ctx->gemm_tile = value;
     else if (key == COMET_TUNE_SKINNY) ctx->skinny_mode = value;
     else if (key == COMET_TUNE_SKINNY_SLICES) ctx->skinny_slices = value;
+    else if (key == COMET_TUNE_TIMING_STRIDE) ctx->ev_stride = value;
+    else if (key == COMET_TUNE_GROUP) ctx->group_mode = value;
     else ctx->components_mode = value;
     return COMET_OK;
 }
@@ -104,6 +110,7 @@ int comet_timing_begin(comet_ctx* ctx, int max_launches) {
     }
     ctx->ev_cap = 2 * max_launches;
     ctx->ev_used = 0;
+    ctx->ev_seen = 0;
     return COMET_OK;
 }
 

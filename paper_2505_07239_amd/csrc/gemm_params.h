@@ -51,6 +51,7 @@ struct GemmParams {
     int grid;                 // workgroups
     int tile_bm, tile_bn;     // output tile
     int own_try;              // plain product (no result blocks, no step lists, default slicing)
+    int group_n;              // members of the group launch this product is part of (0 or 1: on its own)
 };
 
 static __device__ __forceinline__ int n_blocks(const GemmParams& p) {
@@ -85,7 +86,8 @@ static __device__ __forceinline__ bool token_uses(const GemmParams& p, int row, 
 static __device__ __forceinline__ bool owns_tiles(const GemmParams& p, int m_eff, int n_eff, int kc) {
     if (!p.own_try || kc <= 0 || m_eff <= 0 || n_eff <= 0) return false;
     const long tiles = (long)((m_eff + p.tile_bm - 1) / p.tile_bm) * ((n_eff + p.tile_bn - 1) / p.tile_bn);
-    return tiles % p.grid == 0;
+    // (the members of a group have one shape and follow each other tile by tile)
+    return tiles * (p.group_n > 1 ? p.group_n : 1) % p.grid == 0;
 }
 
 // Start of block `blk` on the indexed axis, or -1 when the id does not fit the

@@ -80,10 +80,10 @@ using namespace comet_gemm;
 // grid: x = chunks of four 16-word groups, y = chunks of 64 rows, z = 0 (E), 1 (A'), 2 (Z := C).
 // A workgroup packs a 64-row x 64-word tile: four adjacent lanes read 512 contiguous bytes of
 // one row, and the sixteen lanes that share a group write sixteen adjacent 16-byte units.
-__global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
+__device__ __forceinline__ void xpack_body(const GemmParams& p, const int part) {
     const int nblk = n_blocks(p);
     const int m_eff = n_rows(p);
-    if (blockIdx.z == 2) {
+    if (part == 2) {
         // Z := C on the kept region (the GEMM adds its partial sums onto it); with result blocks
         // (Protocol 2 in general form) Z := C on the blocks and zero between them
         const int n_eff = p.kind == KIND_SOMM ? nblk * p.bs : p.n_cap;
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
     const int row = blockIdx.y * 64 + (threadIdx.x >> 2);      // < mpad by construction
     const int half16 = blockIdx.x * 4 + (threadIdx.x & 3);     // 16-word group over the half
     if (half16 >= p.ks_cap * 2) return;
-    const int h = blockIdx.z;                                  // 0: E, 1: A'
+    const int h = part;                                        // 0: E, 1: A'
     const int k0 = half16 * 16;
     typedef u64 u64x2 __attribute__((ext_vector_type(2)));
     u64 w[16];
@@ -191,6 +191,13 @@ __global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) {
         u64x2* dst = reinterpret_cast<u64x2*>(p.xp) + xp_group(h, s, t, g, p.ks_cap) * p.mpad + row;
         *dst = u64x2{plane[0][t], plane[1][t]};
     }
+}
+
+__global__ __launch_bounds__(GT) void xpack_kernel(GemmParams p) { xpack_body(p, blockIdx.z); }
+
+// the members of a group (one shape): grid.z = 3 * member + part
+__global__ __launch_bounds__(GT) void xpack_group_kernel(GemmGroup grp) {
+    xpack_body(grp.p[blockIdx.z / 3], blockIdx.z % 3);
 }
 
 // ---------------------------------------------------------------------------
@@ -358,6 +365,17 @@ size_t gemm_ws_bytes(int64_t m, int64_t kc_cap, int64_t n_cap) {
            step_ws_bytes(m, kc_cap);
 }
 
+// the parts of the workspace and the derived sizes
+void place_in_workspace(GemmParams& p, void* ws) {
+    p.xp = static_cast<unsigned char*>(ws);
+    p.tile_list = reinterpret_cast<int*>(p.xp + planes_bytes(p.m, p.kc_cap));
+    p.mpad = round_up(p.m, 128);
+    p.ks_cap = (p.kc_cap + KSTEP - 1) / KSTEP;
+    p.bs_shift = -1;
+    for (int sh = 0; sh < 30; ++sh)
+        if (p.bs == (1 << sh)) p.bs_shift = sh;
+}
+
 int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t ws_bytes) {
     const size_t need = gemm_ws_bytes(p.m, p.kc_cap, p.n_cap);
     if (!ws || ws_bytes < need)
@@ -367,13 +385,7 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     comet_device_guard guard(ctx);
     if (!guard.ok) return comet_fail(ctx, COMET_EDEVICE, "%s: cannot select device", what);
 
-    p.xp = static_cast<unsigned char*>(ws);
-    p.tile_list = reinterpret_cast<int*>(p.xp + planes_bytes(p.m, p.kc_cap));
-    p.mpad = round_up(p.m, 128);
-    p.ks_cap = (p.kc_cap + KSTEP - 1) / KSTEP;
-    p.bs_shift = -1;
-    for (int sh = 0; sh < 30; ++sh)
-        if (p.bs == (1 << sh)) p.bs_shift = sh;
+    place_in_workspace(p, ws);
 
     if (p.n_cap == 0) return COMET_OK;
     // (the few-row kernel reads the weights along the output columns: row-major words only)
@@ -469,6 +481,67 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         COMET_LAUNCH_CHECK(ctx, what);
     }
     return launch(bm);
+}
+
+// Several products of one shape, one index list and one operand format.  When they suit the
+// grouped matrix-core kernel (weight planes, more than 64 rows, no few-row path) they run as one
+// packing launch and one share launch over the union of their work units; otherwise one by one.
+int run_share_group(comet_ctx* ctx, const char* what, GemmParams* ps, int n, void* ws, size_t ws_bytes) {
+    const size_t each = gemm_ws_bytes(ps[0].m, ps[0].kc_cap, ps[0].n_cap);
+    if (!ws || each == 0 || ws_bytes / (size_t)n < each)
+        return comet_fail(ctx, COMET_EWORKSPACE, "%s: workspace of %zu bytes required", what, each * (size_t)n);
+    if (reinterpret_cast<uintptr_t>(ws) & 255u)
+        return comet_fail(ctx, COMET_EALIGN, "%s: workspace must be 256-byte aligned", what);
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    const GemmParams& p0 = ps[0];
+    // One launch for all members pays when a member alone is a short launch: between 8 and 128
+    // contraction steps per workgroup.  Below that the single calls shrink their grid instead;
+    // above it the fixed cost of a launch is amortised already and one long launch only runs
+    // at a lower sustained clock than the same work in pieces.
+    using T = Tile<2, 2, 2, 1>;
+    long grid = (ctx->num_cu / 8) * 8 * T::wg_per_cu(W_PLANES);
+    if (grid < 8) grid = 8;
+    if (ctx->gemm_grid > 0) grid = ctx->gemm_grid;
+    const long tiles = (long)((p0.m + T::BM - 1) / T::BM) * ((p0.n_cap + T::BN - 1) / T::BN);
+    const long steps_each = tiles * 2 * ((p0.kc_cap + KSTEP - 1) / KSTEP) / grid;
+    const bool grouped = n > 1 && p0.w_planes && p0.m > 64 && p0.n_cap > 0 && ctx->gemm_tile != 2 &&
+                         (ctx->group_mode == 1 || (ctx->group_mode == 0 && steps_each >= 8 && steps_each <= 128));
+    if (!grouped) {
+        for (int j = 0; j < n; ++j) {
+            const int rc = run_share(ctx, what, ps[j], base + (size_t)j * each, each);
+            if (rc) return rc;
+        }
+        return COMET_OK;
+    }
+    comet_device_guard guard(ctx);
+    if (!guard.ok) return comet_fail(ctx, COMET_EDEVICE, "%s: cannot select device", what);
+
+    GemmGroup grp = {};
+    grp.n = n;
+    for (int j = 0; j < n; ++j) {
+        GemmParams& p = grp.p[j];
+        p = ps[j];
+        place_in_workspace(p, base + (size_t)j * each);
+        // units tile by tile (all of a tile's contraction in a row): a workgroup's share of the
+        // whole sequence then covers few tiles, and whole ones when the grid divides their number
+        p.chunk = 2 * p.ks_cap > 0 ? 2 * p.ks_cap : 1;
+        p.grid = (int)grid;
+        p.tile_bm = T::BM;
+        p.tile_bn = T::BN;
+        p.group_n = n;
+        p.own_try = (tiles * n % grid == 0) ? 1 : 0;
+    }
+    {
+        const GemmParams& p = grp.p[0];
+        unsigned gx = (unsigned)((p.ks_cap * 2 + 3) / 4);
+        if (gx < 1) gx = 1;
+        const long zgx = ((long)p.m * p.n_cap / (2l * 4 * GT) + p.mpad / 64 - 1) / (p.mpad / 64);
+        if (zgx > gx) gx = (unsigned)(zgx > 4096 ? 4096 : zgx);
+        hipLaunchKernelGGL(xpack_group_kernel, dim3(gx, (unsigned)(p.mpad / 64), 3u * (unsigned)n), dim3(GT), 0,
+                           ctx->stream, grp);
+        COMET_LAUNCH_CHECK(ctx, what);
+    }
+    return launch_gemm_group<2, 2, 2, 1>(ctx, what, grp);
 }
 
 int check_common(comet_ctx* ctx, const char* what, int party, int64_t m, int bs, int n_blk_cap,
@@ -628,6 +701,28 @@ int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64
                                E, F, A_i, B_i, C_i, Z_i);
     if (rc) return rc;
     return run_share(ctx, what, p, ws, ws_bytes);
+}
+
+int comet_share_group(comet_ctx* ctx, int op, int n_members, const comet_share_operands* members,
+                      int64_t m, int64_t k, int64_t n, int bs, const int32_t* blk_idx,
+                      const int32_t* n_blk_dev, int n_blk_cap, int flags, void* ws, size_t ws_bytes) {
+    const char* what = "comet_share_group";
+    COMET_CHECK_CTX(ctx);
+    if (op != COMET_OP_SOMM && op != COMET_OP_SIMM)
+        return comet_fail(ctx, COMET_EINVAL, "%s: op must be COMET_OP_SOMM or COMET_OP_SIMM", what);
+    if (!members || n_members < 1 || n_members > COMET_SHARE_GROUP_MAX)
+        return comet_fail(ctx, COMET_EINVAL, "%s: 1 to %d members", what, (int)COMET_SHARE_GROUP_MAX);
+    GemmParams ps[COMET_SHARE_GROUP_MAX] = {};
+    for (int j = 0; j < n_members; ++j) {
+        const comet_share_operands& o = members[j];
+        const int rc = op == COMET_OP_SOMM
+            ? somm_params(ctx, what, ps[j], o.party, m, k, n, bs, blk_idx, n_blk_dev, n_blk_cap, flags, o.E, o.F,
+                          o.A_i, o.B_i, o.C_i, o.Z_i)
+            : simm_params(ctx, what, ps[j], o.party, m, k, n, bs, blk_idx, n_blk_dev, n_blk_cap, flags, o.E, o.F,
+                          o.A_i, o.B_i, o.C_i, o.Z_i);
+        if (rc) return rc;
+    }
+    return run_share_group(ctx, what, ps, n_members, ws, ws_bytes);
 }
 
 int comet_simm_share_masked(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64_t n,

@@ -1,0 +1,5 @@
+// The grouped matrix-core kernel (several products of one shape in one launch), 128 x 64 output
+// tile, weight planes: the variants in which every workgroup owns whole output tiles.
+#include "ring_gemm_kernel.h"
+
+template comet_gemm::GemmGroupKernel comet_gemm::gemm_group_kernel_for<2, 2, 2, 1, true>(const GemmParams&);

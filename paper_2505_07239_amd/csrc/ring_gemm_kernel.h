@@ -789,46 +789,42 @@ __device__ __forceinline__ void gemm_step_mid(const GemmParams& p, L& ld, v16i (
                                      xs_next, ws_next, xs_fill, ws_fill, a_off, b_off, q_fill, q_limit, KS, kc);
 }
 
-// OWN: the variant for launches planned so that every workgroup gets whole output tiles (see
-// owns_tiles()); it still checks that on the device, where the counts are, and falls back to the
-// shared-tile path.  The other variant never owns: it carries none of that code.
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool LISTED, bool OWN = false>
-__global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMODE))) void ring_gemm_kernel(GemmParams p) {
+// What a launch computes, from the device-resident counts.
+struct Geometry {
+    int n_eff, kc, KS, KT, m_eff, tiles_m, tiles_n, tiles;
+    long units;     // work units: (tile, contraction step) pairs
+};
+
+template <class T, int KIND, bool LISTED>
+__device__ __forceinline__ Geometry gemm_geometry(const GemmParams& p) {
+    Geometry q;
+    const int nblk = n_blocks(p);
+    q.n_eff = KIND == KIND_SOMM ? nblk * p.bs : p.n_cap;
+    q.kc = KIND == KIND_SOMM ? p.kc_cap : nblk * p.bs;
+    q.KS = (q.kc + KSTEP - 1) / KSTEP;
+    q.KT = 2 * q.KS;
+    q.m_eff = n_rows(p);
+    q.tiles_m = (q.m_eff + T::BM - 1) / T::BM;
+    q.tiles_n = (q.n_eff + T::BN - 1) / T::BN;
+    // with result blocks only the listed tiles are computed
+    q.tiles = p.row_comp ? p.tile_list[0] : q.tiles_m * q.tiles_n;
+    // with per-token row sets only the listed steps of each row tile are computed
+    q.units = LISTED ? (long)q.tiles_n * 2 * p.step_off[q.tiles_m] : (long)q.tiles * q.KT;
+    return q;
+}
+
+// The work units [u, u_end) of one product: segment by segment (a run of contraction steps of one
+// output tile), the main loop and the write-out of the partial sum.  G: workgroups of the launch.
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool LISTED>
+__device__ __forceinline__ void gemm_sweep(const GemmParams& p, const Geometry& q, long u, const long u_end,
+                                           const int G, const bool own, unsigned char* xs0, unsigned char* xs1,
+                                           unsigned char* xs2, unsigned char* wsm, int* steptab) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     constexpr bool PLANES = is_planes(GMODE);
     using LD = std::conditional_t<PLANES, PlaneLoader<T, KIND, GMODE, LISTED>, Loader<T, KIND, GMODE, LISTED>>;
-    // Three activation stages filled by LDS-DMA two steps ahead, as separate
-    // arrays so that the compiler can tell a stage being filled from the one
-    // being read; two weight stages written from registers one step ahead.
-    __shared__ __align__(16) unsigned char xs0[T::XBYTES];
-    __shared__ __align__(16) unsigned char xs1[T::XBYTES];
-    __shared__ __align__(16) unsigned char xs2[T::XBYTES];
-    __shared__ __align__(16) unsigned char wsm[T::wstages(GMODE) * T::WBYTES];
-    __shared__ __align__(16) int steptab[PLANES ? MAX_SEG * 4 : 4];
-
-    if (p.tile_sel && *p.tile_sel != p.tile_sel_want) return;   // the other tile shape was chosen
-    const int nblk = n_blocks(p);
-    const int n_eff = KIND == KIND_SOMM ? nblk * p.bs : p.n_cap;
-    const int kc = KIND == KIND_SOMM ? p.kc_cap : nblk * p.bs;
-    const int KS = (kc + KSTEP - 1) / KSTEP;
-    const int KT = 2 * KS;
-    const int m_eff = n_rows(p);
-    const int tiles_m = (m_eff + T::BM - 1) / T::BM;
-    const int tiles_n = (n_eff + T::BN - 1) / T::BN;
-    // with result blocks only the listed tiles are computed
-    const int tiles = p.row_comp ? p.tile_list[0] : tiles_m * tiles_n;
-    // with per-token row sets only the listed steps of each row tile are computed
     constexpr bool listed = LISTED;
-    const long units = listed ? (long)tiles_n * 2 * p.step_off[tiles_m] : (long)tiles * KT;
-    if (units == 0) return;
-
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one
-    // contiguous range of work units.
-    const int G = gridDim.x;
-    int b = blockIdx.x;
-    if ((G & 7) == 0) b = (b & 7) * (G >> 3) + (b >> 3);
-    long u = units * b / G;
-    const long u_end = units * (b + 1) / G;
+    const int n_eff = q.n_eff, kc = q.kc, KS = q.KS, KT = q.KT, m_eff = q.m_eff;
+    const int tiles_m = q.tiles_m, tiles_n = q.tiles_n, tiles = q.tiles;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
@@ -846,8 +842,6 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMOD
     // with whole slices, so a weight word is fetched from HBM by one XCD only.
     int CH = p.chunk;
     // every workgroup owns whole tiles: units tile by tile, all of a tile's contraction in a row
-    bool own = false;
-    if constexpr (OWN) own = owns_tiles(p, m_eff, n_eff, kc);
     if (own) CH = KT;
     if (p.row_comp) {
         // the number of listed tiles is only known here: as many slices as workgroups per tile
@@ -1012,6 +1006,72 @@ __global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMOD
     }
 }
 
+// LDS of the kernels: three activation stages filled by LDS-DMA two steps ahead, as separate
+// arrays so that the compiler can tell a stage being filled from the one
+// being read; two weight stages written from registers one step ahead (three, filled by
+// LDS-DMA, for weight planes, with the step table of a segment).
+#define COMET_GEMM_LDS(T, GMODE)                                                        \
+    __shared__ __align__(16) unsigned char xs0[T::XBYTES];                              \
+    __shared__ __align__(16) unsigned char xs1[T::XBYTES];                              \
+    __shared__ __align__(16) unsigned char xs2[T::XBYTES];                              \
+    __shared__ __align__(16) unsigned char wsm[T::wstages(GMODE) * T::WBYTES];          \
+    __shared__ __align__(16) int steptab[is_planes(GMODE) ? MAX_SEG * 4 : 4]
+
+// Workgroups are dealt round-robin to the 8 XCDs; give each XCD one contiguous range of work.
+__device__ __forceinline__ int xcd_contiguous(int b, int G) {
+    return (G & 7) == 0 ? (b & 7) * (G >> 3) + (b >> 3) : b;
+}
+
+// OWN: the variant for launches planned so that every workgroup gets whole output tiles (see
+// owns_tiles()); it still checks that on the device, where the counts are, and falls back to the
+// shared-tile path.  The other variant never owns: it carries none of that code.
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool LISTED, bool OWN = false>
+__global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMODE))) void ring_gemm_kernel(GemmParams p) {
+    using T = Tile<WAVES_M, WAVES_N, WM, WN>;
+    COMET_GEMM_LDS(T, GMODE);
+    if (p.tile_sel && *p.tile_sel != p.tile_sel_want) return;   // the other tile shape was chosen
+    const Geometry q = gemm_geometry<T, KIND, LISTED>(p);
+    if (q.units == 0) return;
+    const int G = gridDim.x;
+    const int b = xcd_contiguous(blockIdx.x, G);
+    bool own = false;
+    if constexpr (OWN) own = owns_tiles(p, q.m_eff, q.n_eff, q.kc);
+    gemm_sweep<WAVES_M, WAVES_N, WM, WN, KIND, GMODE, LISTED>(p, q, q.units * b / G, q.units * (b + 1) / G, G, own,
+                                                             xs0, xs1, xs2, wsm, steptab);
+}
+
+// Several products of one shape and one index list (so: one geometry) in one launch: the work
+// units of the members follow each other, tile by tile inside a member, and the workgroups share
+// out the whole sequence.  A workgroup's range may run across members.
+constexpr int GROUP_MAX = COMET_SHARE_GROUP_MAX;
+struct GemmGroup {
+    int n;
+    GemmParams p[GROUP_MAX];
+};
+
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool OWN>
+__global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMODE))) void ring_gemm_group_kernel(GemmGroup grp) {
+    using T = Tile<WAVES_M, WAVES_N, WM, WN>;
+    COMET_GEMM_LDS(T, GMODE);
+    const Geometry q = gemm_geometry<T, KIND, false>(grp.p[0]);
+    if (q.units == 0) return;
+    const int G = gridDim.x;
+    const int b = xcd_contiguous(blockIdx.x, G);
+    const long total = q.units * grp.n;
+    long u = total * b / G;
+    const long u_end = total * (b + 1) / G;
+    bool own = false;
+    if constexpr (OWN) own = owns_tiles(grp.p[0], q.m_eff, q.n_eff, q.kc);
+#pragma nounroll
+    for (int j = (int)(u / q.units); u < u_end; ++j) {
+        const long base = (long)j * q.units;
+        const long hi = u_end - base < q.units ? u_end - base : q.units;
+        gemm_sweep<WAVES_M, WAVES_N, WM, WN, KIND, GMODE, false>(grp.p[j], q, u - base, hi, G, own, xs0, xs1, xs2,
+                                                                 wsm, steptab);
+        u = base + q.units;
+    }
+}
+
 // The kernel variant for a call: the kind of product, how the weight side is addressed, and
 // (LISTED) whether a step list is walked.  Instantiated explicitly, one translation unit per
 // (tile shape, LISTED), so that the variants compile side by side.
@@ -1147,12 +1207,49 @@ int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
     if (p.tile_bm != T::BM || p.tile_bn != T::BN || p.grid < 1)
         return comet_fail(ctx, COMET_EINVAL, "%s: launch plan does not match the kernel", what);
     const long grid = p.grid;
-    const bool timed = ctx->ev && ctx->ev_used + 2 <= ctx->ev_cap;
-    if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], ctx->stream);
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), 0, ctx->stream, p);
+    const bool timed = comet_time_this_launch(ctx);
     if (timed) {
-        (void)hipEventRecord(ctx->ev[ctx->ev_used + 1], ctx->stream);
+        // the event pair rides on the dispatch itself (its start and end timestamps): no marker
+        // packets before or after the kernel, so timing leaves the stream's schedule as it is
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), 0, ctx->stream, ctx->ev[ctx->ev_used],
+                              ctx->ev[ctx->ev_used + 1], 0, p);
         ctx->ev_used += 2;
+    } else {
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), 0, ctx->stream, p);
+    }
+    COMET_LAUNCH_CHECK(ctx, what);
+    return COMET_OK;
+}
+
+// The grouped kernel exists for weight planes and the 128 x 64 tile (translation units
+// ring_gemm_group_128x64*.hip).
+using GemmGroupKernel = void (*)(GemmGroup);
+
+template <int WAVES_M, int WAVES_N, int WM, int WN, bool OWN>
+GemmGroupKernel gemm_group_kernel_for(const GemmParams& p) {
+    if (p.kind == KIND_SIMM) {
+        if (p.b_full) return ring_gemm_group_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, W_PLANES_GATHER, OWN>;
+        return ring_gemm_group_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SIMM, W_PLANES, OWN>;
+    }
+    return ring_gemm_group_kernel<WAVES_M, WAVES_N, WM, WN, KIND_SOMM, W_PLANES, OWN>;
+}
+extern template GemmGroupKernel gemm_group_kernel_for<2, 2, 2, 1, false>(const GemmParams&);
+extern template GemmGroupKernel gemm_group_kernel_for<2, 2, 2, 1, true>(const GemmParams&);
+
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+int launch_gemm_group(comet_ctx* ctx, const char* what, const GemmGroup& grp) {
+    using T = Tile<WAVES_M, WAVES_N, WM, WN>;
+    const GemmParams& p = grp.p[0];
+    if (grp.n < 1 || grp.n > GROUP_MAX || !p.w_planes || p.tile_bm != T::BM || p.tile_bn != T::BN || p.grid < 1)
+        return comet_fail(ctx, COMET_EINVAL, "%s: launch plan does not match the grouped kernel", what);
+    GemmGroupKernel kern = p.own_try ? gemm_group_kernel_for<WAVES_M, WAVES_N, WM, WN, true>(p)
+                                     : gemm_group_kernel_for<WAVES_M, WAVES_N, WM, WN, false>(p);
+    if (comet_time_this_launch(ctx)) {
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)p.grid), dim3(GT), 0, ctx->stream, ctx->ev[ctx->ev_used],
+                              ctx->ev[ctx->ev_used + 1], 0, grp);
+        ctx->ev_used += 2;
+    } else {
+        hipLaunchKernelGGL(kern, dim3((unsigned)p.grid), dim3(GT), 0, ctx->stream, grp);
     }
     COMET_LAUNCH_CHECK(ctx, what);
     return COMET_OK;

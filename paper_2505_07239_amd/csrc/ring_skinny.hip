@@ -242,13 +242,15 @@ int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p) {
     if (slices < 1) slices = 1;
     void (*kern)(GemmParams, const u64*, int);
     kern = vec2 ? pick_kernel<MR, 2>(p.kind) : pick_kernel<MR, 1>(p.kind);
-    const bool timed = ctx->ev && ctx->ev_used + 2 <= ctx->ev_cap;
-    if (timed) (void)hipEventRecord(ctx->ev[ctx->ev_used], ctx->stream);
-    hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)slices), dim3(ST), 0, ctx->stream, p,
-                       (const u64*)xs, (int)slices);
+    const bool timed = comet_time_this_launch(ctx);
     if (timed) {
-        (void)hipEventRecord(ctx->ev[ctx->ev_used + 1], ctx->stream);
+        // the event pair rides on the dispatch itself: no marker packets around the kernel
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)slices), dim3(ST), 0, ctx->stream,
+                              ctx->ev[ctx->ev_used], ctx->ev[ctx->ev_used + 1], 0, p, (const u64*)xs, (int)slices);
         ctx->ev_used += 2;
+    } else {
+        hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)slices), dim3(ST), 0, ctx->stream, p,
+                           (const u64*)xs, (int)slices);
     }
     COMET_LAUNCH_CHECK(ctx, what);
     return COMET_OK;

@@ -439,6 +439,29 @@ def test_share_is_deterministic(ctx):
     assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], case.z[1])
 
 
+def test_share_kernel_timing_counts_and_leaves_results_alone(ctx):
+    """Timed launches (event pairs attached to the kernel's dispatch), every launch and every
+    third one: the launch counts, positive kernel times, and the same output as untimed calls."""
+    import paper_2505_07239_amd as comet
+    case = _random_case("somm", 96, 160, 256, 16, 7, 56)
+    for m in (96, 5):                                  # the matrix-core kernel and the few-row kernel
+        e, a, c = case.e[:m], case.a[0][:m], case.c[0][:m]
+        want = case.z[0][:m]                            # output rows are independent of each other
+        for stride, calls, timed in ((0, 4, 4), (3, 7, 3), (1, 2, 2)):
+            say("timing m=%d stride=%d" % (m, stride))
+            ctx.set_tuning(comet.TUNE_TIMING_STRIDE, stride)
+            ctx.timing_begin(calls)
+            try:
+                for _ in range(calls):
+                    z = _run_share(ctx, "somm", 0, 16, case.idx, len(case.idx), e, case.f, a, case.b[0], c)
+            finally:
+                ms, n = ctx.timing_end()
+                ctx.set_tuning(comet.TUNE_TIMING_STRIDE, 0)
+            torch.cuda.synchronize()
+            assert n == timed and 0.0 < ms < 1000.0
+            assert np.array_equal(down(z), want)
+
+
 def test_end_to_end_pipeline_config2(ctx):
     """compact -> mask (indexed) -> open -> share, chained on the device with
     n_blk never leaving it; then reconstruction against the plaintext product."""
