@@ -675,6 +675,12 @@ def main():
     else:
         timing = run_timed(ctx, layer, args.steps, args.warmup, run_step)
     ms_per_step = timing["ms_per_step"]
+    t2 = None
+    if run_step == layer.step_grouped and not args.graph:
+        # the same K steps with one share call per product and party, for comparison
+        t2 = run_timed(ctx, layer, args.steps, 2, layer.step)
+        run_step()                      # leave the grouped calls' outputs in place for the oracle check
+        torch.cuda.synchronize()
 
     value = layer.ring_ops_per_step / (ms_per_step * 1e-3) / 1e9
     kernels = None
@@ -703,15 +709,11 @@ def main():
                                  ("eager, two streams" if args.overlap else "eager")},
         "roofline": roofline_of(layer, wname, timing, bool(args.skinny), kernels),
     }
-    if run_step == layer.step_grouped and not args.graph:
-        # the same K steps with one share call per product and party, for comparison
-        t2 = run_timed(ctx, layer, args.steps, 2, layer.step)
+    if t2 is not None:
         r2 = roofline_of(layer, wname, t2, bool(args.skinny), kernels)
         result["per_call"] = {"ms_per_step": t2["ms_per_step"], "value": layer.ring_ops_per_step / (t2["ms_per_step"] * 1e-3) / 1e9,
                               "share_launches_per_step": t2["launches_per_step"], "avg_launch_ms": r2["avg_launch_ms"],
                               "frac": r2["frac"], "frac_of_measured_mfma_issue": r2.get("frac_of_measured_mfma_issue")}
-        run_step()                      # leave the grouped calls' outputs in place for the oracle check
-        torch.cuda.synchronize()
     if kernels is not None:
         result["kernels"] = kernels
     if not args.no_cpu_baseline:

@@ -51,6 +51,7 @@ struct GemmParams {
     int grid;                 // workgroups
     int tile_bm, tile_bn;     // output tile
     int own_try;              // plain product (no result blocks, no step lists, default slicing)
+    int k_rotate;             // units tile by tile; the parts of a tile take its steps in reverse order (see gemm_sweep)
     int group_n;              // members of the group launch this product is part of (0 or 1: on its own)
 };
 

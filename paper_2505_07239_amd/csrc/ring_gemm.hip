@@ -530,6 +530,7 @@ int run_share_group(comet_ctx* ctx, const char* what, GemmParams* ps, int n, voi
         p.tile_bn = T::BN;
         p.group_n = n;
         p.own_try = (tiles * n % grid == 0) ? 1 : 0;
+        p.k_rotate = 1;
     }
     {
         const GemmParams& p = grp.p[0];

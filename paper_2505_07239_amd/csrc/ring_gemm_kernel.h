@@ -834,6 +834,7 @@ __device__ __forceinline__ void gemm_sweep(const GemmParams& p, const Geometry& 
     const int b_off = (g * T::BN + wn * WN * 32 + r) * 16;
 
     LD ld;
+    const long u_begin = u;
 
     // Work units are ordered chunk-major: all tiles for contraction steps
     // [0, CH), then all tiles for [CH, 2 CH), ...  Workgroups that run side by
@@ -888,6 +889,17 @@ __device__ __forceinline__ void gemm_sweep(const GemmParams& p, const Geometry& 
         }
         if (len > u_end - u) len = u_end - u;
         const int L = (int)len;
+        if (!listed && p.k_rotate) {
+            // Units tile by tile, a tile cut into parts by the workgroup ranges: the parts take their
+            // contraction steps in reverse order of their positions (the part [c, d) of a tile gets
+            // the steps [KT - d, KT - c); any order gives the same sum).  A workgroup that starts
+            // in the middle of a tile thus begins at step 0 like one that starts on a tile, and
+            // all workgroups sweep the contraction in two phases only, KT - share apart: the
+            // activation planes of a phase are shared through L2 instead of being fetched per tile.
+            const long tile_u0 = u - ks0;
+            const long c_lo = u_begin - tile_u0, c_hi = u_end - tile_u0;
+            ks0 += KT - (c_lo > 0 ? (int)c_lo : 0) - (c_hi < KT ? (int)c_hi : KT);
+        }
 
         ld.setup(p, tm, tn, n_eff);
         ld.steps = listed_steps;
