@@ -56,9 +56,12 @@ struct Tile {
     static constexpr int WSTAGES = 2;                // written from registers one step ahead
     static constexpr int WBASE = XSTAGES * XBYTES;
     static constexpr int SMEM = XSTAGES * XBYTES + WSTAGES * WBYTES;
-    static constexpr int XVEC = XBYTES / 16 / GT;    // 16-byte units per thread per stage
-    static constexpr int WVEC = WBYTES / 16 / GT;    // same for a weight stage filled by LDS-DMA
-    static constexpr int WTASK = BN * 4 / GT;        // (column, octet) tasks per thread per stage
+    // four wavefronts, one per SIMD (the plane variants also build with eight -- Tile<4, 2, 1, 1>,
+    // two wavefronts per SIMD on the 128 x 64 tile -- which measured no faster and is not instantiated)
+    static constexpr int THREADS = WAVES_M * WAVES_N * 64;
+    static constexpr int XVEC = XBYTES / 16 / THREADS;    // 16-byte units per thread per stage
+    static constexpr int WVEC = WBYTES / 16 / THREADS;    // same for a weight stage filled by LDS-DMA
+    static constexpr int WTASK = BN * 4 / GT;        // (column, octet) tasks per thread per stage (word loader: 256 threads)
     // vector-memory loads a thread issues per step: the LDS-DMA units plus, per weight task,
     // eight 8-byte loads (or four 16-byte loads when the weights are neuron-major)
     // and one load of a block id with the power-of-two row gather; with weight planes only
@@ -74,8 +77,10 @@ struct Tile {
         return XSTAGES * XBYTES + wstages(gmode) * WBYTES + (is_planes(gmode) ? MAX_SEG * 16 : 0);
     }
     // two workgroups share a compute unit when one needs at most half of its registers and LDS
-    static constexpr int wg_per_cu(int gmode) { return (WM * WN == 1 && smem(gmode) <= 80 * 1024) ? 2 : 1; }
-    static_assert(WAVES_M * WAVES_N * 64 == GT, "four wavefronts per workgroup");
+    static constexpr int wg_per_cu(int gmode) {
+        return (WM * WN == 1 && THREADS == GT && smem(gmode) <= 80 * 1024) ? 2 : 1;
+    }
+    static_assert(THREADS == GT || THREADS == 2 * GT, "four or eight wavefronts per workgroup");
     static_assert(XVEC >= 1 && WTASK >= 1, "tile too small for the loader");
     static_assert(vm_per_step(GATHER_POW2) < 63, "outstanding-load counter has 6 bits");
     static_assert(SMEM <= 160 * 1024, "LDS of one CDNA4 compute unit");
@@ -149,6 +154,7 @@ struct Loader {
     int gpend[W];              // GATHER_POW2: block id requested for the step after this one
     const int* steps;          // listed contraction steps of this row tile, or null (all steps)
 
+    static_assert(T::THREADS == GT, "the word loader is written for four wavefronts");
     static constexpr int XGRP_PER_PASS = GT / T::BM;         // groups covered by one pass of the block
     static_assert(GT % T::BM == 0, "tile rows must divide the block");
 
@@ -409,8 +415,8 @@ struct PlaneLoader {
     static constexpr int XV = T::XVEC, WV = T::WVEC;
     static constexpr int P_END = XV + WV;
     static constexpr int VM_PER_STEP = XV + WV;
-    static constexpr int XGRP_PER_PASS = GT / T::BM;
-    static_assert(GT % T::BM == 0, "tile rows must divide the block");
+    static constexpr int XGRP_PER_PASS = T::THREADS / T::BM;
+    static_assert(T::THREADS % T::BM == 0, "tile rows must divide the block");
     static_assert(T::BN % 64 == 0, "a wavefront's transfer stays inside one run of units");
 
     unsigned pcb[WV], pcf[WV], pcsel[WV];   // lane's byte offset of its column inside a run: B_i, F, selected
@@ -427,7 +433,7 @@ struct PlaneLoader {
     __device__ __forceinline__ void setup(const GemmParams& p, int tm, int tn, int n_eff) {
 #pragma unroll
         for (int j = 0; j < WV; ++j) {
-            const int u = threadIdx.x + GT * j;            // unit of the stage: run u / BN, column u % BN
+            const int u = threadIdx.x + T::THREADS * j;            // unit of the stage: run u / BN, column u % BN
             int col = tn * T::BN + u % T::BN;
             col = col < n_eff ? col : n_eff - 1;
             long bcol = col;
@@ -450,7 +456,7 @@ struct PlaneLoader {
     // steps (all threads; the caller synchronises).  Rows past the end of the contraction keep
     // a valid address: their activation digits are zero.
     __device__ __forceinline__ void build_table(const GemmParams& p, int* table, int ks0, int L, int KS, int kc) {
-        for (int q = threadIdx.x; q < L; q += GT) {
+        for (int q = threadIdx.x; q < L; q += T::THREADS) {
             const int ks = ks0 + q;
             const int h = ks >= KS ? 1 : 0;
             int s = ks - h * KS;
@@ -497,7 +503,7 @@ struct PlaneLoader {
     __device__ __forceinline__ void xdma_piece(unsigned char* xstage) {
         const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
         const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)xstage;
-        const unsigned lds = __builtin_amdgcn_readfirstlane(lds0 + (wave * 64 + GT * J) * 16);
+        const unsigned lds = __builtin_amdgcn_readfirstlane(lds0 + (wave * 64 + T::THREADS * J) * 16);
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                      :
                      : "s"(lds), "v"(xs2 + J * xstride)
@@ -509,11 +515,11 @@ struct PlaneLoader {
     template <int J>
     __device__ __forceinline__ void wdma_piece(unsigned char* wstage) {
         const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-        const int run = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + GT * J) / T::BN));   // t * 2 + g
+        const int run = __builtin_amdgcn_readfirstlane((int)((threadIdx.x + T::THREADS * J) / T::BN));   // t * 2 + g
         const int r0 = (run & 1) ? n0b : n0a;
         const char* sb = pbase + (size_t)(r0 >> 5) * prow + (size_t)((run & ~1) | ((r0 >> 4) & 1)) * 1024u;
         const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)wstage;
-        const unsigned lds = __builtin_amdgcn_readfirstlane(lds0 + (wave * 64 + GT * J) * 16);
+        const unsigned lds = __builtin_amdgcn_readfirstlane(lds0 + (wave * 64 + T::THREADS * J) * 16);
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :
                      : "s"(lds), "v"(pcsel[J]), "s"(sb)
@@ -1038,7 +1044,7 @@ __device__ __forceinline__ int xcd_contiguous(int b, int G) {
 // owns_tiles()); it still checks that on the device, where the counts are, and falls back to the
 // shared-tile path.  The other variant never owns: it carries none of that code.
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool LISTED, bool OWN = false>
-__global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMODE))) void ring_gemm_kernel(GemmParams p) {
+__global__ __launch_bounds__((Tile<WAVES_M, WAVES_N, WM, WN>::THREADS), (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMODE))) void ring_gemm_kernel(GemmParams p) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     COMET_GEMM_LDS(T, GMODE);
     if (p.tile_sel && *p.tile_sel != p.tile_sel_want) return;   // the other tile shape was chosen
@@ -1062,7 +1068,7 @@ struct GemmGroup {
 };
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool OWN>
-__global__ __launch_bounds__(GT, (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMODE))) void ring_gemm_group_kernel(GemmGroup grp) {
+__global__ __launch_bounds__((Tile<WAVES_M, WAVES_N, WM, WN>::THREADS), (Tile<WAVES_M, WAVES_N, WM, WN>::wg_per_cu(GMODE))) void ring_gemm_group_kernel(GemmGroup grp) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     COMET_GEMM_LDS(T, GMODE);
     const Geometry q = gemm_geometry<T, KIND, false>(grp.p[0]);
@@ -1223,11 +1229,11 @@ int launch_gemm(comet_ctx* ctx, const char* what, GemmParams p) {
     if (timed) {
         // the event pair rides on the dispatch itself (its start and end timestamps): no marker
         // packets before or after the kernel, so timing leaves the stream's schedule as it is
-        hipExtLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), 0, ctx->stream, ctx->ev[ctx->ev_used],
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(T::THREADS), 0, ctx->stream, ctx->ev[ctx->ev_used],
                               ctx->ev[ctx->ev_used + 1], 0, p);
         ctx->ev_used += 2;
     } else {
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(GT), 0, ctx->stream, p);
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(T::THREADS), 0, ctx->stream, p);
     }
     COMET_LAUNCH_CHECK(ctx, what);
     return COMET_OK;
@@ -1257,11 +1263,11 @@ int launch_gemm_group(comet_ctx* ctx, const char* what, const GemmGroup& grp) {
     GemmGroupKernel kern = p.own_try ? gemm_group_kernel_for<WAVES_M, WAVES_N, WM, WN, true>(p)
                                      : gemm_group_kernel_for<WAVES_M, WAVES_N, WM, WN, false>(p);
     if (comet_time_this_launch(ctx)) {
-        hipExtLaunchKernelGGL(kern, dim3((unsigned)p.grid), dim3(GT), 0, ctx->stream, ctx->ev[ctx->ev_used],
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)p.grid), dim3(T::THREADS), 0, ctx->stream, ctx->ev[ctx->ev_used],
                               ctx->ev[ctx->ev_used + 1], 0, grp);
         ctx->ev_used += 2;
     } else {
-        hipLaunchKernelGGL(kern, dim3((unsigned)p.grid), dim3(GT), 0, ctx->stream, grp);
+        hipLaunchKernelGGL(kern, dim3((unsigned)p.grid), dim3(T::THREADS), 0, ctx->stream, grp);
     }
     COMET_LAUNCH_CHECK(ctx, what);
     return COMET_OK;

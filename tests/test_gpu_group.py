@@ -58,7 +58,8 @@ def _member(seed, kind, party, m, k, n, bs, idx, cap):
     if kind == "somm":
         e, a, b = u64(seed, 1, m, k), u64(seed, 2, m, k), u64(seed, 3, k, n)
         f, c = junk(1, k, ld), junk(2, m, ld)
-        want = co.beaver_share(party, e, f[:, :kc], a, co.index_cols(b, idx, bs), c[:, :kc])
+        want = (co.beaver_share(party, e, f[:, :kc], a, co.index_cols(b, idx, bs), c[:, :kc]) if t
+                else np.zeros((m, 0), np.uint64))
     else:
         e, a, b = junk(3, m, ld), u64(seed, 2, m, k), u64(seed, 3, k, n)
         f, c = junk(4, ld, n), u64(seed, 5, m, n)
@@ -66,7 +67,8 @@ def _member(seed, kind, party, m, k, n, bs, idx, cap):
     return dict(party=party, e=e, f=f, a=a, b=b, c=c, want=want)
 
 
-def _run_group(ctx, kind, m, k, n, bs, kept, spare, parties, planes=True, seed=0):
+def _run_group(ctx, kind, m, k, n, bs, kept, spare, parties, planes=True, seed=0, single=False):
+    """``single``: the members through one ``somm_share`` / ``simm_share`` call each instead."""
     idx = np.array(sorted(kept), dtype=np.int32)
     t, cap = len(idx), len(idx) + spare
     kc = t * bs
@@ -81,7 +83,11 @@ def _run_group(ctx, kind, m, k, n, bs, kept, spare, parties, planes=True, seed=0
         zshape = (m, cap * bs) if kind == "somm" else (m, n)
         outs.append(torch.full(zshape, int(SENTINEL.view(np.int64)), dtype=torch.int64, device="cuda"))
         wants.append(mb["want"])
-    got = ctx.share_group(kind, bs, gi, n_dev, cap, members, out=outs)
+    if single:
+        call = ctx.somm_share if kind == "somm" else ctx.simm_share
+        got = [call(mb[0], bs, gi, n_dev, cap, *mb[1:], out=o) for mb, o in zip(members, outs)]
+    else:
+        got = ctx.share_group(kind, bs, gi, n_dev, cap, members, out=outs)
     torch.cuda.synchronize()
     for j, (z, want) in enumerate(zip(got, wants)):
         z = down(z)
@@ -125,6 +131,24 @@ def test_share_group_one_launch(ctx, kind, m, k, n, bs, kept, spare, parties, gr
     ctx.set_tuning(comet.TUNE_GEMM_GRID, grid)
     try:
         _run_group(ctx, kind, m, k, n, bs, kept, spare, parties, seed=900)
+    finally:
+        ctx.set_tuning(comet.TUNE_GROUP, 0)
+        ctx.set_tuning(comet.TUNE_GEMM_GRID, 0)
+
+
+@pytest.mark.parametrize("single", [False, True])
+@pytest.mark.parametrize("kept,spare", [((0, 1, 4, 5), 0), ((0, 4, 5), 1), ((1, 5), 2), ((3,), 3), ((), 4)])
+def test_owned_tiles_follow_the_device_side_block_count(ctx, kept, spare, single):
+    """A launch planned for owned tiles (capacity of four blocks: 2 x 2 tiles per product on a grid
+    that divides their number) with fewer blocks on the device: a ragged last tile still owned,
+    a tile count the grid no longer divides (shared tiles after all, and the packing kernel has to
+    initialise Z after all), and no block at all.  Weight planes (single and grouped calls)."""
+    import paper_2505_07239_amd as comet
+    say("owned tiles, kept=%s capacity=%d single=%s" % (kept, len(kept) + spare, single))
+    ctx.set_tuning(comet.TUNE_GROUP, 1)
+    ctx.set_tuning(comet.TUNE_GEMM_GRID, 4)
+    try:
+        _run_group(ctx, "somm", 256, 64, 8 * 32, 32, kept, spare, (0, 1), seed=980, single=single)
     finally:
         ctx.set_tuning(comet.TUNE_GROUP, 0)
         ctx.set_tuning(comet.TUNE_GEMM_GRID, 0)
