@@ -32,8 +32,10 @@ def u64(seed, stream, *shape):
     return rng.uniform_u64(seed, stream, int(np.prod(shape))).reshape(shape)
 
 
-@pytest.mark.parametrize("m", [8, 96])
-def test_chain_replays_from_a_graph(m):
+@pytest.mark.parametrize("m,grouped", [(8, False), (96, False), (96, True)])
+def test_chain_replays_from_a_graph(m, grouped):
+    """``grouped``: F is opened straight into digit planes and both parties' shares come out of one
+    ``comet_share_group`` call (one packing launch, one matrix-core launch)."""
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     import paper_2505_07239_amd as comet
@@ -54,8 +56,22 @@ def test_chain_replays_from_a_graph(m):
     g = [torch.empty((k, ld), dtype=torch.int64, device=dev) for _ in (0, 1)]
     e, f = torch.empty((m, k), dtype=torch.int64, device=dev), torch.empty((k, ld), dtype=torch.int64, device=dev)
     z = [torch.zeros((m, ld), dtype=torch.int64, device=dev) for _ in (0, 1)]
+    if grouped:
+        ctx.set_tuning(comet.TUNE_GROUP, 1)
+        b_planes = [ctx.open_weight_planes(b[i]) for i in (0, 1)]      # offline, outside the graph
+        f_planes = ctx.open_weight_planes(g[0], g[1])                   # buffer of the right size
 
     def chain():
+        if grouped:
+            ctx.compact_mask(mask, idx, n_dev)
+            for i in (0, 1):
+                ctx.mask_share(x[i], a[i], out=d[i])
+                ctx.mask_share_gather(y[i], b[i], comet.AXIS_COLS, bs, idx, n_dev, cap, out=g[i])
+            ctx.open(d[0], d[1], out=e)
+            ctx.open_weight_planes(g[0], g[1], out=f_planes.buf)
+            ctx.share_group("somm", bs, idx, n_dev, cap,
+                            [(i, e, f_planes, a[i], b_planes[i], c[i]) for i in (0, 1)], out=z)
+            return
         ctx.compact_mask(mask, idx, n_dev)
         for i in (0, 1):
             ctx.mask_share(x[i], a[i], out=d[i])
