@@ -58,12 +58,13 @@ __global__ __launch_bounds__(EW_THREADS) void ew_kernel(const u64* a, const u64*
 template <int VEC>
 __global__ __launch_bounds__(EW_THREADS) void gather_cols_kernel(
     const u64* __restrict__ w, const u64* __restrict__ b, u64* __restrict__ g, int cols, int ld,
-    int bs, const int* __restrict__ blk_idx, const int* __restrict__ n_blk_dev, int n_blk_cap) {
+    int bs, const int* __restrict__ blk_idx, const int* __restrict__ n_blk_dev, int n_blk_cap, int gy) {
     const int n_blk = n_blk_dev ? min(*n_blk_dev, n_blk_cap) : n_blk_cap;
     const int width = n_blk * bs;
-    const size_t r = blockIdx.x;
-    for (int c = (blockIdx.y * EW_THREADS + threadIdx.x) * VEC; c < width;
-         c += gridDim.y * EW_THREADS * VEC) {
+    // workgroups are numbered row by row (the pieces of a row are dispatched together)
+    const size_t r = blockIdx.x / (unsigned)gy;
+    const int piece = (int)(blockIdx.x % (unsigned)gy);
+    for (int c = (piece * EW_THREADS + threadIdx.x) * VEC; c < width; c += gy * EW_THREADS * VEC) {
         const int blk = c / bs;
         const long start = (long)blk_idx[blk] * bs;
         if (start < 0 || start + bs > cols) continue;      // id outside the matrix: skip, never fault
@@ -172,17 +173,19 @@ int comet_mask_share_gather(comet_ctx* ctx, const uint64_t* w_i, const uint64_t*
     if (axis == COMET_AXIS_COLS) {
         const bool vec = (bs % 2 == 0) && (cols % 2 == 0);
         const int per = EW_THREADS * (vec ? 2 : 1);
-        unsigned gy = (unsigned)((ld + per - 1) / per);
-        if (gy > 65535u) gy = 65535u;
-        const dim3 grid((unsigned)rows, gy);
+        long gy = (ld + per - 1) / per;
+        // pieces per row, capped so that rows x pieces stays a valid one-dimensional grid
+        const long gy_max = (1l << 31) / (rows > 0 ? rows : 1) - 1;
+        if (gy > gy_max) gy = gy_max < 1 ? 1 : gy_max;
+        const dim3 grid((unsigned)(rows * gy));
         if (vec)
             hipLaunchKernelGGL((gather_cols_kernel<2>), grid, dim3(EW_THREADS), 0, ctx->stream,
                                (const u64*)w_i, (const u64*)b_i, (u64*)g_i, (int)cols, ld, bs,
-                               blk_idx, n_blk_dev, n_blk_cap);
+                               blk_idx, n_blk_dev, n_blk_cap, (int)gy);
         else
             hipLaunchKernelGGL((gather_cols_kernel<1>), grid, dim3(EW_THREADS), 0, ctx->stream,
                                (const u64*)w_i, (const u64*)b_i, (u64*)g_i, (int)cols, ld, bs,
-                               blk_idx, n_blk_dev, n_blk_cap);
+                               blk_idx, n_blk_dev, n_blk_cap, (int)gy);
     } else {
         const bool vec = (cols % 2 == 0);
         const int per = EW_THREADS * (vec ? 2 : 1) * 2;
