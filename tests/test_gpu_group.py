@@ -110,6 +110,10 @@ CASES = [
     ("somm", 256, 64, 8 * 32, 32, (0, 1, 4, 5), 2, (0, 1), 8),
     # owned tiles with a contraction longer than one segment (2 * 4128 / 32 = 258 steps)
     ("somm", 128, 4128, 4 * 32, 32, (1, 2), 0, (1, 0), 2),
+    # the same product on three workgroups: tiles cut into parts (some longer than one
+    # accumulation segment), contraction steps taken in the rotated order
+    ("somm", 128, 4128, 4 * 32, 32, (1, 2), 0, (1, 0), 3),
+    ("somm", 256, 4128, 6 * 32, 32, (1, 2, 4), 1, (1, 0, 0), 5),
     # shared tiles, long contraction, one workgroup does everything
     ("somm", 70, 4128, 2 * 32, 32, (1,), 0, (0, 1, 1), 1),
     # eight members
@@ -119,6 +123,8 @@ CASES = [
     ("simm", 256, 8 * 32, 128, 32, (0, 1, 4, 5), 0, (0, 1), 4),
     ("simm", 256, 8 * 32, 128, 32, (0, 1, 4, 5), 2, (0, 1), 8),
     ("simm", 128, 140 * 32, 64, 32, tuple(range(0, 140, 1))[:130], 0, (1, 0), 2),
+    ("simm", 128, 140 * 32, 64, 32, tuple(range(0, 140, 1))[:130], 0, (1, 0), 3),
+    ("simm", 256, 140 * 32, 128, 32, tuple(range(3, 140, 1))[:131], 2, (0, 1, 1), 5),
     ("simm", 100, 6 * 16, 40, 16, (0, 3, 5), 0, (0, 1, 0, 1, 1, 0, 1, 0), 0),
 ]
 
