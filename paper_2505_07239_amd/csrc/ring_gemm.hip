@@ -28,16 +28,23 @@
 //     the stacked contraction) work units are dealt out evenly over a fixed,
 //     chip-sized grid (a stream-K split) and every run of units inside one
 //     tile ends with 64-bit atomic adds onto Z, which starts out as [C]_i.
-//     The result is bit-exact whatever the split.
+//     The result is bit-exact whatever the split.  When the grid divides the
+//     number of tiles every workgroup owns whole tiles instead: it stores
+//     Z = C + sum itself and no atomic add is issued (owns_tiles()).
+//   * Several products of one shape (comet_share_group) run as one launch over
+//     the concatenation of their work units.
 //
 // Data flow
 //   xpack kernel : E, A_i  -> digit planes of [E | A'] in the workspace, laid
 //                  out so that a tile is a linear copy into LDS (small operand).
-//   gemm kernel  : weight-side words are loaded once as uint64 (with the block
+//   gemm kernel  : weight-side WORDS are loaded once as uint64 (with the block
 //                  gather folded into the addressing), split into digits and
 //                  byte-transposed in registers, staged through LDS, and fed
-//                  to v_mfma_i32_32x32x32_i8.  The weight matrices are the
-//                  large operands; they are never re-written to memory.
+//                  to v_mfma_i32_32x32x32_i8; they are never re-written to
+//                  memory.  Weight-side PLANES (COMET_WEIGHT_PLANES: F opened in
+//                  that format, B_i packed offline, see wplanes.hip) go to LDS
+//                  by LDS-DMA like the activation planes: a step then holds
+//                  nothing but matrix instructions and their fragment reads.
 #include "ring_gemm_kernel.h"
 
 #include <mutex>
