@@ -1,6 +1,10 @@
 """GPU parity at the benchmark's full sizes (configs 3, 4 and 5), in the launch
-configuration bench.py times: the whole pipeline (compact -> indexed masking ->
-open -> both parties' shares) runs on the device with n_blk never leaving it.
+configurations bench.py times: the whole pipeline (compact -> indexed masking ->
+open -> both parties' shares) runs on the device with n_blk never leaving it,
+once with word operands and one share call per product and party, and once as
+bench.py's default step does it: F opened straight into digit planes, B_i packed
+into planes beforehand, and the share products that are ready together in one
+grouped call (gate and up of both parties; down of both parties).
 
 Everything is compared element by element: compaction, masking, opening and
 both parties' output shares on every row and column (the oracle needs a few
@@ -188,3 +192,83 @@ def test_config5_density_sweep(ctx, density):
     mm = cfg.matmuls[0]
     say("config 5 density %.2f down-projection m=%d k=%d n=%d" % (density, mm.m, mm.k, mm.n))
     _run_projection(ctx, cfg, mm, mask)
+
+
+def _run_grouped(ctx, cfg, mms, mask_np):
+    """bench.py's default step for the projections ``mms`` (one kind, one shape): weight-side
+    operands as digit planes, all products of both parties in one ``share_group`` call (the
+    library decides whether that is one launch).  Every output element against the oracle."""
+    import paper_2505_07239_amd as comet
+    bs, kind = cfg.bs, mms[0].kind
+    idx_np = co.compact_mask(mask_np)
+    t = len(idx_np)
+    n_act = t * bs
+    idx, n_dev = ctx.compact_mask(torch.from_numpy(mask_np).cuda())
+    members, wants = [], []
+    for mm in mms:
+        sid = lambda role: configs.stream_id(cfg, mm.index, role)
+        u = lambda role, *shape: rng.uniform_u64(rng.BASE_SEED, sid(role), int(np.prod(shape))).reshape(shape)
+        x = [u(configs.R_XSPLIT, mm.m, mm.k), u(configs.R_X, mm.m, mm.k)]
+        y = [u(configs.R_YSPLIT, mm.k, mm.n), u(configs.R_Y, mm.k, mm.n)]
+        a = [u(configs.R_ASPLIT, mm.m, mm.k), u(configs.R_A, mm.m, mm.k)]
+        b = [u(configs.R_BSPLIT, mm.k, mm.n), u(configs.R_B, mm.k, mm.n)]
+        zshape = (mm.m, n_act) if kind == "somm" else (mm.m, mm.n)
+        c = [rng.uniform_u64(rng.BASE_SEED, sid(configs.R_CSPLIT) + 50 * i, zshape[0] * zshape[1]).reshape(zshape)
+             for i in (0, 1)]
+        ga, gb = [up(v) for v in a], [up(v) for v in b]
+        d, g = [], []
+        for i in (0, 1):
+            if kind == "somm":
+                d.append(ctx.mask_share(up(x[i]), ga[i]))
+                g.append(ctx.mask_share_gather(up(y[i]), gb[i], comet.AXIS_COLS, bs, idx, n_dev, t))
+            else:
+                d.append(ctx.mask_share_gather(up(x[i]), ga[i], comet.AXIS_COLS, bs, idx, n_dev, t))
+                g.append(ctx.mask_share_gather(up(y[i]), gb[i], comet.AXIS_ROWS, bs, idx, n_dev, t))
+        e = ctx.open(d[0], d[1])
+        f = ctx.open_weight_planes(g[0], g[1])
+        for i in (0, 1):
+            members.append((i, e, f, ga[i], ctx.open_weight_planes(gb[i]), up(c[i])))
+        torch.cuda.synchronize()
+        del gb, g, d
+        # oracle side, in full
+        if kind == "somm":
+            a_sel, b_sel = a, [co.index_cols(v, idx_np, bs) for v in b]
+            e_ref = co.open_(co.mask_share(x[0], a[0]), co.mask_share(x[1], a[1]))
+            f_ref = co.open_(*[co.mask_share(co.index_cols(y[i], idx_np, bs), b_sel[i]) for i in (0, 1)])
+        else:
+            a_sel = [co.index_cols(v, idx_np, bs) for v in a]
+            b_sel = [co.index_rows(v, idx_np, bs) for v in b]
+            e_ref = co.open_(*[co.mask_share(co.index_cols(x[i], idx_np, bs), a_sel[i]) for i in (0, 1)])
+            f_ref = co.open_(*[co.mask_share(co.index_rows(y[i], idx_np, bs), b_sel[i]) for i in (0, 1)])
+        assert np.array_equal(down(e), e_ref)
+        wants += [co.beaver_share(i, e_ref, f_ref, a_sel[i], b_sel[i], c[i]) for i in (0, 1)]
+        del x, y, a, b, a_sel, b_sel
+    outs = [_sentinel(*w.shape) for w in wants]
+    ctx.share_group(kind, bs, idx, n_dev, t, members, out=outs)
+    torch.cuda.synchronize()
+    assert int(n_dev.item()) == t
+    for j, (z, want) in enumerate(zip(outs, wants)):
+        assert np.array_equal(down(z), want), "member %d (projection %s, party %d)" % (j, mms[j // 2].name, j % 2)
+
+
+def test_config3_grouped_calls_on_weight_planes(ctx):
+    """The step bench.py times by default: gate and up of both parties in one grouped call (four
+    products, one launch), then down of both parties."""
+    cfg = configs.config(3)
+    mask = configs.token_masks(cfg)
+    somm = [mm for mm in cfg.matmuls if mm.kind == "somm"]
+    simm = [mm for mm in cfg.matmuls if mm.kind == "simm"]
+    say("config 3 grouped: %s" % "+".join(mm.name for mm in somm))
+    _run_grouped(ctx, cfg, somm, mask)
+    say("config 3 grouped: %s" % "+".join(mm.name for mm in simm))
+    _run_grouped(ctx, cfg, simm, mask)
+
+
+@pytest.mark.parametrize("density", configs.C5_DENSITIES)
+def test_config5_density_sweep_grouped_calls_on_weight_planes(ctx, density):
+    """Config 5 the way bench.py runs it: both parties' down-projection shares through one grouped
+    call on weight planes (one launch at 10 % and 5 %, two launches with owned tiles above)."""
+    cfg = configs.config(5, density)
+    mask = configs.token_masks(cfg)
+    say("config 5 density %.2f grouped call on weight planes" % density)
+    _run_grouped(ctx, cfg, [cfg.matmuls[0]], mask)
