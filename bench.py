@@ -305,7 +305,8 @@ def roofline_of(layer, wname, timing, skinny_forced, probes):
             r["frac_of_measured_copy"] = ach / probes["copy_GBs"]
     else:
         ach = INT8_OPS_PER_RING_MAC * macs_per_launch / (avg_ms * 1e-3) / 1e12
-        r = {"bound": "mfma", "kernel": "ring_gemm_kernel", "achieved": ach, "peak": PEAK_INT8_TOPS,
+        r = {"bound": "mfma", "kernel": "ring_gemm_group_kernel" if grouped else "ring_gemm_kernel",
+             "achieved": ach, "peak": PEAK_INT8_TOPS,
              "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS,
              "note": "algorithmic int8 ops: 36 digit products x 2 ops per ring MAC, two products per "
                      "party (2*m*k*n_act ring MACs per share product; a grouped launch computes "
