@@ -364,7 +364,9 @@ int comet_truncate_share(comet_ctx* ctx, int party, const uint64_t* z, uint64_t*
  *   COMET_TUNE_GROUP:     comet_share_group normally runs its members as one
  *                         launch when a member alone is a short launch (8 to
  *                         128 contraction steps of 32 words per workgroup);
- *                         1 = whenever the operands allow it, 2 = never */
+ *                         1 = whenever the operands allow it, 2 = never,
+ *                         3 = as 1 but without teaming the workgroups of a
+ *                         column of tiles (a measurement aid) */
 enum { COMET_TUNE_GEMM_GRID = 0, COMET_TUNE_GEMM_CHUNK = 1, COMET_TUNE_GEMM_TILE = 2,
        COMET_TUNE_SKINNY = 3, COMET_TUNE_SKINNY_SLICES = 4, COMET_TUNE_COMPONENTS = 5,
        COMET_TUNE_TIMING_STRIDE = 6, COMET_TUNE_GROUP = 7 };

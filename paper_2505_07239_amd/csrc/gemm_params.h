@@ -52,6 +52,7 @@ struct GemmParams {
     int tile_bm, tile_bn;     // output tile
     int own_try;              // plain product (no result blocks, no step lists, default slicing)
     int k_rotate;             // units tile by tile; the parts of a tile take its steps in reverse order (see gemm_sweep)
+    int team;                 // group launch: workgroups form teams over the row tiles (see ring_gemm_group_kernel)
     int group_n;              // members of the group launch this product is part of (0 or 1: on its own)
 };
 

@@ -512,7 +512,8 @@ int run_share_group(comet_ctx* ctx, const char* what, GemmParams* ps, int n, voi
     const long tiles = (long)((p0.m + T::BM - 1) / T::BM) * ((p0.n_cap + T::BN - 1) / T::BN);
     const long steps_each = tiles * 2 * ((p0.kc_cap + KSTEP - 1) / KSTEP) / grid;
     const bool grouped = n > 1 && p0.w_planes && p0.m > 64 && p0.n_cap > 0 && ctx->gemm_tile != 2 &&
-                         (ctx->group_mode == 1 || (ctx->group_mode == 0 && steps_each >= 8 && steps_each <= 128));
+                         (ctx->group_mode == 1 || ctx->group_mode == 3 ||
+                          (ctx->group_mode == 0 && steps_each >= 8 && steps_each <= 128));
     if (!grouped) {
         for (int j = 0; j < n; ++j) {
             const int rc = run_share(ctx, what, ps[j], base + (size_t)j * each, each);
@@ -538,6 +539,7 @@ int run_share_group(comet_ctx* ctx, const char* what, GemmParams* ps, int n, voi
         p.group_n = n;
         p.own_try = (tiles * n % grid == 0) ? 1 : 0;
         p.k_rotate = 1;
+        p.team = ctx->group_mode != 3;      // (3: one launch without teams, for comparison)
     }
     {
         const GemmParams& p = grp.p[0];

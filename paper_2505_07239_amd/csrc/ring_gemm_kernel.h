@@ -824,13 +824,16 @@ __device__ __forceinline__ Geometry gemm_geometry(const GemmParams& p) {
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KIND, int GMODE, bool LISTED>
 __device__ __forceinline__ void gemm_sweep(const GemmParams& p, const Geometry& q, long u, const long u_end,
                                            const int G, const bool own, unsigned char* xs0, unsigned char* xs1,
-                                           unsigned char* xs2, unsigned char* wsm, int* steptab) {
+                                           unsigned char* xs2, unsigned char* wsm, int* steptab,
+                                           const int team_tm = -1) {
     using T = Tile<WAVES_M, WAVES_N, WM, WN>;
     constexpr bool PLANES = is_planes(GMODE);
     using LD = std::conditional_t<PLANES, PlaneLoader<T, KIND, GMODE, LISTED>, Loader<T, KIND, GMODE, LISTED>>;
     constexpr bool listed = LISTED;
     const int n_eff = q.n_eff, kc = q.kc, KS = q.KS, KT = q.KT, m_eff = q.m_eff;
-    const int tiles_m = q.tiles_m, tiles_n = q.tiles_n, tiles = q.tiles;
+    // team_tm >= 0: this workgroup computes row tile team_tm only and the units are (column tile,
+    // contraction step) pairs; the workgroups of a team walk the same units side by side
+    const int tiles_m = q.tiles_m, tiles_n = q.tiles_n, tiles = team_tm >= 0 ? q.tiles_n : q.tiles;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
@@ -892,6 +895,7 @@ __device__ __forceinline__ void gemm_sweep(const GemmParams& p, const Geometry& 
             if (len > MAX_SEG) len = MAX_SEG;      // (an owned tile's contraction may be longer than a segment)
             tm = tile % tiles_m;
             tn = tile / tiles_m;
+            if (team_tm >= 0) { tm = team_tm; tn = tile; }
         }
         if (len > u_end - u) len = u_end - u;
         const int L = (int)len;
@@ -1075,18 +1079,24 @@ __global__ __launch_bounds__((Tile<WAVES_M, WAVES_N, WM, WN>::THREADS), (Tile<WA
     if (q.units == 0) return;
     const int G = gridDim.x;
     const int b = xcd_contiguous(blockIdx.x, G);
-    const long total = q.units * grp.n;
-    long u = total * b / G;
-    const long u_end = total * (b + 1) / G;
+    // Teams: when the row tiles divide the grid, tiles_m consecutive workgroups (same XCD) form a
+    // team that walks one sequence of (column tile, contraction step) units, each member for its
+    // own row tile: the weight planes of a unit are fetched once for all row tiles, in lockstep.
+    const bool team = grp.p[0].team && q.tiles_m > 1 && G % q.tiles_m == 0;
+    const long units = team ? q.units / q.tiles_m : q.units;        // of one member
+    const int parts = team ? G / q.tiles_m : G, part = team ? b / q.tiles_m : b;
+    const long total = units * grp.n;
+    long u = total * part / parts;
+    const long u_end = total * (part + 1) / parts;
     bool own = false;
     if constexpr (OWN) own = owns_tiles(grp.p[0], q.m_eff, q.n_eff, q.kc);
 #pragma nounroll
-    for (int j = (int)(u / q.units); u < u_end; ++j) {
-        const long base = (long)j * q.units;
-        const long hi = u_end - base < q.units ? u_end - base : q.units;
+    for (int j = (int)(u / units); u < u_end; ++j) {
+        const long base = (long)j * units;
+        const long hi = u_end - base < units ? u_end - base : units;
         gemm_sweep<WAVES_M, WAVES_N, WM, WN, KIND, GMODE, false>(grp.p[j], q, u - base, hi, G, own, xs0, xs1, xs2,
-                                                                 wsm, steptab);
-        u = base + q.units;
+                                                                 wsm, steptab, team ? b % q.tiles_m : -1);
+        u = base + units;
     }
 }
 
