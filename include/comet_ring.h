@@ -377,7 +377,8 @@ int comet_set_tuning(comet_ctx* ctx, int key, int value);
  * creates up to max_launches HIP event pairs; while timing is on, every share
  * call (every n-th with COMET_TUNE_TIMING_STRIDE = n) attaches one pair to the
  * dispatch of its GEMM kernel on the context's stream: the pair reads the
- * kernel's own start and end.  comet_timing_end waits for the last recorded event, returns the summed
+ * kernel's own start and end (do not keep timing on while the stream is being
+ * captured into a HIP graph).  comet_timing_end waits for the last recorded event, returns the summed
  * kernel time and the number of launches timed, and destroys the events. */
 int comet_timing_begin(comet_ctx* ctx, int max_launches);
 int comet_timing_end(comet_ctx* ctx, double* total_ms, int* launches);
