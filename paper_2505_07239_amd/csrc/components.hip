@@ -67,7 +67,7 @@ __global__ __launch_bounds__(CT) void components_kernel(const uint8_t* __restric
     __shared__ int lb[MAX_NB];       // label of a block, NONE when no token uses it
     __shared__ int keys[MAX_NB];
     __shared__ int cnum[MAX_TOK];    // component number of the component whose smallest token is t
-    __shared__ int changed, n_comp;
+    __shared__ int changed;
     const int wpr = (nb + 31) >> 5;
 
     // edges -> bit words; the 32 flags of a word are requested together (independent loads),
@@ -148,7 +148,6 @@ __global__ __launch_bounds__(CT) void components_kernel(const uint8_t* __restric
     if (threadIdx.x == 0) {
         int c = 0;
         for (int t = 0; t < n_tok; ++t) cnum[t] = (lr[t] == t) ? c++ : -1;
-        n_comp = c;
         *n_comp_dev = c;
     }
     __syncthreads();
