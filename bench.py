@@ -371,6 +371,28 @@ def cpu_baseline(layer, budget_s=20.0):
             "matches_gpu": bool(ok)}
 
 
+def graph_replay_ms(layer, steps):
+    """One step captured in a HIP graph (every call only enqueues kernels) and replayed: the time
+    per step without the host-side launch cost of its thirty-odd kernels."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):               # warm-up outside the capture (workspace allocation)
+        layer.step_grouped()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        layer.step_grouped()
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
 def config_entry(ctx, name, probes, planes, skinny_forced, steps=10, warmup=3, layer=None, timing=None,
                  check=None):
     """One configuration: short timed run, roofline, exchanged bytes, oracle check of a row block."""
@@ -413,6 +435,9 @@ def config_entry(ctx, name, probes, planes, skinny_forced, steps=10, warmup=3, l
         "oracle_check": check["sample"],
         "matches_gpu": check["matches_gpu"],
     }
+    if cfg.cid <= 2:
+        # launch-bound configurations: the same step replayed from a HIP graph
+        entry["ms_per_step_graph_replay"] = graph_replay_ms(layer, 4 * steps)
     if own:
         del layer
         torch.cuda.empty_cache()
