@@ -72,3 +72,30 @@ def test_product_path_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text, "%s mentions the oracle" % f
+
+
+def test_share_group_member_struct_matches_the_header():
+    """The ctypes image of comet_share_operands: field order, types and size as the header
+    declares them (two int32, then six pointers), and the group limit."""
+    from paper_2505_07239_amd import binding
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    body = re.search(r"typedef struct comet_share_operands \{(.*?)\} comet_share_operands;", text, flags=re.S).group(1)
+    fields = [re.sub(r"\s+", " ", f.strip()) for f in body.split(";") if f.strip()]
+    names = [f.split()[-1].lstrip("*") for f in fields]
+    assert names == [n for n, _ in binding.ShareOperands._fields_]
+    assert [("*" in f) for f in fields] == [False, False] + [True] * 6
+    assert ctypes.sizeof(binding.ShareOperands) == 2 * 4 + 6 * ctypes.sizeof(ctypes.c_void_p)
+    limit = int(re.search(r"COMET_SHARE_GROUP_MAX = (\d+)", text).group(1))
+    assert limit == binding.SHARE_GROUP_MAX
+
+
+def test_host_side_checks_of_the_group_call_need_no_gpu(lib):
+    """Argument errors of comet_share_group are found before anything touches a device."""
+    from paper_2505_07239_amd import binding
+    lib.comet_share_group.restype = ctypes.c_int
+    lib.comet_share_group.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.POINTER(binding.ShareOperands),
+                                      ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p,
+                                      ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t]
+    arr = (binding.ShareOperands * 1)()
+    # a null context is refused first
+    assert lib.comet_share_group(None, 1, 1, arr, 8, 8, 8, 8, None, None, 1, 0, None, 0) != 0
