@@ -437,7 +437,11 @@ def config_entry(ctx, name, probes, planes, skinny_forced, steps=10, warmup=3, l
     }
     if cfg.cid <= 2:
         # launch-bound configurations: the same step replayed from a HIP graph
-        entry["ms_per_step_graph_replay"] = graph_replay_ms(layer, 4 * steps)
+        try:
+            entry["ms_per_step_graph_replay"] = graph_replay_ms(layer, 4 * steps)
+        except Exception as exc:          # an extra figure: never at the cost of the whole line
+            log("graph replay of %s failed: %s" % (name, exc))
+            entry["ms_per_step_graph_replay"] = None
     if own:
         del layer
         torch.cuda.empty_cache()
