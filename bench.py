@@ -61,6 +61,14 @@ GEMM_TRAFFIC = {
 }
 
 
+PAPER_CONTEXT = {
+    3: "Llama2-7B (ReLU) local computation, dense -> sparse: gate 66.4 -> 21.6 s, up 66.3 -> 19.9 s, down 64.5 -> "
+       "8.9 s; communication 345 -> 36.1 GB (gate, up), 346 -> 35.4 GB (down) (Sec. 7, Performance Breakdown, per-layer table)",
+    5: "SOMM / SIMM communication against a dense GEMM: 1.41x to 95.3x over the sparsity sweep, 8.1x at 90 % "
+       "sparsity; computation is about 15 % of the matmul time on the paper's platform (Sec. 7, Component-wise Analysis)",
+}
+
+
 def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
@@ -434,6 +442,12 @@ def config_entry(ctx, name, probes, planes, skinny_forced, steps=10, warmup=3, l
         "exchange_reduction": dense / sent,
         "oracle_check": check["sample"],
         "matches_gpu": check["matches_gpu"],
+        # the CPU oracle on the sampled rows, same run, same box (a reported baseline, not a target)
+        "cpu_oracle_gops": check["value"], "cpu_oracle_cores": check["cores"],
+        "cpu_oracle_gops_1core": check.get("value_1core"),
+        # what the paper reports for the corresponding layer (its own platform: two servers with
+        # A100 + Xeon 8458P, 5 Gbps links, CrypTen; whole-inference sums) -- context only
+        "paper_context": PAPER_CONTEXT.get(cfg.cid),
     }
     if cfg.cid <= 2:
         # launch-bound configurations: the same step replayed from a HIP graph
