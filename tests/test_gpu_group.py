@@ -255,3 +255,42 @@ def test_share_group_argument_checks(ctx):
     assert call(comet.OP_SOMM, 2, bad, 2 * each) == -1
     assert call(comet.OP_SOMM, 1, arr, 2 * each) == 0               # a group of one is a single call
     torch.cuda.synchronize()
+
+
+def _draw(case):
+    r = rng.uniform_u64(4343, case, 12)
+    pick = lambda i, lo, hi: lo + int(r[i] % np.uint64(hi - lo + 1))
+    kind = "somm" if r[0] & np.uint64(1) else "simm"
+    m = [65, 100, 128, 129, 200, 256, 300, 385][pick(1, 0, 7)]
+    bs = [16, 32, 48, 64][pick(2, 0, 3)]
+    nb = pick(3, 2, max(2, 640 // bs))
+    keep = pick(4, 1, nb)
+    other = pick(5, 1, 300)                       # the axis that is not indexed
+    members = pick(6, 1, 5)
+    grid = [0, 1, 2, 3, 4, 6, 8, 16][pick(7, 0, 7)]
+    spare = pick(8, 0, 2)
+    mode = 1 if r[9] & np.uint64(1) else 3        # with and without teams over the row tiles
+    return kind, m, bs, nb, keep, other, members, grid, spare, mode
+
+
+@pytest.mark.parametrize("case", range(40))
+def test_share_group_sweep(ctx, case):
+    """Seeded sweep of grouped launches over shapes, block sizes, member counts, grids and both
+    ways of sharing out the row tiles, each member compared element by element with the oracle."""
+    import paper_2505_07239_amd as comet
+    from workloads import masks
+    kind, m, bs, nb, keep, other, members, grid, spare, mode = _draw(case)
+    mk = masks.uniform_block_mask(6000 + case, 1, nb, keep / nb)
+    kept = tuple(int(v) for v in co.compact_mask(mk[None, :]))
+    spare = min(spare, nb - len(kept))
+    say("sweep %d: %s m=%d bs=%d nb=%d kept=%d other=%d members=%d grid=%d spare=%d mode=%d"
+        % (case, kind, m, bs, nb, len(kept), other, members, grid, spare, mode))
+    dims = (m, other, nb * bs) if kind == "somm" else (m, nb * bs, other)
+    parties = tuple((case + j) & 1 for j in range(members))
+    ctx.set_tuning(comet.TUNE_GROUP, mode)
+    ctx.set_tuning(comet.TUNE_GEMM_GRID, grid)
+    try:
+        _run_group(ctx, kind, *dims, bs, kept, spare, parties, seed=7000 + 20 * case)
+    finally:
+        ctx.set_tuning(comet.TUNE_GROUP, 0)
+        ctx.set_tuning(comet.TUNE_GEMM_GRID, 0)
