@@ -57,14 +57,19 @@ def draw(case):
     return kind, m, bs, nb, keep, other, party, compact, spare, on_device
 
 
+@pytest.mark.parametrize("fmt", ["words", "planes"])
 @pytest.mark.parametrize("case", range(48))
-def test_share_sweep(ctx, case):
+def test_share_sweep(ctx, case, fmt):
+    """``fmt``: the weight-side operands F and B_i as words or as digit planes."""
     kind, m, bs, nb, keep, other, party, compact, spare, on_device = draw(case)
+    if fmt == "planes" and kind == "simm" and bs % 16:
+        compact = True        # planes of a full-size B_i are gathered in units of sixteen rows
+    wt = (lambda a: ctx.open_weight_planes(up(a))) if fmt == "planes" else up
     if not on_device:
         spare = 0                                  # without a device count the capacity is the count
     full = nb * bs
-    say("case %d: %s m=%d bs=%d nb=%d keep=%d other=%d party=%d compact=%s spare=%d device_count=%s"
-        % (case, kind, m, bs, nb, keep, other, party, compact, spare, on_device))
+    say("case %d (%s): %s m=%d bs=%d nb=%d keep=%d other=%d party=%d compact=%s spare=%d device_count=%s"
+        % (case, fmt, kind, m, bs, nb, keep, other, party, compact, spare, on_device))
     seed = 5000 + case
     mk = masks.uniform_block_mask(seed, 1, nb, keep / nb)
     idx_np = co.compact_mask(mk[None, :])
@@ -94,8 +99,8 @@ def test_share_sweep(ctx, case):
         c = u64(seed, 6, m, n_act)
         b_sel = co.index_cols(b, idx_np, bs)
         want = co.beaver_share(party, e, f, a, b_sel, c)
-        z = ctx.somm_share(party, bs, gi, n_dev, cap, up(e), up(pad_cols(f)), up(a),
-                           up(pad_cols(b_sel)) if compact else up(b), up(pad_cols(c)), b_full=not compact)
+        z = ctx.somm_share(party, bs, gi, n_dev, cap, up(e), wt(pad_cols(f)), up(a),
+                           wt(pad_cols(b_sel)) if compact else wt(b), up(pad_cols(c)), b_full=not compact)
         torch.cuda.synchronize()
         assert np.array_equal(down(z)[:, :n_act], want)
     else:
@@ -105,9 +110,9 @@ def test_share_sweep(ctx, case):
         c = u64(seed, 6, m, n)
         a_sel, b_sel = co.index_cols(a, idx_np, bs), co.index_rows(b, idx_np, bs)
         want = co.beaver_share(party, e, f, a_sel, b_sel, c)
-        z = ctx.simm_share(party, bs, gi, n_dev, cap, up(pad_cols(e)), up(pad_rows(f)),
+        z = ctx.simm_share(party, bs, gi, n_dev, cap, up(pad_cols(e)), wt(pad_rows(f)),
                            up(pad_cols(a_sel)) if compact else up(a),
-                           up(pad_rows(b_sel)) if compact else up(b), up(c),
+                           wt(pad_rows(b_sel)) if compact else wt(b), up(c),
                            a_full=not compact, b_full=not compact)
         torch.cuda.synchronize()
         assert np.array_equal(down(z), want)
