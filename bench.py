@@ -515,6 +515,50 @@ def general_forms(ctx, timed):
     return out
 
 
+def mha_layers(ctx, timed):
+    """The MHA-shaped workload (LLaMA-2-7B attention, block = one head of 128): sparse QKV layer
+    with merged cache-refill rows (Protocol 2 on the result blocks of the head-granular mask, 8
+    current tokens + 56 refill rows) and sparse output layer (Protocol 3 with per-token head
+    sets), against the same calls on the union of all masks."""
+    import numpy as np
+    import torch
+    from workloads import configs, rng
+    cfg = configs.mha_config()
+    qkv_mask, out_mask = configs.mha_head_masks(cfg)
+    d, h, bs = cfg.d_model, cfg.n_heads, cfg.head_dim
+    dev = torch.device("cuda:0")
+    words = lambda st, *shape: rng.uniform_u64_torch(rng.BASE_SEED, 9600 + st, int(np.prod(shape)), dev).view(*shape)
+    tm = torch.from_numpy(qkv_mask).to(dev)
+    comp = ctx.components(tm)
+    torch.cuda.synchronize()
+    n_row, n_blk, n_comp = (int(comp[q].item()) for q in ("n_row", "n_blk", "n_comp"))
+    n_act = n_blk * bs
+    out = {"mha_qkv_rows": n_row, "mha_qkv_head_blocks": n_blk, "mha_qkv_components": n_comp}
+    e, a, f = words(1, n_row, d), words(2, n_row, d), words(3, d, n_act)
+    b, c = words(4, d, 3 * h * bs), words(5, n_row, n_act)
+    z = torch.empty_like(c)
+    out["mha_components_us"] = timed(lambda: ctx.components(tm), reps=20) * 1e6
+    out["mha_qkv_result_blocks_us"] = timed(
+        lambda: ctx.somm_share_blocks(1, bs, comp["blk_idx"], comp["blk_comp"], comp["n_blk"], n_blk, comp["row_comp"],
+                                      comp["n_row"], e, f, a, b, c, out=z), reps=10) * 1e6
+    out["mha_qkv_union_of_masks_us"] = timed(
+        lambda: ctx.somm_share(1, bs, comp["blk_idx"], comp["n_blk"], n_blk, e, f, a, b, c, out=z), reps=10) * 1e6
+    om = torch.from_numpy(out_mask).to(dev)
+    idx, n_dev = ctx.compact_mask(om)
+    torch.cuda.synchronize()
+    t = int(n_dev.item())
+    m, kc = cfg.tokens, t * bs
+    e2, a2, f2 = words(6, m, kc), words(7, m, h * bs), words(8, kc, d)
+    b2, c2 = words(9, h * bs, d), words(10, m, d)
+    z2 = torch.empty_like(c2)
+    out["mha_output_heads_in_union"] = t
+    out["mha_output_head_sets_us"] = timed(
+        lambda: ctx.simm_share_masked(1, bs, idx, n_dev, t, om, e2, f2, a2, b2, c2, out=z2), reps=10) * 1e6
+    out["mha_output_union_of_masks_us"] = timed(
+        lambda: ctx.simm_share(1, bs, idx, n_dev, t, e2, f2, a2, b2, c2, out=z2), reps=10) * 1e6
+    return out
+
+
 def weight_side_masking(ctx, timed_rotating):
     """Indexed masking of the weight side of the LLaMA-7B gate projection (4096 x 11008 words,
     52 of 344 blocks of 32): row-major weights (kept neurons are 256-byte segments of every row)
@@ -635,6 +679,7 @@ def micro(ctx, layer):
     t = timed(lambda: ctx.compact_mask(layer.mask, layer.idx, layer.n_dev), reps=50)
     out["compact_layer_mask_us"] = t * 1e6
     out.update(general_forms(ctx, timed))
+    out.update(mha_layers(ctx, timed))
     out.update(glue_steps(ctx, timed))
     out.update(weight_side_masking(ctx, timed_rotating))
     macs = ctx.probe_mfma_i8(1024, 2000)
