@@ -47,17 +47,17 @@ ALL_CONFIGS = ["c1", "c2", "c3", "c4", "c5_d100", "c5_d050", "c5_d025", "c5_d010
 # the copy probe of known size in the same run.  The summaries, with the commands, are the
 # files named here under profiles/.  None until measured for that workload and operand format.
 GEMM_TRAFFIC = {
-    ("c2", "planes", "single"): (13392299, "profiles/bench_c2_kernel_trace_and_hbm_counters.md"),
-    ("c3", "planes", "grouped"): (608718505, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
-    ("c3", "planes", "single"): (197387685, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
-    ("c4", "words", "single"): (987123422, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
-    ("c5_d100", "planes", "single"): (1549275257, "profiles/bench_c5_d100_kernel_trace_and_hbm_counters.md"),
-    ("c5_d050", "planes", "single"): (792771963, "profiles/bench_c5_d050_kernel_trace_and_hbm_counters.md"),
-    ("c5_d025", "planes", "single"): (396955833, "profiles/bench_c5_d025_kernel_trace_and_hbm_counters.md"),
-    ("c5_d010", "planes", "grouped"): (358220381, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
-    ("c5_d010", "planes", "single"): (178866724, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
-    ("c5_d005", "planes", "grouped"): (215621648, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
-    ("c5_d005", "planes", "single"): (107567099, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
+    ("c2", "planes", "single"): (13560827, "profiles/bench_c2_kernel_trace_and_hbm_counters.md"),
+    ("c3", "planes", "grouped"): (606583491, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
+    ("c3", "planes", "single"): (196971350, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
+    ("c4", "words", "single"): (982336472, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
+    ("c5_d100", "planes", "single"): (1541727619, "profiles/bench_c5_d100_kernel_trace_and_hbm_counters.md"),
+    ("c5_d050", "planes", "single"): (789180325, "profiles/bench_c5_d050_kernel_trace_and_hbm_counters.md"),
+    ("c5_d025", "planes", "single"): (395182306, "profiles/bench_c5_d025_kernel_trace_and_hbm_counters.md"),
+    ("c5_d010", "planes", "grouped"): (357237357, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
+    ("c5_d010", "planes", "single"): (178384918, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
+    ("c5_d005", "planes", "grouped"): (215484009, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
+    ("c5_d005", "planes", "single"): (107508231, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
 }
 
 
