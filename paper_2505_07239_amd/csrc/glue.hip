@@ -17,21 +17,23 @@ constexpr int ROW_WORDS = 16384;      // longest row staged in LDS (128 KB)
 
 typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 
-// Permutation of whole rows: dst(j, :) = src(perm[j], :) +/- mask(j, :).  grid.x = output row,
-// grid.y = chunks of columns; rows are contiguous, so every access is a full-width vector.
+// Permutation of whole rows: dst(j, :) = src(perm[j], :) +/- mask(j, :).  One workgroup per
+// (output row, chunk of columns); rows are contiguous, so every access is a full-width vector.
 template <int VEC, bool SUB>
 __global__ __launch_bounds__(GT) void permute_rows_kernel(const u64* __restrict__ src,
                                                           const int* __restrict__ perm,
                                                           const u64* __restrict__ mask,
-                                                          u64* __restrict__ dst, int rows, int cols) {
-    const int j = blockIdx.x;
+                                                          u64* __restrict__ dst, int rows, int cols, int gy) {
+    // workgroups are numbered row by row (the pieces of a row are dispatched together)
+    const int j = (int)(blockIdx.x / (unsigned)gy);
+    const int piece = (int)(blockIdx.x % (unsigned)gy);
     int from = perm[j];
     from = (from < 0 || from >= rows) ? 0 : from;             // a bad entry never leaves the operand
     const u64* s = src + (size_t)from * cols;
     const u64* mk = mask + (size_t)j * cols;
     u64* d = dst + (size_t)j * cols;
     const int nvec = cols / VEC;
-    for (int c = blockIdx.y * GT + threadIdx.x; c < nvec; c += gridDim.y * GT) {
+    for (int c = piece * GT + threadIdx.x; c < nvec; c += gy * GT) {
         if (VEC == 2) {
             const u64x2 v = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(s) + c);
             const u64x2 q = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(mk) + c);
@@ -101,6 +103,7 @@ __global__ __launch_bounds__(GT) void fill_zero_kernel(u64* __restrict__ p, size
 }
 
 // full(r, blk_idx[t] * bs + j) = compact(r, t * bs + j); grid.x = row, grid.y = column chunks
+// (numbering the workgroups row by row, which helps the gathers, measured 3 % slower here)
 template <int VEC>
 __global__ __launch_bounds__(GT) void scatter_cols_kernel(const u64* __restrict__ compact, int ld, int bs,
                                                           const int* __restrict__ blk_idx,
@@ -172,11 +175,11 @@ int comet_permute_mask(comet_ctx* ctx, const uint64_t* src, const int32_t* perm,
         unsigned gy = (unsigned)(((vec ? cols / 2 : cols) + GT * 4 - 1) / (GT * 4));
         if (gy < 1) gy = 1;
         if (gy > 64) gy = 64;
-        const dim3 grid((unsigned)rows, gy);
-        if (vec && sign > 0) hipLaunchKernelGGL((permute_rows_kernel<2, false>), grid, dim3(GT), 0, ctx->stream, s, perm, mk, d, (int)rows, (int)cols);
-        else if (vec) hipLaunchKernelGGL((permute_rows_kernel<2, true>), grid, dim3(GT), 0, ctx->stream, s, perm, mk, d, (int)rows, (int)cols);
-        else if (sign > 0) hipLaunchKernelGGL((permute_rows_kernel<1, false>), grid, dim3(GT), 0, ctx->stream, s, perm, mk, d, (int)rows, (int)cols);
-        else hipLaunchKernelGGL((permute_rows_kernel<1, true>), grid, dim3(GT), 0, ctx->stream, s, perm, mk, d, (int)rows, (int)cols);
+        const dim3 grid((unsigned)(rows * gy));               // rows < 2^24, gy <= 64
+        if (vec && sign > 0) hipLaunchKernelGGL((permute_rows_kernel<2, false>), grid, dim3(GT), 0, ctx->stream, s, perm, mk, d, (int)rows, (int)cols, (int)gy);
+        else if (vec) hipLaunchKernelGGL((permute_rows_kernel<2, true>), grid, dim3(GT), 0, ctx->stream, s, perm, mk, d, (int)rows, (int)cols, (int)gy);
+        else if (sign > 0) hipLaunchKernelGGL((permute_rows_kernel<1, false>), grid, dim3(GT), 0, ctx->stream, s, perm, mk, d, (int)rows, (int)cols, (int)gy);
+        else hipLaunchKernelGGL((permute_rows_kernel<1, true>), grid, dim3(GT), 0, ctx->stream, s, perm, mk, d, (int)rows, (int)cols, (int)gy);
     } else if (cols <= ROW_WORDS) {
         unsigned g = (unsigned)(rows < ctx->num_cu ? rows : ctx->num_cu);
         if (sign > 0) hipLaunchKernelGGL(permute_cols_lds_kernel<false>, dim3(g), dim3(PT), 0, ctx->stream, s, perm, mk, d, (int)rows, (int)cols);
