@@ -48,16 +48,16 @@ ALL_CONFIGS = ["c1", "c2", "c3", "c4", "c5_d100", "c5_d050", "c5_d025", "c5_d010
 # files named here under profiles/.  None until measured for that workload and operand format.
 GEMM_TRAFFIC = {
     ("c2", "planes", "single"): (13560827, "profiles/bench_c2_kernel_trace_and_hbm_counters.md"),
-    ("c3", "planes", "grouped"): (606583491, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
-    ("c3", "planes", "single"): (196971350, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
-    ("c4", "words", "single"): (982336472, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
-    ("c5_d100", "planes", "single"): (1541727619, "profiles/bench_c5_d100_kernel_trace_and_hbm_counters.md"),
-    ("c5_d050", "planes", "single"): (789180325, "profiles/bench_c5_d050_kernel_trace_and_hbm_counters.md"),
-    ("c5_d025", "planes", "single"): (395182306, "profiles/bench_c5_d025_kernel_trace_and_hbm_counters.md"),
-    ("c5_d010", "planes", "grouped"): (357237357, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
+    ("c3", "planes", "grouped"): (608774720, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
+    ("c3", "planes", "single"): (196775094, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
+    ("c4", "words", "single"): (982336438, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
+    ("c5_d100", "planes", "single"): (1541727902, "profiles/bench_c5_d100_kernel_trace_and_hbm_counters.md"),
+    ("c5_d050", "planes", "single"): (789179683, "profiles/bench_c5_d050_kernel_trace_and_hbm_counters.md"),
+    ("c5_d025", "planes", "single"): (395182257, "profiles/bench_c5_d025_kernel_trace_and_hbm_counters.md"),
+    ("c5_d010", "planes", "grouped"): (357237377, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
     ("c5_d010", "planes", "single"): (178384918, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
-    ("c5_d005", "planes", "grouped"): (215484009, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
-    ("c5_d005", "planes", "single"): (107508231, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
+    ("c5_d005", "planes", "grouped"): (215483809, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
+    ("c5_d005", "planes", "single"): (107508130, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
 }
 
 
