@@ -81,9 +81,10 @@ __global__ __launch_bounds__(GC_THREADS) void gather_cols_kernel(
     }
 }
 
-// Indexed masking along rows: one grid column per kept matrix row.
+// Indexed masking along rows: the workgroups of a kept matrix row follow each other.
+constexpr int GR_THREADS = 128;
 template <int VEC>
-__global__ __launch_bounds__(EW_THREADS) void gather_rows_kernel(
+__global__ __launch_bounds__(GR_THREADS) void gather_rows_kernel(
     const u64* __restrict__ w, const u64* __restrict__ b, u64* __restrict__ g, int rows, int cols,
     int bs, const int* __restrict__ blk_idx, const int* __restrict__ n_blk_dev, int n_blk_cap, int gy) {
     const int n_blk = n_blk_dev ? min(*n_blk_dev, n_blk_cap) : n_blk_cap;
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(EW_THREADS) void gather_rows_kernel(
     if (start < 0 || start + bs > rows) return;             // id outside the matrix: skip, never fault
     const size_t src = ((size_t)start + (r - blk * bs)) * (size_t)cols;
     const size_t dst = (size_t)r * cols;
-    for (int c = (piece * EW_THREADS + threadIdx.x) * VEC; c < cols; c += gy * EW_THREADS * VEC) {
+    for (int c = (piece * GR_THREADS + threadIdx.x) * VEC; c < cols; c += gy * GR_THREADS * VEC) {
         if (VEC == 2) {
             const u64x2 x = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(w + src + c));
             const u64x2 y = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(b + src + c));
@@ -190,17 +191,17 @@ int comet_mask_share_gather(comet_ctx* ctx, const uint64_t* w_i, const uint64_t*
                                blk_idx, n_blk_dev, n_blk_cap, (int)gy);
     } else {
         const bool vec = (cols % 2 == 0);
-        const int per = EW_THREADS * (vec ? 2 : 1) * 2;
+        const int per = GR_THREADS * (vec ? 2 : 1) * 2;
         long gy = (cols + per - 1) / per;
         const long gy_max = (1l << 31) / ld - 1;           // rows x pieces stays a valid one-dimensional grid
         if (gy > gy_max) gy = gy_max < 1 ? 1 : gy_max;
         const dim3 grid((unsigned)((long)ld * gy));
         if (vec)
-            hipLaunchKernelGGL((gather_rows_kernel<2>), grid, dim3(EW_THREADS), 0, ctx->stream,
+            hipLaunchKernelGGL((gather_rows_kernel<2>), grid, dim3(GR_THREADS), 0, ctx->stream,
                                (const u64*)w_i, (const u64*)b_i, (u64*)g_i, (int)rows, (int)cols, bs,
                                blk_idx, n_blk_dev, n_blk_cap, (int)gy);
         else
-            hipLaunchKernelGGL((gather_rows_kernel<1>), grid, dim3(EW_THREADS), 0, ctx->stream,
+            hipLaunchKernelGGL((gather_rows_kernel<1>), grid, dim3(GR_THREADS), 0, ctx->stream,
                                (const u64*)w_i, (const u64*)b_i, (u64*)g_i, (int)rows, (int)cols, bs,
                                blk_idx, n_blk_dev, n_blk_cap, (int)gy);
     }

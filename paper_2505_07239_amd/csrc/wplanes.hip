@@ -16,7 +16,7 @@ namespace {
 
 using namespace comet_gemm;
 
-constexpr int WT = 256;
+constexpr int WT = 128;
 typedef u64 u64x2 __attribute__((ext_vector_type(2)));
 
 // One thread packs sixteen contraction rows of one column: its sixteen loads per operand are
