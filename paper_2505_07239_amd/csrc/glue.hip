@@ -94,11 +94,20 @@ __global__ __launch_bounds__(GT) void permute_cols_direct_kernel(const u64* __re
     }
 }
 
+// (the streaming kernels below give every workgroup one contiguous chunk of GT * SU 16-byte
+// vectors, in dispatch order: the chip walks the buffers front to back)
+constexpr int SU = 4;
 __global__ __launch_bounds__(GT) void fill_zero_kernel(u64* __restrict__ p, size_t n) {
     const size_t nvec = n >> 1;
     u64x2* pv = reinterpret_cast<u64x2*>(p);
-    for (size_t i = (size_t)blockIdx.x * GT + threadIdx.x; i < nvec; i += (size_t)gridDim.x * GT)
-        __builtin_nontemporal_store(u64x2{0, 0}, pv + i);
+    const size_t chunk = (size_t)GT * SU;
+    for (size_t base = (size_t)blockIdx.x * chunk; base < nvec; base += (size_t)gridDim.x * chunk) {
+#pragma unroll
+        for (int j = 0; j < SU; ++j) {
+            const size_t i = base + (size_t)j * GT + threadIdx.x;
+            if (i < nvec) __builtin_nontemporal_store(u64x2{0, 0}, pv + i);
+        }
+    }
     if ((n & 1) && blockIdx.x == 0 && threadIdx.x == 0) p[n - 1] = 0;
 }
 
@@ -134,17 +143,28 @@ __global__ __launch_bounds__(GT) void truncate_kernel(int party, const u64* __re
         return party == 0 ? (u64)((long long)v >> f) : (u64)0 - (u64)((long long)((u64)0 - v) >> f);
     };
     const size_t nvec = n >> 1;
-    for (size_t i = (size_t)blockIdx.x * GT + threadIdx.x; i < nvec; i += (size_t)gridDim.x * GT) {
-        const u64x2 v = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(z) + i);
-        __builtin_nontemporal_store(u64x2{one(v.x), one(v.y)}, reinterpret_cast<u64x2*>(out) + i);
+    const size_t chunk = (size_t)GT * SU;
+    for (size_t base = (size_t)blockIdx.x * chunk; base < nvec; base += (size_t)gridDim.x * chunk) {
+        u64x2 v[SU];
+#pragma unroll
+        for (int j = 0; j < SU; ++j) {
+            const size_t i = base + (size_t)j * GT + threadIdx.x;
+            if (i < nvec) v[j] = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(z) + i);
+        }
+#pragma unroll
+        for (int j = 0; j < SU; ++j) {
+            const size_t i = base + (size_t)j * GT + threadIdx.x;
+            if (i < nvec) __builtin_nontemporal_store(u64x2{one(v[j].x), one(v[j].y)}, reinterpret_cast<u64x2*>(out) + i);
+        }
     }
     if ((n & 1) && blockIdx.x == 0 && threadIdx.x == 0) out[n - 1] = one(z[n - 1]);
 }
 
-inline unsigned stream_grid(const comet_ctx* ctx, size_t work_items) {
-    size_t g = (work_items + GT - 1) / GT;
-    const size_t cap = (size_t)ctx->num_cu * 16;
-    if (g > cap) g = cap;
+// workgroups for n_elems words: one chunk each (the kernels loop beyond 2^30 chunks)
+inline unsigned stream_grid(size_t n_elems) {
+    const size_t chunk = (size_t)GT * SU * 2;
+    size_t g = (n_elems + chunk - 1) / chunk;
+    if (g > ((size_t)1 << 30)) g = (size_t)1 << 30;
     return (unsigned)(g < 1 ? 1 : g);
 }
 
@@ -210,7 +230,7 @@ int comet_scatter_cols(comet_ctx* ctx, const uint64_t* compact, int64_t m, int b
     comet_device_guard guard(ctx);
     if (!guard.ok) return comet_fail(ctx, COMET_EDEVICE, "%s: cannot select device", what);
     const size_t total = (size_t)m * (size_t)n_full;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(stream_grid(ctx, total / 8 + 1)), dim3(GT), 0, ctx->stream,
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(stream_grid(total)), dim3(GT), 0, ctx->stream,
                        (u64*)full, total);
     COMET_LAUNCH_CHECK(ctx, what);
     if (n_blk_cap == 0) return COMET_OK;
@@ -238,7 +258,7 @@ int comet_truncate_share(comet_ctx* ctx, int party, const uint64_t* z, uint64_t*
         return comet_fail(ctx, COMET_EALIGN, "%s: operands must be 16-byte aligned", what);
     comet_device_guard guard(ctx);
     if (!guard.ok) return comet_fail(ctx, COMET_EDEVICE, "%s: cannot select device", what);
-    hipLaunchKernelGGL(truncate_kernel, dim3(stream_grid(ctx, n_elems / 8 + 1)), dim3(GT), 0, ctx->stream,
+    hipLaunchKernelGGL(truncate_kernel, dim3(stream_grid(n_elems)), dim3(GT), 0, ctx->stream,
                        party, (const u64*)z, (u64*)out, n_elems, frac_bits);
     COMET_LAUNCH_CHECK(ctx, what);
     return COMET_OK;
