@@ -83,9 +83,8 @@ int comet_open_weight_planes(comet_ctx* ctx, const uint64_t* g_0, const uint64_t
     if (!guard.ok) return comet_fail(ctx, COMET_EDEVICE, "%s: cannot select device", what);
     const long groups = 2 * ((k + 31) / 32);
     const unsigned gx = (unsigned)((n + WT - 1) / WT);
-    // enough workgroups to fill the chip, at most one per group of sixteen rows
-    long gy = (32l * ctx->num_cu + gx - 1) / gx;
-    if (gy > groups) gy = groups;
+    // one workgroup per (chunk of columns, group of sixteen rows), in dispatch order
+    long gy = groups;
     if (gy > 65535) gy = 65535;
     if (gy < 1) gy = 1;
     hipLaunchKernelGGL(wpack_kernel, dim3(gx, (unsigned)gy), dim3(WT), 0, ctx->stream, (const u64*)g_0,
