@@ -46,7 +46,10 @@ __global__ __launch_bounds__(GT) void permute_rows_kernel(const u64* __restrict_
 
 // Permutation inside rows: dst(r, j) = src(r, perm[j]) +/- mask(r, j).  A workgroup stages a
 // whole source row in LDS with coalesced loads and gathers from there, so that HBM sees each
-// word once, in order; rows are dealt round-robin to the workgroups.
+// word once, in order; rows are dealt round-robin to the workgroups.  A row fills most of a
+// compute unit's LDS, so one workgroup is resident per unit: to keep loads in flight during the
+// gather, the next row is fetched into registers before the current one is gathered.
+constexpr int ROW_VECS = ROW_WORDS / 2 / PT;                  // 16-byte vectors of a row per thread
 template <bool SUB>
 __global__ __launch_bounds__(PT) void permute_cols_lds_kernel(const u64* __restrict__ src,
                                                               const int* __restrict__ perm,
@@ -54,23 +57,49 @@ __global__ __launch_bounds__(PT) void permute_cols_lds_kernel(const u64* __restr
                                                               u64* __restrict__ dst, int rows, int cols) {
     __shared__ __align__(16) u64 row[ROW_WORDS];
     const bool vec = (cols & 1) == 0;
+    const int nvec = cols / 2;
+    u64x2 nxt[ROW_VECS];
+    auto fetch = [&](int r) {
+        const u64x2* s = reinterpret_cast<const u64x2*>(src + (size_t)r * cols);
+#pragma unroll
+        for (int i = 0; i < ROW_VECS; ++i) {
+            const int c = i * PT + threadIdx.x;
+            if (c < nvec) nxt[i] = __builtin_nontemporal_load(s + c);
+        }
+    };
+    if (vec && (int)blockIdx.x < rows) fetch(blockIdx.x);
     for (int r = blockIdx.x; r < rows; r += gridDim.x) {
-        const u64* s = src + (size_t)r * cols;
         if (vec) {
-            for (int c = threadIdx.x; c < cols / 2; c += PT)
-                reinterpret_cast<u64x2*>(row)[c] = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(s) + c);
+#pragma unroll
+            for (int i = 0; i < ROW_VECS; ++i) {
+                const int c = i * PT + threadIdx.x;
+                if (c < nvec) reinterpret_cast<u64x2*>(row)[c] = nxt[i];
+            }
         } else {
+            const u64* s = src + (size_t)r * cols;
             for (int c = threadIdx.x; c < cols; c += PT) row[c] = s[c];
         }
         __syncthreads();
+        if (vec && r + (int)gridDim.x < rows) fetch(r + gridDim.x);
         const u64* mk = mask + (size_t)r * cols;
         u64* d = dst + (size_t)r * cols;
-        for (int c = threadIdx.x; c < cols; c += PT) {
-            int from = perm[c];
-            from = (from < 0 || from >= cols) ? 0 : from;
-            const u64 v = row[from];
-            const u64 q = mk[c];
-            d[c] = SUB ? v - q : v + q;
+        if (vec) {
+            for (int c = threadIdx.x; c < nvec; c += PT) {
+                int f0 = perm[2 * c], f1 = perm[2 * c + 1];
+                f0 = (f0 < 0 || f0 >= cols) ? 0 : f0;
+                f1 = (f1 < 0 || f1 >= cols) ? 0 : f1;
+                const u64x2 v = {row[f0], row[f1]};
+                const u64x2 q = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(mk) + c);
+                __builtin_nontemporal_store(SUB ? v - q : v + q, reinterpret_cast<u64x2*>(d) + c);
+            }
+        } else {
+            for (int c = threadIdx.x; c < cols; c += PT) {
+                int from = perm[c];
+                from = (from < 0 || from >= cols) ? 0 : from;
+                const u64 v = row[from];
+                const u64 q = mk[c];
+                d[c] = SUB ? v - q : v + q;
+            }
         }
         __syncthreads();
     }
