@@ -676,6 +676,17 @@ def micro(ctx, layer):
     out["compact_stress_GBs"] = (flags + 4.0 * kept) / t / 1e9
     out["compact_stress_kept"] = kept
     del m, idx
+    # the same number of flags as a batch of per-token masks (65536 tokens x 4096 blocks, tokens
+    # agree on most of their blocks): the OR over the tokens is a read-only stream
+    tall = (masks.stress_mask_device(8, flags, torch.device("cuda:0"), 0.5).view(65536, 4096)
+            & masks.stress_mask_device(9, 4096, torch.device("cuda:0"), 0.3).view(1, 4096)).contiguous()
+    idx = torch.empty(4096, dtype=torch.int32, device="cuda")
+    t = timed(lambda: ctx.compact_mask(tall, idx, nd), reps=10)
+    out["compact_token_masks_65536x4096_GBs"] = (flags + 4.0 * int(nd.item())) / t / 1e9
+    # per-token masks of one batch at FFN width (LLaMA-7B: 344 blocks of 32; 512 tokens)
+    t = timed(lambda: ctx.compact_mask(tall.view(-1)[:512 * 344].view(512, 344), idx, nd), reps=50)
+    out["compact_token_masks_512x344_us"] = t * 1e6
+    del tall, idx
     t = timed(lambda: ctx.compact_mask(layer.mask, layer.idx, layer.n_dev), reps=50)
     out["compact_layer_mask_us"] = t * 1e6
     out.update(general_forms(ctx, timed))

@@ -146,7 +146,11 @@ int comet_open_weight_planes(comet_ctx* ctx, const uint64_t* g_0, const uint64_t
  * (any alignment).  The masks of all tokens are OR-ed (one matmul serves the
  * whole batch), then blk_idx[0 .. T) receives the ascending ids of the active
  * blocks and *n_blk_dev = T.  blk_idx must hold nb int32 (4-byte aligned);
- * entries at or beyond T are left untouched.  1 <= n_tok, 0 <= nb < 2^31 - 2^16.
+ * entries at or beyond T are left untouched.  1 <= n_tok, 0 <= nb < 2^31 - 2^16,
+ * n_tok * nb <= 2^40.  ws: comet_workspace_bytes(COMET_OP_COMPACT, n_tok, 0, nb, 0)
+ * bytes of device memory, 256-byte aligned (none for a single row of at most
+ * 4096 flags, nor for up to 128 KB of flags in rows of at most 4096); it depends
+ * on both sizes (COMET_EWORKSPACE when too small).
  * This is the local, communication-free step that Protocol 2 starts with (its
  * graph search degenerates to this when every token keeps the same blocks) and
  * the "find all non-zero columns" step of Protocol 3. */

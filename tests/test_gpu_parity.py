@@ -133,6 +133,53 @@ def test_compact_mask_shapes(ctx, n_tok, nb):
     _check_compact(ctx, np.ascontiguousarray(m.astype(np.uint8)))
 
 
+def _token_masks(seed, n_tok, nb, density=0.3, shared=0.4):
+    """[n_tok, nb] flags: clustered draws per position, restricted to a shared set of columns
+    (tokens of a batch agree on most of their active neurons), any non-zero byte active."""
+    flat = masks.stress_mask(seed, 1, n_tok * nb, density).reshape(n_tok, nb)
+    common = masks.stress_mask(seed, 3, nb, shared)
+    vals = 1 + (rng.uniform_u64(seed, 5, n_tok * nb) % np.uint64(255)).astype(np.uint8).reshape(n_tok, nb)
+    return np.ascontiguousarray((flat & common[None, :]) * vals).astype(np.uint8)
+
+
+@pytest.mark.parametrize("n_tok,nb", [
+    (2, 1), (2, 3), (7, 5), (33, 15), (16, 16), (9, 17), (64, 344), (512, 344), (513, 343), (380, 345),
+    (31, 4095), (32, 4096), (4096, 344), (1000, 1001), (300, 4096), (129, 4097), (40, 13824), (333, 11008),
+    (17, 65535), (9, 65536), (700, 65536), (5, 65537), (3, 200_003), (300, 70_001), (2100, 16400)])
+def test_compact_mask_many_tokens(ctx, n_tok, nb):
+    """Several token rows: one workgroup over the flat mask, the flat pass with merged bitmaps,
+    and (beyond 65536 columns) the token split per column chunk; row lengths of every
+    alignment."""
+    say("compact many tokens n_tok=%d nb=%d" % (n_tok, nb))
+    _check_compact(ctx, _token_masks(41, n_tok, nb))
+
+
+@pytest.mark.parametrize("lead", [1, 4, 15])
+@pytest.mark.parametrize("n_tok,nb", [(50, 344), (700, 344), (90, 4096), (600, 13824), (11, 65537)])
+def test_compact_mask_many_tokens_unaligned_pointer(ctx, n_tok, nb, lead):
+    say("compact many tokens n_tok=%d nb=%d lead=%d" % (n_tok, nb, lead))
+    m = _token_masks(42 + lead, n_tok, nb)
+    # surrounded by set flags that are not part of the mask
+    backing = torch.full((lead + n_tok * nb + 64,), 1, dtype=torch.uint8, device="cuda")
+    backing[lead:lead + n_tok * nb] = torch.from_numpy(m.reshape(-1)).cuda()
+    view = backing[lead:lead + n_tok * nb].view(n_tok, nb)
+    idx, n_dev = ctx.compact_mask(view)
+    torch.cuda.synchronize()
+    want = co.compact_mask(m)
+    assert int(n_dev.item()) == len(want) and np.array_equal(idx[:len(want)].cpu().numpy(), want)
+
+
+def test_compact_mask_many_tokens_corners(ctx):
+    say("compact many tokens corners")
+    for n_tok, nb in ((2, 16), (100, 344), (2000, 344), (50, 5000), (40, 70_000)):
+        _check_compact(ctx, np.zeros((n_tok, nb), np.uint8))
+        _check_compact(ctx, np.full((n_tok, nb), 255, np.uint8))
+        for r, c in ((0, 0), (n_tok - 1, nb - 1), (n_tok - 1, 0), (0, nb - 1), (n_tok // 2, nb // 2)):
+            m = np.zeros((n_tok, nb), np.uint8)
+            m[r, c] = 128
+            _check_compact(ctx, m)
+
+
 def test_compact_mask_degenerate(ctx):
     say("compact degenerate")
     for nb in (7, 5000, 70_000):
