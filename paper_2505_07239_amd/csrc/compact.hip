@@ -150,18 +150,7 @@ __global__ __launch_bounds__(CT) void compact_pack_kernel(const uint8_t* __restr
 #pragma unroll
         for (int j = 0; j < ITEMS; ++j) acc[j] = u32x4{0, 0, 0, 0};
         const uint8_t* src = mask + t0 * nb + base + (long)threadIdx.x * FL;
-        long t = t0;
-        for (; t + 2 <= t1; t += 2, src += 2 * nb) {           // eight loads in flight per lane
-            u32x4 v[2 * ITEMS];
-#pragma unroll
-            for (int j = 0; j < ITEMS; ++j) {
-                v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (long)j * CT * FL));
-                v[ITEMS + j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + nb + (long)j * CT * FL));
-            }
-#pragma unroll
-            for (int j = 0; j < ITEMS; ++j) acc[j] |= v[j] | v[ITEMS + j];
-        }
-        for (; t < t1; ++t, src += nb) {
+        for (long t = t0; t < t1; ++t, src += nb) {
 #pragma unroll
             for (int j = 0; j < ITEMS; ++j)
                 acc[j] |= __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (long)j * CT * FL));
