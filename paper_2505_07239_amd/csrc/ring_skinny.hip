@@ -117,7 +117,8 @@ __device__ __forceinline__ const u64* weight_row(const GemmParams& p, int kk, in
 template <int MR, int VEC, int KIND>
 __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64* __restrict__ xs,
                                                          int slices) {
-    __shared__ __align__(16) u64 red[SW][RG][64 * VEC];
+    constexpr int RGM = MR < RG ? MR : RG;                     // rows reduced through LDS at a time
+    __shared__ __align__(16) u64 red[SW][RGM][64 * VEC];
     const int nblk = n_blocks(p);
     const int n_eff = KIND == KIND_SOMM ? nblk * p.bs : p.n_cap;
     const int kc = KIND == KIND_SOMM ? p.kc_cap : nblk * p.bs;
@@ -181,15 +182,15 @@ __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64
 
     // partial sums of the four wavefronts -> LDS -> one atomic add per output element
 #pragma unroll
-    for (int r0 = 0; r0 < MR; r0 += RG) {
+    for (int r0 = 0; r0 < MR; r0 += RGM) {
         if (r0) __syncthreads();
 #pragma unroll
-        for (int r = 0; r < RG; ++r)
+        for (int r = 0; r < RGM; ++r)
 #pragma unroll
             for (int v = 0; v < VEC; ++v)
                 red[wave][r][lane * VEC + v] = acc[r0 + r][v] + (cross[r0 + r][v] << 32);
         __syncthreads();
-        for (int i = threadIdx.x; i < RG * 64 * VEC; i += ST) {
+        for (int i = threadIdx.x; i < RGM * 64 * VEC; i += ST) {
             const int r = i / (64 * VEC), c = i - r * (64 * VEC);
             u64 s = 0;
 #pragma unroll
@@ -212,7 +213,9 @@ void (*pick_kernel(int kind))(GemmParams, const u64*, int) {
 int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p) {
     if (p.m < 1 || p.m > COMET_SKINNY_MAX_ROWS)
         return comet_fail(ctx, COMET_EINVAL, "%s: row count outside the vector-ALU path", what);
-    constexpr int MR = COMET_SKINNY_MAX_ROWS;
+    // rows the kernel carries: every weight word is multiplied into all of them, and at eight
+    // rows the vector ALU is as busy as the memory system, so fewer rows get a narrower variant
+    const int MR = p.m <= 2 ? 2 : p.m <= 4 ? 4 : COMET_SKINNY_MAX_ROWS;
     u64* xs = reinterpret_cast<u64*>(p.xp);
     // k-major activation words and Z := C (the workspace of the matrix-core path, 2048 bytes per
     // contraction index, always covers the 2 * MR * 8 bytes per index used here)
@@ -241,7 +244,9 @@ int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p) {
     if (slices > 65535) slices = 65535;
     if (slices < 1) slices = 1;
     void (*kern)(GemmParams, const u64*, int);
-    kern = vec2 ? pick_kernel<MR, 2>(p.kind) : pick_kernel<MR, 1>(p.kind);
+    if (MR == 2) kern = vec2 ? pick_kernel<2, 2>(p.kind) : pick_kernel<2, 1>(p.kind);
+    else if (MR == 4) kern = vec2 ? pick_kernel<4, 2>(p.kind) : pick_kernel<4, 1>(p.kind);
+    else kern = vec2 ? pick_kernel<COMET_SKINNY_MAX_ROWS, 2>(p.kind) : pick_kernel<COMET_SKINNY_MAX_ROWS, 1>(p.kind);
     const bool timed = comet_time_this_launch(ctx);
     if (timed) {
         // the event pair rides on the dispatch itself: no marker packets around the kernel
