@@ -16,7 +16,7 @@ SOURCES = ["ring_gemm_tile_128x64_own.hip", "ring_gemm_planes_128x64_own.hip",
            "ring_gemm_tile_64x64.hip", "ring_gemm_tile_64x64_listed.hip",
            "ring_gemm_planes_128x64.hip", "ring_gemm_planes_64x64.hip", "ring_gemm_planes_64x64_listed.hip",
            "ring_gemm_planes_32x128.hip", "ring_gemm_planes_32x128_listed.hip", "ring_gemm.hip", "wplanes.hip",
-           "ring_skinny.hip", "ctx.hip", "elementwise.hip", "compact.hip", "components.hip", "glue.hip", "probe.hip"]
+           "ring_skinny.hip", "ring_fewrow.hip", "ctx.hip", "elementwise.hip", "compact.hip", "components.hip", "glue.hip", "probe.hip"]
 FLAGS = ["-O3", "-std=c++20", "--offload-arch=gfx950", "-fPIC", "-fvisibility=default",
          # the LDS-DMA helper names M0 as clobbered, which clang flags as a reserved register
          "-Wno-inline-asm",

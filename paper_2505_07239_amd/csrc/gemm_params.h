@@ -107,3 +107,10 @@ static __device__ __forceinline__ long block_start(const GemmParams& p, int blk)
 // traffic and the matrix-core kernel's 32-row tile is faster.
 static const int COMET_SKINNY_MAX_ROWS = 8;
 int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p);
+
+// Matrix-core path for at most COMET_FEWROW_MAX_ROWS activation rows with the weight side in digit
+// planes (plain products only: no result blocks, no per-token row sets): every wavefront streams
+// its own weight fragments from memory into registers.  Runs after the packing kernel (digit
+// planes of [E | A'] in p.xp, Z := C).
+static const int COMET_FEWROW_MAX_ROWS = 32;
+int comet_launch_fewrow(comet_ctx* ctx, const char* what, const GemmParams& p);

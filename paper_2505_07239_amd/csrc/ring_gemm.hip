@@ -432,6 +432,10 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     // per-token row sets: 64-row tiles follow the row sets more closely
     else if (p.tmask) bm = 64;
     plan(bm);
+    // a decoding batch on weight planes: the kernel that streams the planes wavefront by wavefront
+    const bool fewrow = p.w_planes && p.m <= COMET_FEWROW_MAX_ROWS && !p.w_tr && !p.row_comp && !p.tmask &&
+                        ctx->skinny_mode != 1 && ctx->gemm_tile != 2;
+    if (fewrow) p.own_try = 0;                                 // Z := C comes from the packing kernel
 
     // digit planes of [E | A'] and Z := C, one launch
     {
@@ -445,6 +449,7 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         COMET_LAUNCH_CHECK(ctx, what);
     }
     if (p.ks_cap == 0) return COMET_OK;
+    if (fewrow) return comet_launch_fewrow(ctx, what, p);
     if (p.row_comp) {
         // result blocks: list the tiles that are computed (see tile_list_kernel)
         int* sel = p.tile_list;

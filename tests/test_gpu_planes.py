@@ -180,6 +180,65 @@ def test_simm_share_with_weight_planes(ctx, m, other, bs, kept, spare, b_full):
         _run(ctx, cs, party, b_full)
 
 
+# A decoding batch (m <= 32) on weight planes takes the kernel in which every wavefront streams
+# its own fragments: several column groups of 128 with a ragged last one, contraction lengths that
+# are no multiple of 32, blocks of 16 / 48 / 64, every row count that matters for the 32-row
+# matrix-instruction tile; grids of 1, 3 and 7 workgroups make the runs of steps cross from one
+# column group into the next.
+FEW_SHAPES = [
+    (1, 96, 16, (0, 3, 4, 9, 10, 11, 12, 20, 21), 0), (8, 130, 64, (1, 2, 6), 1), (9, 70, 48, (0, 2, 3, 5), 0),
+    (17, 200, 32, tuple(range(0, 22, 2)), 2), (31, 33, 16, tuple(range(19)), 0), (32, 515, 64, (0, 1, 4, 5, 6), 0),
+]
+
+
+@pytest.mark.parametrize("grid", [0, 1, 3, 7])
+@pytest.mark.parametrize("m,other,bs,kept,spare", FEW_SHAPES)
+@pytest.mark.parametrize("kind", ["somm", "simm"])
+def test_few_rows_on_weight_planes(ctx, kind, m, other, bs, kept, spare, grid):
+    import paper_2505_07239_amd as comet
+    nb = max(kept) + 2
+    cs = _case(900 + m, kind, m, other if kind == "somm" else nb * bs, nb * bs if kind == "somm" else other,
+               bs, kept, spare)
+    ctx.set_tuning(comet.TUNE_GEMM_GRID, grid)
+    try:
+        for b_full in (True, False):
+            if kind == "simm" and b_full and bs % 16:
+                continue
+            for party in (0, 1):
+                say("few rows planes %s m=%d other=%d bs=%d blocks=%d grid=%d b_full=%s party %d"
+                    % (kind, m, other, bs, len(kept), grid, b_full, party))
+                _run(ctx, cs, party, b_full)
+    finally:
+        ctx.set_tuning(comet.TUNE_GEMM_GRID, 0)
+
+
+@pytest.mark.parametrize("m", [3, 32])
+def test_few_rows_long_contraction_worst_case_digits(ctx, m):
+    """All digits -128 over runs of steps longer than one accumulation segment (one workgroup
+    takes all 2 x 257 steps of a column group)."""
+    import paper_2505_07239_amd as comet
+    k, n, bs = 8224, 160, 32
+    worst = np.uint64(0x8080808080808080)
+    e, a = np.full((m, k), worst), np.full((m, k), worst)
+    f, b = np.full((k, n), worst), np.full((k, n), worst)
+    e[::3, ::5] = u64(55, 2, m, k)[::3, ::5]
+    f[::7, ::2] = u64(55, 3, k, n)[::7, ::2]
+    c = u64(55, 1, m, n)
+    idx = torch.arange(n // bs, dtype=torch.int32, device="cuda")
+    want = [co.beaver_share(party, e, f, a, b, c) for party in (0, 1)]
+    for grid in (0, 1, 2):
+        ctx.set_tuning(comet.TUNE_GEMM_GRID, grid)
+        try:
+            for party in (0, 1):
+                say("few rows worst-case digits m=%d grid=%d party %d" % (m, grid, party))
+                z = ctx.somm_share(party, bs, idx, None, n // bs, up(e), ctx.open_weight_planes(up(f)), up(a),
+                                   ctx.open_weight_planes(up(b)), up(c))
+                torch.cuda.synchronize()
+                assert np.array_equal(down(z), want[party])
+        finally:
+            ctx.set_tuning(comet.TUNE_GEMM_GRID, 0)
+
+
 def test_planes_long_contraction_worst_case_digits(ctx):
     """All digits -128 over a contraction longer than one accumulation segment."""
     m, k, n, bs = 33, 8224, 32, 32
