@@ -596,6 +596,35 @@ def weight_side_masking(ctx, timed_rotating):
     return out
 
 
+def decoding_batches(ctx, timed_rotating):
+    """The gate projection of the decoding workload (LLaMA-2-13B, 179 of 216 blocks of 64 kept)
+    for batches of 2, 8, 16 and 32 tokens: weight words (vector-ALU kernel up to 8 rows, matrix-core
+    tile kernel beyond) and weight planes (the kernel in which every wavefront streams its own
+    fragments).  Three weight sets in rotation, so every call reads from HBM; the rate counts
+    B_i and F once per call."""
+    import numpy as np
+    import torch
+    from workloads import rng
+    k, nb, bs, t = 5120, 216, 64, 179
+    dev = torch.device("cuda:0")
+    na = t * bs
+    words = lambda st, *shape: rng.uniform_u64_torch(rng.BASE_SEED, 9700 + st, int(np.prod(shape)), dev).view(*shape)
+    idx = torch.arange(t, dtype=torch.int32, device=dev)
+    n_dev = torch.tensor([t], dtype=torch.int32, device=dev)
+    sets = []
+    for q in range(3):
+        f, b = words(10 * q + 1, k, na), words(10 * q + 2, k, nb * bs)
+        sets.append((f, b, ctx.open_weight_planes(f), ctx.open_weight_planes(b)))
+    out = {}
+    for m in (2, 8, 16, 32):
+        e, a, c = words(91, m, k), words(92, m, k), words(93, m, na)
+        z = torch.empty_like(c)
+        for name, off in (("words", 0), ("planes", 2)):
+            call = lambda q: ctx.somm_share(1, bs, idx, n_dev, t, e, sets[q][off], a, sets[q][off + 1], c, out=z)
+            out["decode_gate_m%d_%s_GBs" % (m, name)] = 16.0 * k * na / timed_rotating(call, 3, reps=12) / 1e9
+    return out
+
+
 def glue_steps(ctx, timed):
     """Shuffle steps, merge to full width and rescaling on a 4096 x 11008 matrix of words (the
     activations of 4096 tokens at the FFN width): achieved GB/s of algorithmic bytes."""
@@ -693,6 +722,7 @@ def micro(ctx, layer):
     out.update(mha_layers(ctx, timed))
     out.update(glue_steps(ctx, timed))
     out.update(weight_side_masking(ctx, timed_rotating))
+    out.update(decoding_batches(ctx, timed_rotating))
     macs = ctx.probe_mfma_i8(1024, 2000)
     t = timed(lambda: ctx.probe_mfma_i8(1024, 2000), reps=5)
     out["mfma_i8_issue_TOPs"] = 2.0 * macs / t / 1e12
