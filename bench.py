@@ -47,17 +47,17 @@ ALL_CONFIGS = ["c1", "c2", "c3", "c4", "c5_d100", "c5_d050", "c5_d025", "c5_d010
 # the copy probe of known size in the same run.  The summaries, with the commands, are the
 # files named here under profiles/.  None until measured for that workload and operand format.
 GEMM_TRAFFIC = {
-    ("c2", "planes", "single"): (13560827, "profiles/bench_c2_kernel_trace_and_hbm_counters.md"),
-    ("c3", "planes", "grouped"): (608774720, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
-    ("c3", "planes", "single"): (196775094, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
-    ("c4", "words", "single"): (982336438, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
-    ("c5_d100", "planes", "single"): (1541727902, "profiles/bench_c5_d100_kernel_trace_and_hbm_counters.md"),
-    ("c5_d050", "planes", "single"): (789179683, "profiles/bench_c5_d050_kernel_trace_and_hbm_counters.md"),
-    ("c5_d025", "planes", "single"): (395182257, "profiles/bench_c5_d025_kernel_trace_and_hbm_counters.md"),
-    ("c5_d010", "planes", "grouped"): (357237377, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
-    ("c5_d010", "planes", "single"): (178384918, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
-    ("c5_d005", "planes", "grouped"): (215483809, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
-    ("c5_d005", "planes", "single"): (107508130, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
+    ("c2", "planes", "single"): (13392293, "profiles/bench_c2_kernel_trace_and_hbm_counters.md"),
+    ("c3", "planes", "grouped"): (608387953, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
+    ("c3", "planes", "single"): (197660993, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
+    ("c4", "words", "single"): (987120663, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
+    ("c5_d100", "planes", "single"): (1549274757, "profiles/bench_c5_d100_kernel_trace_and_hbm_counters.md"),
+    ("c5_d050", "planes", "single"): (792771729, "profiles/bench_c5_d050_kernel_trace_and_hbm_counters.md"),
+    ("c5_d025", "planes", "single"): (396956726, "profiles/bench_c5_d025_kernel_trace_and_hbm_counters.md"),
+    ("c5_d010", "planes", "grouped"): (358220326, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
+    ("c5_d010", "planes", "single"): (178866692, "profiles/bench_c5_d010_kernel_trace_and_hbm_counters.md"),
+    ("c5_d005", "planes", "grouped"): (215621442, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
+    ("c5_d005", "planes", "single"): (107567254, "profiles/bench_c5_d005_kernel_trace_and_hbm_counters.md"),
 }
 
 
