@@ -122,7 +122,8 @@ __device__ __forceinline__ void xpack_body(const GemmParams& p, const int part) 
         return;
     }
     const int kc = p.kind == KIND_SOMM ? p.kc_cap : nblk * p.bs;
-    const int row = blockIdx.y * 64 + (threadIdx.x >> 2);      // < mpad by construction
+    const int row = blockIdx.y * 64 + (threadIdx.x >> 2);
+    if (row >= p.mpad) return;                                 // (the few-row kernel packs 32 rows)
     const int half16 = blockIdx.x * 4 + (threadIdx.x & 3);     // 16-word group over the half
     if (half16 >= p.ks_cap * 2) return;
     const int h = part;                                        // 0: E, 1: A'
@@ -435,7 +436,10 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     // a decoding batch on weight planes: the kernel that streams the planes wavefront by wavefront
     const bool fewrow = p.w_planes && p.m <= COMET_FEWROW_MAX_ROWS && !p.w_tr && !p.row_comp && !p.tmask &&
                         ctx->skinny_mode != 1 && ctx->gemm_tile != 2;
-    if (fewrow) p.own_try = 0;                                 // Z := C comes from the packing kernel
+    if (fewrow) {
+        p.own_try = 0;                                         // Z := C comes from the packing kernel
+        p.mpad = 32;                                           // one row tile: a digit group is 512 bytes
+    }
 
     // digit planes of [E | A'] and Z := C, one launch
     {
@@ -443,9 +447,10 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
         if (gx < 1) gx = 1;
         // the Z := C slab shares the launch: give it enough workgroups for about four 16-byte
         // accesses per thread (the packing slabs return at once from the extra ones)
-        const long zgx = ((long)p.m * p.n_cap / (2l * 4 * GT) + p.mpad / 64 - 1) / (p.mpad / 64);
+        const int slabs = (p.mpad + 63) / 64;
+        const long zgx = ((long)p.m * p.n_cap / (2l * 4 * GT) + slabs - 1) / slabs;
         if (zgx > gx) gx = (unsigned)(zgx > 4096 ? 4096 : zgx);
-        hipLaunchKernelGGL(xpack_kernel, dim3(gx, (unsigned)(p.mpad / 64), 3), dim3(GT), 0, ctx->stream, p);
+        hipLaunchKernelGGL(xpack_kernel, dim3(gx, (unsigned)slabs, 3), dim3(GT), 0, ctx->stream, p);
         COMET_LAUNCH_CHECK(ctx, what);
     }
     if (p.ks_cap == 0) return COMET_OK;
