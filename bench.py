@@ -40,6 +40,7 @@ METRIC = "sparse secret-shared FFN ring-GEMM Gop/s (mod 2^64) per party; % of ro
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 INT8_OPS_PER_RING_MAC = 72   # 36 digit products, 2 ops each
+UNOPENED_FEW_ROWS = True     # decoding workloads: fold the opening of F into the share kernel (--opened-few-rows: off)
 ALL_CONFIGS = ["c1", "c2", "c3", "c4", "c5_d100", "c5_d050", "c5_d025", "c5_d010", "c5_d005"]
 
 # HBM bytes per share-kernel launch (average over the launches of one step) from rocprofv3 --pmc
@@ -50,7 +51,7 @@ GEMM_TRAFFIC = {
     ("c2", "planes", "single"): (13392293, "profiles/bench_c2_kernel_trace_and_hbm_counters.md"),
     ("c3", "planes", "grouped"): (608387953, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
     ("c3", "planes", "single"): (197660993, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
-    ("c4", "words", "single"): (987120663, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
+    ("c4", "words", "single"): (1456339776, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
     ("c5_d100", "planes", "single"): (1549274757, "profiles/bench_c5_d100_kernel_trace_and_hbm_counters.md"),
     ("c5_d050", "planes", "single"): (792771729, "profiles/bench_c5_d050_kernel_trace_and_hbm_counters.md"),
     ("c5_d025", "planes", "single"): (396956726, "profiles/bench_c5_d025_kernel_trace_and_hbm_counters.md"),
@@ -94,12 +95,15 @@ class Layer:
     as digit planes -- F is opened directly in that format (``comet_open_weight_planes``), the
     triple shares B_i are packed once, outside the step (offline material, Sec. 3.2)."""
 
-    def __init__(self, ctx, cfg, seed, planes):
+    def __init__(self, ctx, cfg, seed, planes, unopened=True):
         import numpy as np
         import torch
         from workloads import configs, rng
         self.ctx, self.cfg = ctx, cfg
         self.planes = bool(planes) and cfg.tokens > 8      # the few-row kernel reads words
+        # a few rows: the share kernel takes the two masked weight shares and forms F as it reads
+        # them (comet_*_share_unopened); F is then never written to memory
+        self.unopened = bool(unopened) and not self.planes and cfg.tokens <= 8
         dev = torch.device("cuda:0")
         self.mask_np = configs.token_masks(cfg, seed)
         self.mask = torch.from_numpy(self.mask_np).to(dev)
@@ -159,7 +163,9 @@ class Layer:
                 ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_ROWS, cfg.bs, idx, n_dev, self.n_blk,
                                       out=b["g"][i])
         ctx.open(b["d"][0], b["d"][1], out=b["e"])
-        if self.planes:
+        if self.unopened:
+            pass                                            # F = g_0 + g_1 is formed inside the share kernel
+        elif self.planes:
             ctx.open_weight_planes(b["g"][0], b["g"][1], out=b["f"].buf)
         else:
             ctx.open(b["g"][0], b["g"][1], out=b["f"])
@@ -167,7 +173,11 @@ class Layer:
     def _shares(self, ctx, b, idx, n_dev):
         cfg, mm = self.cfg, b["mm"]
         for i in (0, 1):
-            if mm.kind == "somm":
+            if self.unopened:
+                call = ctx.somm_share_unopened if mm.kind == "somm" else ctx.simm_share_unopened
+                call(i, cfg.bs, idx, n_dev, self.n_blk, b["e"], b["g"][0], b["g"][1], b["a"][i], b["bw"][i],
+                     b["c"][i], out=b["z"][i])
+            elif mm.kind == "somm":
                 ctx.somm_share(i, cfg.bs, idx, n_dev, self.n_blk, b["e"], b["f"], b["a"][i], b["bw"][i],
                                b["c"][i], out=b["z"][i])
             else:
@@ -194,6 +204,10 @@ class Layer:
                 continue
             for b in group:
                 self._mask_and_open(ctx, b, self.idx, self.n_dev)
+            if self.unopened:                               # (one call per product and party)
+                for b in group:
+                    self._shares(ctx, b, self.idx, self.n_dev)
+                continue
             members = [(i, b["e"], b["f"], b["a"][i], b["bw"][i], b["c"][i]) for b in group for i in (0, 1)]
             outs = [b["z"][i] for b in group for i in (0, 1)]
             ctx.share_group(kind, cfg.bs, self.idx, self.n_dev, self.n_blk, members, out=outs)
@@ -302,13 +316,15 @@ def roofline_of(layer, wname, timing, skinny_forced, probes):
               "ring_macs_per_launch": macs_per_launch, "gemm_share_of_step": share, "weight_operands": fmt}
     if cfg.tokens <= 8 and not skinny_forced:
         # a few activation rows: the share calls take the vector-ALU kernel, bound by reading the
-        # two weight-side operands (B_i and F, kc x n words each) once per launch
-        wbytes = macs_per_launch / cfg.tokens * 8.0
+        # weight-side operands once per launch: B_i and F (kc x n words each), or B_i and the two
+        # masked shares F is the sum of when the opening is folded into the kernel
+        wbytes = macs_per_launch / cfg.tokens * 8.0 * (1.5 if layer.unopened else 1.0)
         ach = wbytes / (avg_ms * 1e-3) / 1e9
         r = {"bound": "hbm", "kernel": "ring_skinny_kernel", "achieved": ach, "peak": PEAK_HBM_GBS,
              "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-             "note": "algorithmic bytes: the weight-side operands B_i and F of one launch, 8 bytes "
-                     "per word, read once"}
+             "note": "algorithmic bytes: the weight-side operands of one launch, 8 bytes per word, read once: "
+                     + ("B_i and the two masked shares [G]_0, [G]_1 whose sum F is (the opening is folded "
+                        "into the share kernel)" if layer.unopened else "B_i and F")}
         if probes:
             r["frac_of_measured_copy"] = ach / probes["copy_GBs"]
     else:
@@ -409,7 +425,7 @@ def config_entry(ctx, name, probes, planes, skinny_forced, steps=10, warmup=3, l
     cfg, wname = parse_workload(name)
     own = layer is None
     if own:
-        layer = Layer(ctx, cfg, rng.BASE_SEED, planes)
+        layer = Layer(ctx, cfg, rng.BASE_SEED, planes, UNOPENED_FEW_ROWS)
         timing = run_timed(ctx, layer, steps, warmup)
     ms, gemm_ms, n_timed = timing["ms_per_step"], timing["gemm_ms"], timing["n_timed"]
     roof = roofline_of(layer, wname, timing, skinny_forced, probes)
@@ -751,6 +767,8 @@ def main():
                     help="format of the weight-side operands of the share calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true")
+    ap.add_argument("--opened-few-rows", action="store_true",
+                    help="decoding workloads: open F into memory first instead of folding the opening into the share kernel")
     ap.add_argument("--per-call", action="store_true",
                     help="one share call per product and party instead of the grouped calls")
     ap.add_argument("--overlap", action="store_true",
@@ -763,6 +781,8 @@ def main():
     ap.add_argument("--skinny", type=int, default=0, help="tuning sweep: 1 = matrix cores even for m <= 8")
     ap.add_argument("--skinny-slices", type=int, default=0, help="tuning sweep: contraction slices of the m <= 8 kernel")
     args = ap.parse_args()
+    global UNOPENED_FEW_ROWS
+    UNOPENED_FEW_ROWS = not args.opened_few_rows
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (both parties are simulated on it); "
               "run with --gpus 1", file=sys.stderr)
@@ -786,7 +806,7 @@ def main():
     ctx.set_tuning(comet.TUNE_SKINNY, args.skinny)
     ctx.set_tuning(comet.TUNE_SKINNY_SLICES, args.skinny_slices)
     planes = args.weights == "planes"
-    layer = Layer(ctx, cfg, rng.BASE_SEED, planes)
+    layer = Layer(ctx, cfg, rng.BASE_SEED, planes, UNOPENED_FEW_ROWS)
     log("workload %s: %s, m=%d d=%d f=%d bs=%d kept blocks %d/%d (n_act=%d), %.2f G ring ops/step, weight "
         "operands as %s" % (wname, cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs, layer.n_blk, cfg.nb,
                             layer.n_act, layer.ring_ops_per_step / 1e9, "planes" if layer.planes else "words"))

@@ -218,6 +218,28 @@ int comet_simm_share(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64
                      const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i,
                      void* ws, size_t ws_bytes);
 
+/* Decoding (m <= 8 rows): comet_somm_share / comet_simm_share with the opening of
+ * the masked weights folded in (Sec. 2.1: F = [G]_0 + [G]_1).  Instead of the
+ * opened F the call takes the two masked shares of the indexed weights -- what
+ * comet_mask_share(_gather) wrote and what the other party sent -- in F's
+ * layout (G_0, G_1: k x ld for SOMM, ld x n for SIMM) and adds them while it
+ * streams them.  With a few rows the share is bound by reading the weight side
+ * once; opening F first costs a read of both shares, a write of F and a read of
+ * F where this call reads both shares once.  The result is the one of the
+ * opened call, bit for bit.  Everything else as in comet_somm_share /
+ * comet_simm_share, with these limits: m <= 8, row-major words (neither
+ * COMET_WEIGHTS_NEURON_MAJOR nor COMET_WEIGHT_PLANES); COMET_EINVAL otherwise. */
+int comet_somm_share_unopened(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_full, int bs,
+                              const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap,
+                              int flags, const uint64_t* E, const uint64_t* G_0, const uint64_t* G_1,
+                              const uint64_t* A_i, const uint64_t* B_i, const uint64_t* C_i,
+                              uint64_t* Z_i, void* ws, size_t ws_bytes);
+int comet_simm_share_unopened(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64_t n, int bs,
+                              const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap,
+                              int flags, const uint64_t* E, const uint64_t* G_0, const uint64_t* G_1,
+                              const uint64_t* A_i, const uint64_t* B_i, const uint64_t* C_i,
+                              uint64_t* Z_i, void* ws, size_t ws_bytes);
+
 /* Several share products of one shape in one call: the gate and up projections
  * of one layer (Protocol 2 twice, over the same index list), the share
  * products of several requests, or -- where one process plays both parties --

@@ -28,6 +28,7 @@ EXPORTS = [
     "comet_workspace_bytes", "comet_mask_share", "comet_mask_share_gather", "comet_open",
     "comet_weight_planes_bytes", "comet_open_weight_planes",
     "comet_compact_mask", "comet_somm_share", "comet_somm_share_static", "comet_simm_share", "comet_share_group",
+    "comet_somm_share_unopened", "comet_simm_share_unopened",
     "comet_components", "comet_somm_share_blocks", "comet_simm_share_masked",
     "comet_permute_mask", "comet_scatter_cols", "comet_truncate_share",
     "comet_set_tuning", "comet_timing_begin", "comet_timing_end", "comet_probe_mfma_i8", "comet_probe_valu_mac64", "comet_probe_copy",
@@ -71,6 +72,9 @@ def load_library() -> ctypes.CDLL:
     lib.comet_somm_share.argtypes = share
     lib.comet_simm_share.argtypes = share
     lib.comet_somm_share_static.argtypes = share[:-2]
+    # (E, G_0, G_1, A_i, B_i, C_i, Z_i): one pointer more than the opened form
+    lib.comet_somm_share_unopened.argtypes = share[:10] + [vp] + share[10:]
+    lib.comet_simm_share_unopened.argtypes = share[:10] + [vp] + share[10:]
     lib.comet_share_group.argtypes = [vp, i32, i32, ctypes.POINTER(ShareOperands), i64, i64, i64, i32, vp, vp, i32,
                                       i32, vp, sz]
     lib.comet_components.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
@@ -326,6 +330,51 @@ class Context:
                                               _ptr(n_blk_dev), n_blk_cap, flags, _ptr(e), _ptr(f),
                                               _ptr(a_i), _ptr(b_i), _ptr(c_i), _ptr(out), _ptr(ws),
                                               need))
+        return out
+
+    def somm_share_unopened(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, e, g_0, g_1, a_i, b_i, c_i,
+                            b_full=True, out=None):
+        """``somm_share`` for at most 8 rows with the opening folded in: ``g_0``, ``g_1`` are the
+        two masked shares of the indexed weights (k x ld words), F = g_0 + g_1 is never stored."""
+        if _operands(e, g_0, a_i, b_i, c_i) or isinstance(g_1, WeightPlanes):
+            raise TypeError("the unopened form takes words, not weight planes")
+        m, k = e.shape
+        n_full = b_i.shape[1] if b_full else 0
+        ld = n_blk_cap * bs
+        out = torch.empty((m, ld), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        self._somm_shapes(m, k, ld, n_full, g_0, a_i, b_i, c_i, out, b_full, False)
+        _shape(_words(g_1, "g_1"), (k, ld), "G_1")
+        _index_list(blk_idx, n_blk_dev, n_blk_cap, b_full)
+        need = workspace_bytes(OP_SOMM, m, k, ld, bs)
+        ws = self.workspace(need)
+        self._sync_stream()
+        self._check(self.lib.comet_somm_share_unopened(self.h, party, m, k, n_full, bs, _ptr(blk_idx),
+                                                       _ptr(n_blk_dev), n_blk_cap, FULL_B if b_full else 0,
+                                                       _ptr(e), _ptr(g_0), _ptr(g_1), _ptr(a_i), _ptr(b_i),
+                                                       _ptr(c_i), _ptr(out), _ptr(ws), need))
+        return out
+
+    def simm_share_unopened(self, party, bs, blk_idx, n_blk_dev, n_blk_cap, e, g_0, g_1, a_i, b_i, c_i,
+                            a_full=True, b_full=True, out=None):
+        """``simm_share`` for at most 8 rows with the opening folded in (``g_0``, ``g_1``: ld x n)."""
+        if _operands(e, g_0, a_i, b_i, c_i) or isinstance(g_1, WeightPlanes):
+            raise TypeError("the unopened form takes words, not weight planes")
+        m = e.shape[0]
+        n = g_0.shape[1]
+        ld = n_blk_cap * bs
+        k_full = a_i.shape[1] if a_full else (b_i.shape[0] if b_full else 0)
+        out = torch.empty((m, n), dtype=torch.int64, device=e.device) if out is None else _words(out, "out")
+        self._simm_shapes(m, n, ld, k_full, e, g_0, a_i, b_i, c_i, out, a_full, b_full)
+        _shape(_words(g_1, "g_1"), (ld, n), "G_1")
+        _index_list(blk_idx, n_blk_dev, n_blk_cap, a_full or b_full)
+        need = workspace_bytes(OP_SIMM, m, ld, n, bs)
+        ws = self.workspace(need)
+        flags = (FULL_A if a_full else 0) | (FULL_B if b_full else 0)
+        self._sync_stream()
+        self._check(self.lib.comet_simm_share_unopened(self.h, party, m, k_full, n, bs, _ptr(blk_idx),
+                                                       _ptr(n_blk_dev), n_blk_cap, flags, _ptr(e), _ptr(g_0),
+                                                       _ptr(g_1), _ptr(a_i), _ptr(b_i), _ptr(c_i), _ptr(out),
+                                                       _ptr(ws), need))
         return out
 
     def share_group(self, kind, bs, blk_idx, n_blk_dev, n_blk_cap, members, a_full=True, b_full=True, out=None):

@@ -23,6 +23,7 @@ struct GemmParams {
     // W side
     const u64* B;  long ldb;  int b_full;
     const u64* F;  long ldf;
+    const u64* F2;  // few-row path only: second masked share of the weights, F = F + F2 formed on the fly (else null)
     int w_tr;       // SOMM: B_i and F are stored neuron-major (one row of k words per output column)
     int w_planes;   // B_i and F are digit planes (comet_open_weight_planes); ldb / ldf = their columns
     const u64* C;

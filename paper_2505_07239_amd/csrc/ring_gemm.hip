@@ -396,6 +396,9 @@ int run_share(comet_ctx* ctx, const char* what, GemmParams p, void* ws, size_t w
     place_in_workspace(p, ws);
 
     if (p.n_cap == 0) return COMET_OK;
+    if (p.F2 && (p.m > COMET_SKINNY_MAX_ROWS || ctx->skinny_mode == 1 || p.w_tr || p.w_planes || p.row_comp || p.tmask))
+        return comet_fail(ctx, COMET_EINVAL, "%s: unopened weight shares are taken by the few-row kernel only "
+                          "(m <= %d, row-major words)", what, COMET_SKINNY_MAX_ROWS);
     // (the few-row kernel reads the weights along the output columns: row-major words only)
     if (p.m <= COMET_SKINNY_MAX_ROWS && ctx->skinny_mode != 1 && !p.w_tr && !p.w_planes)
         return comet_launch_skinny(ctx, what, p);
@@ -667,6 +670,44 @@ int comet_somm_share(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_
     const int rc = somm_params(ctx, what, p, party, m, k, n_full, bs, blk_idx, n_blk_dev, n_blk_cap, flags,
                                E, F, A_i, B_i, C_i, Z_i);
     if (rc) return rc;
+    return run_share(ctx, what, p, ws, ws_bytes);
+}
+
+// second masked share of the weights for the *_unopened calls: same layout and checks as F
+static int set_unopened(comet_ctx* ctx, const char* what, GemmParams& p, const uint64_t* G_1) {
+    if (!G_1) return comet_fail(ctx, COMET_EINVAL, "%s: null pointer", what);
+    if (!comet_aligned16(G_1)) return comet_fail(ctx, COMET_EALIGN, "%s: operands must be 16-byte aligned", what);
+    p.F2 = (const u64*)G_1;
+    return COMET_OK;
+}
+
+int comet_somm_share_unopened(comet_ctx* ctx, int party, int64_t m, int64_t k, int64_t n_full, int bs,
+                              const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap, int flags,
+                              const uint64_t* E, const uint64_t* G_0, const uint64_t* G_1,
+                              const uint64_t* A_i, const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i,
+                              void* ws, size_t ws_bytes) {
+    const char* what = "comet_somm_share_unopened";
+    COMET_CHECK_CTX(ctx);
+    GemmParams p = {};
+    int rc = somm_params(ctx, what, p, party, m, k, n_full, bs, blk_idx, n_blk_dev, n_blk_cap, flags,
+                         E, G_0, A_i, B_i, C_i, Z_i);
+    if (rc) return rc;
+    if ((rc = set_unopened(ctx, what, p, G_1)) != COMET_OK) return rc;
+    return run_share(ctx, what, p, ws, ws_bytes);
+}
+
+int comet_simm_share_unopened(comet_ctx* ctx, int party, int64_t m, int64_t k_full, int64_t n, int bs,
+                              const int32_t* blk_idx, const int32_t* n_blk_dev, int n_blk_cap, int flags,
+                              const uint64_t* E, const uint64_t* G_0, const uint64_t* G_1,
+                              const uint64_t* A_i, const uint64_t* B_i, const uint64_t* C_i, uint64_t* Z_i,
+                              void* ws, size_t ws_bytes) {
+    const char* what = "comet_simm_share_unopened";
+    COMET_CHECK_CTX(ctx);
+    GemmParams p = {};
+    int rc = simm_params(ctx, what, p, party, m, k_full, n, bs, blk_idx, n_blk_dev, n_blk_cap, flags,
+                         E, G_0, A_i, B_i, C_i, Z_i);
+    if (rc) return rc;
+    if ((rc = set_unopened(ctx, what, p, G_1)) != COMET_OK) return rc;
     return run_share(ctx, what, p, ws, ws_bytes);
 }
 

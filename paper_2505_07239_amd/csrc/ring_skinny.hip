@@ -82,6 +82,8 @@ template <>
 struct WVec<1> {
     u64 v[1];
     __device__ __forceinline__ void load(const u64* q) { v[0] = __builtin_nontemporal_load(q); }
+    __device__ __forceinline__ void zero() { v[0] = 0; }
+    __device__ __forceinline__ void add(const WVec& o) { v[0] += o.v[0]; }
 };
 template <>
 struct WVec<2> {
@@ -90,6 +92,8 @@ struct WVec<2> {
         const u64x2 t = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(q));   // read once
         v[0] = t.x; v[1] = t.y;
     }
+    __device__ __forceinline__ void zero() { v[0] = v[1] = 0; }
+    __device__ __forceinline__ void add(const WVec& o) { v[0] += o.v[0]; v[1] += o.v[1]; }
 };
 
 __device__ __forceinline__ void mac(u64& acc, u64& cross, u64 x, u64 w) {
@@ -114,7 +118,9 @@ __device__ __forceinline__ const u64* weight_row(const GemmParams& p, int kk, in
     return wB + (size_t)row * p.ldb;
 }
 
-template <int MR, int VEC, int KIND>
+// UNOPENED: the rows of F are given as the two masked shares whose sum F is (p.F and p.F2, same
+// layout): both are streamed and added on the fly, F itself is never written to memory.
+template <int MR, int VEC, int KIND, bool UNOPENED>
 __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64* __restrict__ xs,
                                                          int slices) {
     constexpr int RGM = MR < RG ? MR : RG;                     // rows reduced through LDS at a time
@@ -137,6 +143,7 @@ __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64
     }
     const u64* wB = p.B + colB;
     const u64* wF = p.F + col;
+    const u64* wF2 = UNOPENED ? p.F2 + col : nullptr;
 
     // this wavefront's run [k0, k1) of the stacked contraction [0, 2 kc)
     const int kt = 2 * kc;
@@ -157,11 +164,19 @@ __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64
 
     int kk = k0;
     for (; kk + UNROLL <= k1; kk += UNROLL) {
-        WVec<VEC> w[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) w[u].load(weight_row<KIND>(p, kk + u, kc, wB, wF));
+        WVec<VEC> w[UNROLL], w2[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
+            const u64* src = weight_row<KIND>(p, kk + u, kc, wB, wF);
+            w[u].load(src);
+            if (UNOPENED) {
+                if (kk + u >= kc) w2[u].load(wF2 + (src - wF));   // the same row of the other share
+                else w2[u].zero();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            if (UNOPENED) w[u].add(w2[u]);
             const int q = kk + u;
             const u64* x = xs + ((size_t)(q >= kc ? p.kc_cap + (q - kc) : q)) * MR;
 #pragma unroll
@@ -172,7 +187,13 @@ __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64
     }
     for (; kk < k1; ++kk) {
         WVec<VEC> w;
-        w.load(weight_row<KIND>(p, kk, kc, wB, wF));
+        const u64* src = weight_row<KIND>(p, kk, kc, wB, wF);
+        w.load(src);
+        if (UNOPENED && kk >= kc) {
+            WVec<VEC> w2;
+            w2.load(wF2 + (src - wF));
+            w.add(w2);
+        }
         const u64* x = xs + ((size_t)(kk >= kc ? p.kc_cap + (kk - kc) : kk)) * MR;
 #pragma unroll
         for (int r = 0; r < MR; ++r)
@@ -204,8 +225,10 @@ __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64
 }
 
 template <int MR, int VEC>
-void (*pick_kernel(int kind))(GemmParams, const u64*, int) {
-    return kind == KIND_SOMM ? ring_skinny_kernel<MR, VEC, KIND_SOMM> : ring_skinny_kernel<MR, VEC, KIND_SIMM>;
+void (*pick_kernel(int kind, bool unopened))(GemmParams, const u64*, int) {
+    if (unopened)
+        return kind == KIND_SOMM ? ring_skinny_kernel<MR, VEC, KIND_SOMM, true> : ring_skinny_kernel<MR, VEC, KIND_SIMM, true>;
+    return kind == KIND_SOMM ? ring_skinny_kernel<MR, VEC, KIND_SOMM, false> : ring_skinny_kernel<MR, VEC, KIND_SIMM, false>;
 }
 
 }  // namespace
@@ -244,9 +267,10 @@ int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p) {
     if (slices > 65535) slices = 65535;
     if (slices < 1) slices = 1;
     void (*kern)(GemmParams, const u64*, int);
-    if (MR == 2) kern = vec2 ? pick_kernel<2, 2>(p.kind) : pick_kernel<2, 1>(p.kind);
-    else if (MR == 4) kern = vec2 ? pick_kernel<4, 2>(p.kind) : pick_kernel<4, 1>(p.kind);
-    else kern = vec2 ? pick_kernel<COMET_SKINNY_MAX_ROWS, 2>(p.kind) : pick_kernel<COMET_SKINNY_MAX_ROWS, 1>(p.kind);
+    const bool un = p.F2 != nullptr;
+    if (MR == 2) kern = vec2 ? pick_kernel<2, 2>(p.kind, un) : pick_kernel<2, 1>(p.kind, un);
+    else if (MR == 4) kern = vec2 ? pick_kernel<4, 2>(p.kind, un) : pick_kernel<4, 1>(p.kind, un);
+    else kern = vec2 ? pick_kernel<COMET_SKINNY_MAX_ROWS, 2>(p.kind, un) : pick_kernel<COMET_SKINNY_MAX_ROWS, 1>(p.kind, un);
     const bool timed = comet_time_this_launch(ctx);
     if (timed) {
         // the event pair rides on the dispatch itself: no marker packets around the kernel

@@ -316,6 +316,59 @@ def test_share_few_rows(ctx, kind, m, k, n, bs, keep, path):
         ctx.set_tuning(comet.TUNE_SKINNY, 0)
 
 
+@pytest.mark.parametrize("kind,m,k,n,bs,keep", [
+    ("somm", 1, 70, 96, 3, 5), ("somm", 2, 300, 512, 16, 20), ("somm", 4, 45, 200, 8, 9), ("somm", 5, 130, 77, 7, 6),
+    ("somm", 8, 1100, 640, 64, 7),
+    ("simm", 1, 96, 70, 3, 5), ("simm", 2, 512, 300, 16, 20), ("simm", 3, 200, 45, 8, 9), ("simm", 7, 77, 131, 7, 6),
+    ("simm", 8, 640, 1100, 64, 7)])
+@pytest.mark.parametrize("b_full", [True, False])
+def test_share_few_rows_unopened(ctx, kind, m, k, n, bs, keep, b_full):
+    """The few-row share with the opening folded in: handed the two masked shares of the indexed
+    weights (F = G_0 + G_1, Sec. 2.1) it must give the bits of Eq. 1 on the opened F.  The split of
+    F into shares is random, so a dropped or doubled share cannot cancel."""
+    case = _random_case(kind, m, k, n, bs, keep, 180 + m)
+    t = len(case.idx)
+    g_1 = u64(181, m + 3, *case.f.shape)
+    g_0 = case.f - g_1                                      # mod 2^64
+    assert np.array_equal(co.open_(g_0, g_1), case.f)
+    gi = torch.from_numpy(case.idx).cuda() if t else torch.zeros(1, dtype=torch.int32, device="cuda")
+    n_dev = torch.tensor([t], dtype=torch.int32, device="cuda")
+    for party in (0, 1):
+        say("few rows unopened %s m=%d k=%d n=%d bs=%d b_full=%s party %d" % (kind, m, k, n, bs, b_full, party))
+        if kind == "somm":
+            b_i = case.b[party] if b_full else co.index_cols(case.b[party], case.idx, bs)
+            z = ctx.somm_share_unopened(party, bs, gi, n_dev, t, up(case.e), up(g_0), up(g_1), up(case.a[party]),
+                                        up(b_i), up(case.c[party]), b_full=b_full)
+        else:
+            a_i = case.a[party] if b_full else co.index_cols(case.a[party], case.idx, bs)
+            b_i = case.b[party] if b_full else co.index_rows(case.b[party], case.idx, bs)
+            z = ctx.simm_share_unopened(party, bs, gi, n_dev, t, up(case.e), up(g_0), up(g_1), up(a_i), up(b_i),
+                                        up(case.c[party]), a_full=b_full, b_full=b_full)
+        torch.cuda.synchronize()
+        assert np.array_equal(down(z), case.z[party])
+
+
+def test_share_unopened_limits(ctx):
+    """Beyond eight rows, or when the few-row kernel is switched off, the unopened form is refused
+    with a clear error (and nothing is launched)."""
+    import paper_2505_07239_amd as comet
+    case = _random_case("somm", 9, 64, 96, 8, 4, 190)
+    t = len(case.idx)
+    gi, n_dev = torch.from_numpy(case.idx).cuda(), torch.tensor([t], dtype=torch.int32, device="cuda")
+    args = (1, 8, gi, n_dev, t, up(case.e), up(case.f), up(case.f), up(case.a[1]), up(case.b[1]), up(case.c[1]))
+    with pytest.raises(comet.CometError) as ei:
+        ctx.somm_share_unopened(*args)
+    assert ei.value.code == -1 and "few-row" in str(ei.value)
+    case = _random_case("somm", 4, 64, 96, 8, 4, 191)
+    args = (1, 8, gi, n_dev, t, up(case.e), up(case.f), up(case.f), up(case.a[1]), up(case.b[1]), up(case.c[1]))
+    ctx.set_tuning(comet.TUNE_SKINNY, 1)
+    try:
+        with pytest.raises(comet.CometError):
+            ctx.somm_share_unopened(*args)
+    finally:
+        ctx.set_tuning(comet.TUNE_SKINNY, 0)
+
+
 @pytest.mark.parametrize("m,k,n,bs,keep", [
     (1, 2, 4, 4, 1), (37, 70, 96, 3, 5), (130, 46, 200, 8, 9), (65, 34, 64, 32, 1),
     (200, 300, 512, 16, 20), (9, 520, 600, 20, 17), (16, 778, 384, 32, 5), (256, 768, 3072, 32, 10)])
