@@ -176,14 +176,9 @@ constexpr int FEWROW_STAGES = 3;
 template <int KIND, bool GATHER>
 int launch_fewrow(comet_ctx* ctx, const char* what, const GemmParams& p) {
     auto kern = ring_fewrow_kernel<KIND, GATHER, FEWROW_STAGES>;
-    // as many workgroups as fit the chip at once (the kernel uses no LDS: registers decide)
-    static int per_cu = 0;
-    if (!per_cu) {
-        int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, FT, 0) != hipSuccess || n < 1) n = 1;
-        per_cu = n > 2 ? 2 : n;
-    }
-    int grid = ctx->gemm_grid > 0 ? ctx->gemm_grid : ctx->num_cu * per_cu;
+    // one workgroup per compute unit: the accumulator planes and the fragments in flight take a
+    // wavefront's whole register budget, so that is what the chip holds at once
+    int grid = ctx->gemm_grid > 0 ? ctx->gemm_grid : ctx->num_cu;
     const long units = (long)((p.n_cap + FCOLS - 1) / FCOLS) * 2 * p.ks_cap;
     if (grid > units) grid = (int)(units > 0 ? units : 1);
     if (comet_time_this_launch(ctx)) {
