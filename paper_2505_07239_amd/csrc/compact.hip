@@ -373,7 +373,7 @@ __global__ __launch_bounds__(CT) void compact_count_kernel(const unsigned short*
 // One workgroup; the counts pass through LDS in tiles so that global accesses are
 // coalesced and each thread scans a contiguous run out of LDS.
 constexpr int ST = 1024;
-constexpr int SCAN_PER = 8;                       // counts per thread per tile
+constexpr int SCAN_PER = 16;                      // counts per thread per tile (64 KB of LDS)
 __global__ __launch_bounds__(ST) void compact_scan_kernel(int* __restrict__ counts, int n,
                                                           int* __restrict__ n_blk_dev) {
     __shared__ int tile[ST * SCAN_PER];
