@@ -145,7 +145,9 @@ def _token_masks(seed, n_tok, nb, density=0.3, shared=0.4):
 @pytest.mark.parametrize("n_tok,nb", [
     (2, 1), (2, 3), (7, 5), (33, 15), (16, 16), (9, 17), (64, 344), (512, 344), (513, 343), (380, 345),
     (31, 4095), (32, 4096), (4096, 344), (1000, 1001), (300, 4096), (129, 4097), (40, 13824), (333, 11008),
-    (17, 65535), (9, 65536), (700, 65536), (5, 65537), (3, 200_003), (300, 70_001), (2100, 16400)])
+    (17, 65535), (9, 65536), (700, 65536), (5, 65537), (3, 200_003), (300, 70_001), (2100, 16400),
+    # column periods of exactly one trip of the narrow and of the wide workgroup, and in between
+    (40, 16384), (20, 32768), (50, 2049), (66, 8190), (2, 65536), (8200, 344)])
 def test_compact_mask_many_tokens(ctx, n_tok, nb):
     """Several token rows: one workgroup over the flat mask, the flat pass with merged bitmaps,
     and (beyond 65536 columns) the token split per column chunk; row lengths of every
