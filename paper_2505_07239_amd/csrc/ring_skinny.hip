@@ -238,7 +238,7 @@ int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p) {
         return comet_fail(ctx, COMET_EINVAL, "%s: row count outside the vector-ALU path", what);
     // rows the kernel carries: every weight word is multiplied into all of them, and at eight
     // rows the vector ALU is as busy as the memory system, so fewer rows get a narrower variant
-    const int MR = p.m <= 2 ? 2 : p.m <= 4 ? 4 : COMET_SKINNY_MAX_ROWS;
+    const int MR = p.m <= 2 ? 2 : p.m <= 4 ? 4 : p.m <= 6 ? 6 : COMET_SKINNY_MAX_ROWS;
     u64* xs = reinterpret_cast<u64*>(p.xp);
     // k-major activation words and Z := C (the workspace of the matrix-core path, 2048 bytes per
     // contraction index, always covers the 2 * MR * 8 bytes per index used here)
@@ -270,6 +270,7 @@ int comet_launch_skinny(comet_ctx* ctx, const char* what, const GemmParams& p) {
     const bool un = p.F2 != nullptr;
     if (MR == 2) kern = vec2 ? pick_kernel<2, 2>(p.kind, un) : pick_kernel<2, 1>(p.kind, un);
     else if (MR == 4) kern = vec2 ? pick_kernel<4, 2>(p.kind, un) : pick_kernel<4, 1>(p.kind, un);
+    else if (MR == 6) kern = vec2 ? pick_kernel<6, 2>(p.kind, un) : pick_kernel<6, 1>(p.kind, un);
     else kern = vec2 ? pick_kernel<COMET_SKINNY_MAX_ROWS, 2>(p.kind, un) : pick_kernel<COMET_SKINNY_MAX_ROWS, 1>(p.kind, un);
     const bool timed = comet_time_this_launch(ctx);
     if (timed) {
