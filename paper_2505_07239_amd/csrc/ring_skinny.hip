@@ -145,7 +145,10 @@ __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64
     const u64* wF = p.F + col;
     const u64* wF2 = UNOPENED ? p.F2 + col : nullptr;
 
-    // this wavefront's run [k0, k1) of the stacked contraction [0, 2 kc)
+    // this wavefront's run [k0, k1) of the stacked contraction [0, 2 kc), taken in interleaved
+    // order: position j is row j / 2 of B_i (j even) or of F (j odd), so that every run reads
+    // both operands alike (with the opening folded in an F row is two loads, a B_i row one)
+    auto stacked = [&](int j) { return (j >> 1) + ((j & 1) ? kc : 0); };
     const int kt = 2 * kc;
     const int per_wg = (kt + slices - 1) / slices;
     const int per_wave = (per_wg + SW - 1) / SW;
@@ -167,17 +170,18 @@ __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64
         WVec<VEC> w[UNROLL], w2[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const u64* src = weight_row<KIND>(p, kk + u, kc, wB, wF);
+            const int q = stacked(kk + u);
+            const u64* src = weight_row<KIND>(p, q, kc, wB, wF);
             w[u].load(src);
             if (UNOPENED) {
-                if (kk + u >= kc) w2[u].load(wF2 + (src - wF));   // the same row of the other share
+                if (q >= kc) w2[u].load(wF2 + (src - wF));       // the same row of the other share
                 else w2[u].zero();
             }
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             if (UNOPENED) w[u].add(w2[u]);
-            const int q = kk + u;
+            const int q = stacked(kk + u);
             const u64* x = xs + ((size_t)(q >= kc ? p.kc_cap + (q - kc) : q)) * MR;
 #pragma unroll
             for (int r = 0; r < MR; ++r)
@@ -187,14 +191,15 @@ __global__ __launch_bounds__(ST) void ring_skinny_kernel(GemmParams p, const u64
     }
     for (; kk < k1; ++kk) {
         WVec<VEC> w;
-        const u64* src = weight_row<KIND>(p, kk, kc, wB, wF);
+        const int q = stacked(kk);
+        const u64* src = weight_row<KIND>(p, q, kc, wB, wF);
         w.load(src);
-        if (UNOPENED && kk >= kc) {
+        if (UNOPENED && q >= kc) {
             WVec<VEC> w2;
             w2.load(wF2 + (src - wF));
             w.add(w2);
         }
-        const u64* x = xs + ((size_t)(kk >= kc ? p.kc_cap + (kk - kc) : kk)) * MR;
+        const u64* x = xs + ((size_t)(q >= kc ? p.kc_cap + (q - kc) : q)) * MR;
 #pragma unroll
         for (int r = 0; r < MR; ++r)
 #pragma unroll
