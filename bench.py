@@ -51,7 +51,7 @@ GEMM_TRAFFIC = {
     ("c2", "planes", "single"): (13392293, "profiles/bench_c2_kernel_trace_and_hbm_counters.md"),
     ("c3", "planes", "grouped"): (608387953, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
     ("c3", "planes", "single"): (197660993, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
-    ("c4", "words", "single"): (1456339776, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
+    ("c4", "words", "single"): (1456341918, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
     ("c5_d100", "planes", "single"): (1549274757, "profiles/bench_c5_d100_kernel_trace_and_hbm_counters.md"),
     ("c5_d050", "planes", "single"): (792771729, "profiles/bench_c5_d050_kernel_trace_and_hbm_counters.md"),
     ("c5_d025", "planes", "single"): (396956726, "profiles/bench_c5_d025_kernel_trace_and_hbm_counters.md"),
