@@ -504,6 +504,46 @@ def test_share_empty_mask(ctx):
     assert np.array_equal(down(z), c)
 
 
+@pytest.mark.parametrize("m", [4, 16, 40])
+def test_share_empty_mask_every_path(ctx, m):
+    """No active block (count on the device is zero, capacity is not): SIMM returns C_i and SOMM
+    writes nothing, on weight words, on weight planes (the few-row and the tile kernels) and with
+    the opening folded in."""
+    k, n, bs, cap = 64, 48, 16, 2
+    gi = torch.zeros(cap, dtype=torch.int32, device="cuda")
+    n_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sent = int(SENTINEL.view(np.int64))
+    # SIMM: E m x ld, F ld x n, A m x k, B k x n
+    e, a, c = u64(57, 1, m, cap * bs), u64(57, 2, m, k), u64(57, 3, m, n)
+    f, b = u64(57, 4, cap * bs, n), u64(57, 5, k, n)
+    forms = [("words", up(f), up(b))]
+    forms.append(("planes", ctx.open_weight_planes(up(f)), ctx.open_weight_planes(up(b))))
+    for name, fw, bw in forms:
+        say("empty mask simm %s m=%d" % (name, m))
+        z = ctx.simm_share(1, bs, gi, n_dev, cap, up(e), fw, up(a), bw, up(c))
+        torch.cuda.synchronize()
+        assert np.array_equal(down(z), c)
+    if m <= 8:
+        z = ctx.simm_share_unopened(1, bs, gi, n_dev, cap, up(e), up(f), up(f), up(a), up(b), up(c))
+        torch.cuda.synchronize()
+        assert np.array_equal(down(z), c)
+    # SOMM: E, A m x k, F k x ld, B k x n_full, C m x ld
+    e, a, c = u64(58, 1, m, k), u64(58, 2, m, k), u64(58, 3, m, cap * bs)
+    f, b = u64(58, 4, k, cap * bs), u64(58, 5, k, 6 * bs)
+    forms = [("words", up(f), up(b)), ("planes", ctx.open_weight_planes(up(f)), ctx.open_weight_planes(up(b)))]
+    for name, fw, bw in forms:
+        say("empty mask somm %s m=%d" % (name, m))
+        out = torch.full((m, cap * bs), sent, dtype=torch.int64, device="cuda")
+        ctx.somm_share(0, bs, gi, n_dev, cap, up(e), fw, up(a), bw, up(c), out=out)
+        torch.cuda.synchronize()
+        assert np.all(down(out) == SENTINEL)
+    if m <= 8:
+        out = torch.full((m, cap * bs), sent, dtype=torch.int64, device="cuda")
+        ctx.somm_share_unopened(0, bs, gi, n_dev, cap, up(e), up(f), up(f), up(a), up(b), up(c), out=out)
+        torch.cuda.synchronize()
+        assert np.all(down(out) == SENTINEL)
+
+
 @pytest.mark.parametrize("grid", [0, 1, 8])
 def test_share_extreme_digits_long_contraction(ctx, grid):
     """All-0x80 bytes make every signed digit -128, the worst case for the
