@@ -343,12 +343,19 @@ __global__ __launch_bounds__(MT) void compact_merge_kernel(const u32* __restrict
     }
 }
 
-// index list of a mask of at most 4096 columns from its bit words (one word per thread)
+// index list of a mask of at most 4096 columns from its bit words (one word per thread), or from
+// a few bitmaps of them that are ORed on the way (n_parts of them, stride16 words apart)
+constexpr long SMALL_MERGE_MAX = 32;
 __global__ __launch_bounds__(CT) void compact_small_words_kernel(const unsigned short* __restrict__ words,
-                                                                 long nb, int* __restrict__ blk_idx,
+                                                                 long n_parts, long stride16, long nb,
+                                                                 int* __restrict__ blk_idx,
                                                                  int* __restrict__ n_blk_dev) {
     __shared__ int sm[CT / 64 + 1];
-    const u32 bits = ((long)threadIdx.x * FL < nb) ? (u32)words[threadIdx.x] : 0u;
+    u32 bits = 0;
+    if ((long)threadIdx.x * FL < nb) {
+#pragma unroll 8
+        for (long y = 0; y < n_parts; ++y) bits |= (u32)words[y * stride16 + threadIdx.x];
+    }
     int count;
     const int off = block_excl_scan(__builtin_popcount(bits), sm, &count);
     emit_bits(bits, (int)threadIdx.x * FL, blk_idx + off);
@@ -588,7 +595,8 @@ extern "C" int comet_compact_mask(comet_ctx* ctx, const uint8_t* mask, int64_t n
                            p.gy > 1 ? reinterpret_cast<unsigned short*>(parts) : words, 2 * p.stride32, counts);
         COMET_LAUNCH_CHECK(ctx, what);
     }
-    if (p.gy > 1) {
+    const bool small_merge = nb <= (long)CT * FL && p.gy > 1 && p.gy <= SMALL_MERGE_MAX;
+    if (p.gy > 1 && !small_merge) {
         int mw_log2 = 4;                                       // 64 lane groups share the bitmaps ...
         while (mw_log2 < 10 && (MT >> (mw_log2 + 1)) >= p.gy) ++mw_log2;   // ... or as many as there are bitmaps
         const long mw = 1l << mw_log2;
@@ -597,8 +605,13 @@ extern "C" int comet_compact_mask(comet_ctx* ctx, const uint8_t* mask, int64_t n
         COMET_LAUNCH_CHECK(ctx, what);
     }
     if (nb <= (long)CT * FL) {
-        hipLaunchKernelGGL(compact_small_words_kernel, dim3(1), dim3(CT), 0, ctx->stream, words, (long)nb,
-                           blk_idx, n_blk_dev);
+        if (small_merge)                                       // the few bitmaps are merged on the way
+            hipLaunchKernelGGL(compact_small_words_kernel, dim3(1), dim3(CT), 0, ctx->stream,
+                               reinterpret_cast<const unsigned short*>(parts), p.gy, 2 * p.stride32, (long)nb,
+                               blk_idx, n_blk_dev);
+        else
+            hipLaunchKernelGGL(compact_small_words_kernel, dim3(1), dim3(CT), 0, ctx->stream, words, 1l, 0l,
+                               (long)nb, blk_idx, n_blk_dev);
         COMET_LAUNCH_CHECK(ctx, what);
         return COMET_OK;
     }
