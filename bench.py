@@ -40,6 +40,7 @@ METRIC = "sparse secret-shared FFN ring-GEMM Gop/s (mod 2^64) per party; % of ro
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 INT8_OPS_PER_RING_MAC = 72   # 36 digit products, 2 ops each
+NEURON_MAJOR_SOMM = True     # SOMM weights stored one row per neuron when they travel as planes (--row-major-weights: off)
 UNOPENED_FEW_ROWS = True     # decoding workloads: fold the opening of F into the share kernel (--opened-few-rows: off)
 ALL_CONFIGS = ["c1", "c2", "c3", "c4", "c5_d100", "c5_d050", "c5_d025", "c5_d010", "c5_d005"]
 
@@ -95,7 +96,7 @@ class Layer:
     as digit planes -- F is opened directly in that format (``comet_open_weight_planes``), the
     triple shares B_i are packed once, outside the step (offline material, Sec. 3.2)."""
 
-    def __init__(self, ctx, cfg, seed, planes, unopened=True):
+    def __init__(self, ctx, cfg, seed, planes, unopened=True, neuron_major=True):
         import numpy as np
         import torch
         from workloads import configs, rng
@@ -104,6 +105,10 @@ class Layer:
         # a few rows: the share kernel takes the two masked weight shares and forms F as it reads
         # them (comet_*_share_unopened); F is then never written to memory
         self.unopened = bool(unopened) and not self.planes and cfg.tokens <= 8
+        # SOMM weights (and their triple shares) stored one row per neuron: a kept neuron is one
+        # contiguous run in both projections of the layer (the weights are permuted and stored
+        # once, offline, so their layout is free); the planes the share calls read are the same
+        self.neuron_major = bool(neuron_major) and self.planes
         dev = torch.device("cuda:0")
         self.mask_np = configs.token_masks(cfg, seed)
         self.mask = torch.from_numpy(self.mask_np).to(dev)
@@ -123,11 +128,14 @@ class Layer:
             b = dict(mm=mm)
             # additive shares and triple shares are uniform over Z_{2^64} whatever the secrets are
             b["x"] = [words(mm, configs.R_XSPLIT, mm.m, mm.k), words(mm, configs.R_X, mm.m, mm.k)]
-            b["y"] = [words(mm, configs.R_YSPLIT, mm.k, mm.n), words(mm, configs.R_Y, mm.k, mm.n)]
+            wshape = (mm.n, mm.k) if (self.neuron_major and mm.kind == "somm") else (mm.k, mm.n)
+            b["y"] = [words(mm, configs.R_YSPLIT, *wshape), words(mm, configs.R_Y, *wshape)]
             b["a"] = [words(mm, configs.R_ASPLIT, mm.m, mm.k), words(mm, configs.R_A, mm.m, mm.k)]
-            b["b"] = [words(mm, configs.R_BSPLIT, mm.k, mm.n), words(mm, configs.R_B, mm.k, mm.n)]
+            b["b"] = [words(mm, configs.R_BSPLIT, *wshape), words(mm, configs.R_B, *wshape)]
+            b["nm"] = self.neuron_major and mm.kind == "somm"
             if mm.kind == "somm":
-                dshape, gshape, zshape = (mm.m, mm.k), (mm.k, self.n_act), (mm.m, self.n_act)
+                dshape, zshape = (mm.m, mm.k), (mm.m, self.n_act)
+                gshape = (self.n_act, mm.k) if b["nm"] else (mm.k, self.n_act)
             else:
                 dshape, gshape, zshape = (mm.m, self.n_act), (self.n_act, mm.n), (mm.m, mm.n)
             b["c"] = [words(mm, configs.R_CSPLIT, *zshape, shift=50 * i) for i in (0, 1)]
@@ -136,8 +144,8 @@ class Layer:
             b["e"] = torch.empty(dshape, dtype=torch.int64, device=dev)
             b["z"] = [torch.empty(zshape, dtype=torch.int64, device=dev) for _ in (0, 1)]
             if self.planes:
-                b["bw"] = [ctx.open_weight_planes(b["b"][i]) for i in (0, 1)]       # offline
-                b["f"] = ctx.open_weight_planes(b["g"][0], b["g"][1])               # buffer of the right size
+                b["bw"] = [ctx.open_weight_planes(b["b"][i], neuron_major=b["nm"]) for i in (0, 1)]   # offline
+                b["f"] = ctx.open_weight_planes(b["g"][0], b["g"][1], neuron_major=b["nm"])   # buffer of the right size
             else:
                 b["bw"] = b["b"]
                 b["f"] = torch.empty(gshape, dtype=torch.int64, device=dev)
@@ -155,8 +163,8 @@ class Layer:
         for i in (0, 1):
             if mm.kind == "somm":
                 ctx.mask_share(b["x"][i], b["a"][i], out=b["d"][i])
-                ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_COLS, cfg.bs, idx, n_dev, self.n_blk,
-                                      out=b["g"][i])
+                ctx.mask_share_gather(b["y"][i], b["b"][i], comet.AXIS_ROWS if b["nm"] else comet.AXIS_COLS,
+                                      cfg.bs, idx, n_dev, self.n_blk, out=b["g"][i])
             else:
                 ctx.mask_share_gather(b["x"][i], b["a"][i], comet.AXIS_COLS, cfg.bs, idx, n_dev, self.n_blk,
                                       out=b["d"][i])
@@ -166,7 +174,7 @@ class Layer:
         if self.unopened:
             pass                                            # F = g_0 + g_1 is formed inside the share kernel
         elif self.planes:
-            ctx.open_weight_planes(b["g"][0], b["g"][1], out=b["f"].buf)
+            ctx.open_weight_planes(b["g"][0], b["g"][1], out=b["f"].buf, neuron_major=b["nm"])
         else:
             ctx.open(b["g"][0], b["g"][1], out=b["f"])
 
@@ -233,7 +241,7 @@ class Layer:
                     for key in ("d", "g", "z"):
                         c2[key] = [torch.empty_like(t) for t in b[key]]
                     c2["e"] = torch.empty_like(b["e"])
-                    c2["f"] = self.ctx.open_weight_planes(b["g"][0], b["g"][1]) if self.planes \
+                    c2["f"] = self.ctx.open_weight_planes(b["g"][0], b["g"][1], neuron_major=b["nm"]) if self.planes \
                         else torch.empty_like(b["f"])
                     st["mm"].append(c2)
             st["ew_done"] = [torch.cuda.Event() for _ in self.mm]
@@ -362,10 +370,14 @@ def cpu_baseline(layer, budget_s=20.0):
         # the opened operands as words: E as the GPU wrote it, F from the two masked shares
         # (the GPU path may hold F only as digit planes)
         e, f = host(b["e"]), co.open_(host(b["g"][0]), host(b["g"][1]))
+        if b["nm"]:
+            f = np.ascontiguousarray(f.T)                 # stored one row per neuron
         k_eff, n_eff = e.shape[1], f.shape[1]
         a_sel, b_sel = [], []
         for i in (0, 1):
             a_i, b_i = host(b["a"][i]), host(b["b"][i])
+            if b["nm"]:
+                b_i = np.ascontiguousarray(b_i.T)
             if mm.kind == "somm":
                 a_sel.append(a_i)
                 b_sel.append(co.index_cols(b_i, idx, cfg.bs))
@@ -425,7 +437,7 @@ def config_entry(ctx, name, probes, planes, skinny_forced, steps=10, warmup=3, l
     cfg, wname = parse_workload(name)
     own = layer is None
     if own:
-        layer = Layer(ctx, cfg, rng.BASE_SEED, planes, UNOPENED_FEW_ROWS)
+        layer = Layer(ctx, cfg, rng.BASE_SEED, planes, UNOPENED_FEW_ROWS, NEURON_MAJOR_SOMM)
         timing = run_timed(ctx, layer, steps, warmup)
     ms, gemm_ms, n_timed = timing["ms_per_step"], timing["gemm_ms"], timing["n_timed"]
     roof = roofline_of(layer, wname, timing, skinny_forced, probes)
@@ -767,6 +779,8 @@ def main():
                     help="format of the weight-side operands of the share calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-micro", action="store_true")
+    ap.add_argument("--row-major-weights", action="store_true",
+                    help="store the SOMM weights k x n (kept neurons are column blocks) instead of one row per neuron")
     ap.add_argument("--opened-few-rows", action="store_true",
                     help="decoding workloads: open F into memory first instead of folding the opening into the share kernel")
     ap.add_argument("--per-call", action="store_true",
@@ -781,8 +795,9 @@ def main():
     ap.add_argument("--skinny", type=int, default=0, help="tuning sweep: 1 = matrix cores even for m <= 8")
     ap.add_argument("--skinny-slices", type=int, default=0, help="tuning sweep: contraction slices of the m <= 8 kernel")
     args = ap.parse_args()
-    global UNOPENED_FEW_ROWS
+    global UNOPENED_FEW_ROWS, NEURON_MAJOR_SOMM
     UNOPENED_FEW_ROWS = not args.opened_few_rows
+    NEURON_MAJOR_SOMM = not args.row_major_weights
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (both parties are simulated on it); "
               "run with --gpus 1", file=sys.stderr)
@@ -806,7 +821,7 @@ def main():
     ctx.set_tuning(comet.TUNE_SKINNY, args.skinny)
     ctx.set_tuning(comet.TUNE_SKINNY_SLICES, args.skinny_slices)
     planes = args.weights == "planes"
-    layer = Layer(ctx, cfg, rng.BASE_SEED, planes, UNOPENED_FEW_ROWS)
+    layer = Layer(ctx, cfg, rng.BASE_SEED, planes, UNOPENED_FEW_ROWS, NEURON_MAJOR_SOMM)
     log("workload %s: %s, m=%d d=%d f=%d bs=%d kept blocks %d/%d (n_act=%d), %.2f G ring ops/step, weight "
         "operands as %s" % (wname, cfg.name, cfg.tokens, cfg.d_model, cfg.d_ff, cfg.bs, layer.n_blk, cfg.nb,
                             layer.n_act, layer.ring_ops_per_step / 1e9, "planes" if layer.planes else "words"))
@@ -863,6 +878,10 @@ def main():
                                   else "comet_share_group: gate+up of both parties, then down of both parties",
                    "weight_operands": "digit planes (F opened in that format, B_i packed offline)"
                                       if layer.planes else "words",
+                   "weight_layout": "one row per neuron in both projections (kept neurons are whole rows)"
+                                    if layer.neuron_major else
+                                    "gate / up: d_model x d_ff (kept neurons are column blocks); down: d_ff x d_model",
+                   "few_row_shares": "opening of F folded into the share kernel" if layer.unopened else None,
                    "inputs": "seeded streams of workloads/ (seed %d), drawn on the device" % rng.BASE_SEED,
                    "submission": "hip graph replay" if args.graph else
                                  ("eager, two streams" if args.overlap else "eager")},

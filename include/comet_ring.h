@@ -140,6 +140,15 @@ size_t comet_weight_planes_bytes(int64_t k, int64_t n);
 int comet_open_weight_planes(comet_ctx* ctx, const uint64_t* g_0, const uint64_t* g_1, int64_t k,
                              int64_t n, void* planes);
 
+/* comet_open_weight_planes for operands stored one ROW per column of the matrix
+ * (g_0, g_1: n x k words, row c = column c of the k x n matrix the planes stand
+ * for): the neuron-major layout of the SOMM weights (see
+ * COMET_WEIGHTS_NEURON_MAJOR), in which the kept neurons are gathered as whole
+ * rows (comet_mask_share_gather with COMET_AXIS_ROWS).  The planes are the same,
+ * byte for byte, as those of the row-major call on the transposed operands. */
+int comet_open_weight_planes_neuron_major(comet_ctx* ctx, const uint64_t* g_0, const uint64_t* g_1,
+                                          int64_t k, int64_t n, void* planes);
+
 /* ---- (2) sparsity distribution -> ordered index list -------------------- */
 
 /* mask: n_tok x nb bytes, non-zero = block predicted active for that token

@@ -26,7 +26,7 @@ TUNE_TIMING_STRIDE, TUNE_GROUP = 6, 7
 EXPORTS = [
     "comet_create", "comet_destroy", "comet_set_stream", "comet_last_error", "comet_version",
     "comet_workspace_bytes", "comet_mask_share", "comet_mask_share_gather", "comet_open",
-    "comet_weight_planes_bytes", "comet_open_weight_planes",
+    "comet_weight_planes_bytes", "comet_open_weight_planes", "comet_open_weight_planes_neuron_major",
     "comet_compact_mask", "comet_somm_share", "comet_somm_share_static", "comet_simm_share", "comet_share_group",
     "comet_somm_share_unopened", "comet_simm_share_unopened",
     "comet_components", "comet_somm_share_blocks", "comet_simm_share_masked",
@@ -66,6 +66,7 @@ def load_library() -> ctypes.CDLL:
     lib.comet_weight_planes_bytes.argtypes = [i64, i64]
     lib.comet_weight_planes_bytes.restype = sz
     lib.comet_open_weight_planes.argtypes = [vp, vp, vp, i64, i64, vp]
+    lib.comet_open_weight_planes_neuron_major.argtypes = [vp, vp, vp, i64, i64, vp]
     lib.comet_mask_share_gather.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, i32]
     lib.comet_compact_mask.argtypes = [vp, vp, i64, i64, vp, vp, vp, sz]
     share = [vp, i32, i64, i64, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz]
@@ -229,20 +230,22 @@ class Context:
         self._check(self.lib.comet_open(self.h, _ptr(d_0), _ptr(d_1), _ptr(out), d_0.numel()))
         return out
 
-    def open_weight_planes(self, g_0, g_1=None, out=None) -> WeightPlanes:
-        """F = g_0 + g_1 (or g_0 alone: offline packing of a triple share) as digit planes."""
+    def open_weight_planes(self, g_0, g_1=None, out=None, neuron_major=False) -> WeightPlanes:
+        """F = g_0 + g_1 (or g_0 alone: offline packing of a triple share) as digit planes.
+        ``neuron_major``: the operands are stored one row per column of the matrix (n x k)."""
         _words(g_0, "g_0")
-        k, n = g_0.shape
+        k, n = (g_0.shape[1], g_0.shape[0]) if neuron_major else g_0.shape
         if g_1 is not None:
             _words(g_1, "g_1")
-            _shape(g_1, (k, n), "g_1")
+            _shape(g_1, tuple(g_0.shape), "g_1")
         need = int(self.lib.comet_weight_planes_bytes(k, n))
         if out is None:
             out = torch.empty(max(need, 16), dtype=torch.uint8, device=g_0.device)
         elif out.dtype != torch.uint8 or not out.is_cuda or out.numel() < need:
             raise TypeError("out must be a uint8 tensor on the GPU of at least %d bytes" % need)
         self._sync_stream()
-        self._check(self.lib.comet_open_weight_planes(self.h, _ptr(g_0), _ptr(g_1), k, n, _ptr(out)))
+        call = self.lib.comet_open_weight_planes_neuron_major if neuron_major else self.lib.comet_open_weight_planes
+        self._check(call(self.h, _ptr(g_0), _ptr(g_1), k, n, _ptr(out)))
         return WeightPlanes(out, k, n)
 
     def mask_share_gather(self, w_i, b_i, axis, bs, blk_idx, n_blk_dev, n_blk_cap, out=None):

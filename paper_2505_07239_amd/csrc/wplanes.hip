@@ -59,6 +59,64 @@ __global__ __launch_bounds__(WT) void wpack_kernel(const u64* __restrict__ a, co
     }
 }
 
+// The same planes from operands stored one ROW per column of W (n x k: the neuron-major layout of
+// the SOMM weights, in which the sixteen contraction rows of a unit are 128 consecutive bytes).
+// Loads want the lanes along k, the stores along the columns, so a workgroup passes a tile of 64
+// columns x 64 contraction rows through LDS: coalesced 16-byte loads of both shares, their sum
+// into the tile, then every thread takes the sixteen words of one (column, k-half) from there.
+constexpr int TT = 256;
+constexpr int TPITCH = 33;                       // 16-byte vectors per tile row (32 + 1 of padding)
+__global__ __launch_bounds__(TT) void wpack_t_kernel(const u64* __restrict__ a, const u64* __restrict__ b,
+                                                     u64x2* __restrict__ out, long k, long n) {
+    __shared__ u64x2 tile[64 * TPITCH];
+    const long c0 = (long)blockIdx.x * 64, k0 = (long)blockIdx.y * 64;
+    const long nch = (n + 63) >> 6;
+    const bool vec = (k & 1) == 0;               // rows start on 16-byte boundaries
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int v = i * TT + threadIdx.x;      // vector of the tile: column v / 32, words 2 (v % 32) ..
+        const int c = v >> 5, kv = v & 31;
+        const long col = c0 + c, kk = k0 + 2 * kv;
+        u64x2 w = {0, 0};
+        if (col < n) {
+            const u64* pa = a + col * k + kk;
+            const u64* pb = b ? b + col * k + kk : nullptr;
+            if (vec && kk + 2 <= k) {
+                w = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(pa));
+                if (pb) w += __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(pb));
+            } else {
+                if (kk < k) w.x = pa[0] + (pb ? pb[0] : 0ull);
+                if (kk + 1 < k) w.y = pa[1] + (pb ? pb[1] : 0ull);
+            }
+        }
+        tile[c * TPITCH + kv] = w;
+    }
+    __syncthreads();
+    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;      // column of the chunk, sixteen-row group of the tile
+    const long col = c0 + c;
+    const long r0 = k0 + 16 * q;
+    if (col >= n || r0 >= ((k + 31) >> 5) * 32) return;
+    u64 w[16];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const u64x2 t = tile[c * TPITCH + 8 * q + i];
+        w[2 * i] = t.x; w[2 * i + 1] = t.y;
+    }
+    u64 plane[2][8];
+#pragma unroll
+    for (int o = 0; o < 2; ++o) {
+        u64 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = to_digits(w[8 * o + i]);
+        digits_to_planes(v, plane[o]);
+    }
+    const long s = r0 >> 5, g = (r0 >> 4) & 1;
+    u64x2* dst = out + ((s * nch + (col >> 6)) * 16 + g) * 64 + (col & 63);
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        __builtin_nontemporal_store(u64x2{plane[0][t], plane[1][t]}, dst + t * 128);
+}
+
 }  // namespace
 
 extern "C" {
@@ -68,9 +126,8 @@ size_t comet_weight_planes_bytes(int64_t k, int64_t n) {
     return (size_t)((k + 31) / 32) * 32 * (size_t)((n + 63) / 64) * 64 * 8;
 }
 
-int comet_open_weight_planes(comet_ctx* ctx, const uint64_t* g_0, const uint64_t* g_1, int64_t k, int64_t n,
-                             void* planes) {
-    const char* what = "comet_open_weight_planes";
+static int open_planes(comet_ctx* ctx, const char* what, const uint64_t* g_0, const uint64_t* g_1, int64_t k,
+                       int64_t n, void* planes, bool neuron_major) {
     COMET_CHECK_CTX(ctx);
     if (k < 0 || n < 0) return comet_fail(ctx, COMET_EINVAL, "%s: bad size", what);
     if (k > COMET_DIM_MAX || n > COMET_DIM_MAX || k * n >= (1ll << 31))
@@ -81,6 +138,14 @@ int comet_open_weight_planes(comet_ctx* ctx, const uint64_t* g_0, const uint64_t
         return comet_fail(ctx, COMET_EALIGN, "%s: pointers must be 16-byte aligned", what);
     comet_device_guard guard(ctx);
     if (!guard.ok) return comet_fail(ctx, COMET_EDEVICE, "%s: cannot select device", what);
+    if (neuron_major) {
+        // one workgroup per (chunk of 64 columns, 64 contraction rows), the tiles of a chunk together
+        const dim3 grid((unsigned)((n + 63) / 64), (unsigned)((k + 63) / 64));
+        hipLaunchKernelGGL(wpack_t_kernel, grid, dim3(TT), 0, ctx->stream, (const u64*)g_0, (const u64*)g_1,
+                           (u64x2*)planes, (long)k, (long)n);
+        COMET_LAUNCH_CHECK(ctx, what);
+        return COMET_OK;
+    }
     const long groups = 2 * ((k + 31) / 32);
     const unsigned gx = (unsigned)((n + WT - 1) / WT);
     // one workgroup per (chunk of columns, group of sixteen rows), in dispatch order
@@ -91,6 +156,16 @@ int comet_open_weight_planes(comet_ctx* ctx, const uint64_t* g_0, const uint64_t
                        (const u64*)g_1, (u64x2*)planes, (long)k, (long)n, groups);
     COMET_LAUNCH_CHECK(ctx, what);
     return COMET_OK;
+}
+
+int comet_open_weight_planes(comet_ctx* ctx, const uint64_t* g_0, const uint64_t* g_1, int64_t k, int64_t n,
+                             void* planes) {
+    return open_planes(ctx, "comet_open_weight_planes", g_0, g_1, k, n, planes, false);
+}
+
+int comet_open_weight_planes_neuron_major(comet_ctx* ctx, const uint64_t* g_0, const uint64_t* g_1, int64_t k,
+                                          int64_t n, void* planes) {
+    return open_planes(ctx, "comet_open_weight_planes_neuron_major", g_0, g_1, k, n, planes, true);
 }
 
 }  // extern "C"

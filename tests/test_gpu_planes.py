@@ -83,6 +83,27 @@ def test_plane_bytes_follow_the_documented_format(ctx):
             assert np.array_equal(got.buf.cpu().numpy()[:need][real], want[real])
 
 
+@pytest.mark.parametrize("k,n", [(64, 64), (33, 7), (130, 300), (16, 65), (1, 1), (257, 129), (4096, 96), (31, 200)])
+def test_plane_bytes_from_neuron_major_operands(ctx, k, n):
+    """Operands stored one row per column of the matrix give the planes of the row-major call on
+    their transposes, byte for byte (both shares, one share; odd k takes the word-by-word loads)."""
+    import paper_2505_07239_amd as comet
+    g0, g1 = u64(75, k + n, k, n), u64(76, k + n, k, n)
+    t0, t1 = up(np.ascontiguousarray(g0.T)), up(np.ascontiguousarray(g1.T))
+    say("plane bytes from neuron-major operands k=%d n=%d" % (k, n))
+    need = comet.binding.load_library().comet_weight_planes_bytes(k, n)
+    for pair in ((0, 1), (0,)):
+        want = ctx.open_weight_planes(up(g0), up(g1) if len(pair) == 2 else None)
+        fill = torch.full((max(need, 16),), 0x5A, dtype=torch.uint8, device="cuda")
+        got = ctx.open_weight_planes(t0, t1 if len(pair) == 2 else None, out=fill, neuron_major=True)
+        torch.cuda.synchronize()
+        assert got.shape == (k, n)
+        _, real = planes_by_definition(co.open_(g0, g1) if len(pair) == 2 else g0)
+        assert np.array_equal(got.buf.cpu().numpy()[:need][real], want.buf.cpu().numpy()[:need][real])
+        # the padding of the last chunk is never written
+        assert np.all(got.buf.cpu().numpy()[:need][~real] == 0x5A)
+
+
 def _case(seed, kind, m, k, n, bs, kept, cap_extra=0):
     """Random words for one share call.  SOMM: n = number of neurons (columns of B_i), SIMM: k =
     number of neurons (rows of B_i).  Returns host arrays, index list and the oracle result."""
