@@ -194,10 +194,12 @@ def test_config5_density_sweep(ctx, density):
     _run_projection(ctx, cfg, mm, mask)
 
 
-def _run_grouped(ctx, cfg, mms, mask_np):
+def _run_grouped(ctx, cfg, mms, mask_np, neuron_major=False):
     """bench.py's default step for the projections ``mms`` (one kind, one shape): weight-side
     operands as digit planes, all products of both parties in one ``share_group`` call (the
-    library decides whether that is one launch).  Every output element against the oracle."""
+    library decides whether that is one launch).  Every output element against the oracle.
+    ``neuron_major`` (SOMM): the weights and their triple shares are stored one row per neuron,
+    the kept neurons are gathered as rows and the planes are packed from that layout."""
     import paper_2505_07239_amd as comet
     bs, kind = cfg.bs, mms[0].kind
     idx_np = co.compact_mask(mask_np)
@@ -218,16 +220,23 @@ def _run_grouped(ctx, cfg, mms, mask_np):
         ga, gb = [up(v) for v in a], [up(v) for v in b]
         d, g = [], []
         for i in (0, 1):
-            if kind == "somm":
+            if kind == "somm" and neuron_major:
+                d.append(ctx.mask_share(up(x[i]), ga[i]))
+                g.append(ctx.mask_share_gather(up(np.ascontiguousarray(y[i].T)), up(np.ascontiguousarray(b[i].T)),
+                                               comet.AXIS_ROWS, bs, idx, n_dev, t))
+            elif kind == "somm":
                 d.append(ctx.mask_share(up(x[i]), ga[i]))
                 g.append(ctx.mask_share_gather(up(y[i]), gb[i], comet.AXIS_COLS, bs, idx, n_dev, t))
             else:
                 d.append(ctx.mask_share_gather(up(x[i]), ga[i], comet.AXIS_COLS, bs, idx, n_dev, t))
                 g.append(ctx.mask_share_gather(up(y[i]), gb[i], comet.AXIS_ROWS, bs, idx, n_dev, t))
         e = ctx.open(d[0], d[1])
-        f = ctx.open_weight_planes(g[0], g[1])
+        nm = neuron_major and kind == "somm"
+        f = ctx.open_weight_planes(g[0], g[1], neuron_major=nm)
         for i in (0, 1):
-            members.append((i, e, f, ga[i], ctx.open_weight_planes(gb[i]), up(c[i])))
+            b_pl = ctx.open_weight_planes(up(np.ascontiguousarray(b[i].T)), neuron_major=True) if nm \
+                else ctx.open_weight_planes(gb[i])
+            members.append((i, e, f, ga[i], b_pl, up(c[i])))
         torch.cuda.synchronize()
         del gb, g, d
         # oracle side, in full
@@ -262,6 +271,16 @@ def test_config3_grouped_calls_on_weight_planes(ctx):
     _run_grouped(ctx, cfg, somm, mask)
     say("config 3 grouped: %s" % "+".join(mm.name for mm in simm))
     _run_grouped(ctx, cfg, simm, mask)
+
+
+def test_config3_gate_and_up_from_neuron_major_weights(ctx):
+    """bench.py keeps the gate / up weights one row per neuron: row gather of the kept neurons,
+    planes packed from that layout, the same grouped share call; every output element."""
+    cfg = configs.config(3)
+    mask = configs.token_masks(cfg)
+    somm = [mm for mm in cfg.matmuls if mm.kind == "somm"]
+    say("config 3 grouped, neuron-major weights: %s" % "+".join(mm.name for mm in somm))
+    _run_grouped(ctx, cfg, somm, mask, neuron_major=True)
 
 
 @pytest.mark.parametrize("density", configs.C5_DENSITIES)
