@@ -122,6 +122,63 @@ __device__ __forceinline__ void xpack_body(const GemmParams& p, const int part) 
         return;
     }
     const int kc = p.kind == KIND_SOMM ? p.kc_cap : nblk * p.bs;
+    // Whole tile of 64 rows x 64 contraction words inside the operands: the loads want the lanes
+    // along k (a row piece of 512 bytes per half wavefront), the stores want them along the rows (a
+    // digit group is one run of rows), so the tile passes through LDS in between.
+    {
+        const int kw = blockIdx.x * 64;                        // first word of the workgroup's four groups
+        // (an indexed A_i keeps the direct path: one block lookup per sixteen words there, one per pair here)
+        const bool tiled = !p.tmask && (p.lde & 1) == 0 && (p.lda & 1) == 0 && !p.a_full &&
+                           kw + 64 <= kc;                      // uniform over the workgroup
+        if (tiled) {
+            typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+            constexpr int PITCH = 33;                          // 16-byte vectors per tile row (32 + padding)
+            __shared__ u64x2 tile[64 * PITCH];
+            const int h = part;                                // 0: E, 1: A'
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int v = i * GT + threadIdx.x;            // vector of the tile: row v / 32, words 2 (v % 32) ..
+                const int r = v >> 5, kv = v & 31;
+                const int trow = blockIdx.y * 64 + r, kk = kw + 2 * kv;
+                u64x2 w = {0, 0};
+                if (trow < m_eff) {
+                    u64x2 ev = {0, 0};
+                    if (h == 0 || p.party)                      // party 0's A' is A_i itself
+                        ev = *reinterpret_cast<const u64x2*>(p.E + (size_t)trow * p.lde + kk);
+                    if (h == 0) {
+                        w = ev;
+                    } else {
+                        w = *reinterpret_cast<const u64x2*>(p.A + (size_t)trow * p.lda + kk) + ev;
+                    }
+                }
+                tile[r * PITCH + kv] = w;
+            }
+            __syncthreads();
+            const int r = threadIdx.x & 63, q = threadIdx.x >> 6;
+            const int trow = blockIdx.y * 64 + r;
+            if (trow >= p.mpad) return;                        // (the few-row kernel packs 32 rows)
+            u64 plane[2][8];
+#pragma unroll
+            for (int o = 0; o < 2; ++o) {
+                u64 v[8];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const u64x2 t = tile[r * PITCH + 8 * q + 4 * o + j];
+                    v[2 * j] = to_digits(t.x);
+                    v[2 * j + 1] = to_digits(t.y);
+                }
+                digits_to_planes(v, plane[o]);
+            }
+            const int half16 = blockIdx.x * 4 + q;
+            const int s = half16 >> 1, g = half16 & 1;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                u64x2* dst = reinterpret_cast<u64x2*>(p.xp) + xp_group(h, s, t, g, p.ks_cap) * p.mpad + trow;
+                *dst = u64x2{plane[0][t], plane[1][t]};
+            }
+            return;
+        }
+    }
     const int row = blockIdx.y * 64 + (threadIdx.x >> 2);
     if (row >= p.mpad) return;                                 // (the few-row kernel packs 32 rows)
     const int half16 = blockIdx.x * 4 + (threadIdx.x & 3);     // 16-word group over the half
