@@ -49,9 +49,9 @@ ALL_CONFIGS = ["c1", "c2", "c3", "c4", "c5_d100", "c5_d050", "c5_d025", "c5_d010
 # the copy probe of known size in the same run.  The summaries, with the commands, are the
 # files named here under profiles/.  None until measured for that workload and operand format.
 GEMM_TRAFFIC = {
-    ("c2", "planes", "single"): (13393311, "profiles/bench_c2_kernel_trace_and_hbm_counters.md"),
-    ("c3", "planes", "grouped"): (608364924, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
-    ("c3", "planes", "single"): (197370152, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
+    ("c2", "planes", "single"): (13393313, "profiles/bench_c2_kernel_trace_and_hbm_counters.md"),
+    ("c3", "planes", "grouped"): (611880557, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
+    ("c3", "planes", "single"): (197516269, "profiles/bench_c3_kernel_trace_and_hbm_counters.md"),
     ("c4", "words", "single"): (1456341918, "profiles/bench_c4_kernel_trace_and_hbm_counters.md"),
     ("c5_d100", "planes", "single"): (1549274757, "profiles/bench_c5_d100_kernel_trace_and_hbm_counters.md"),
     ("c5_d050", "planes", "single"): (792771729, "profiles/bench_c5_d050_kernel_trace_and_hbm_counters.md"),
